@@ -1,0 +1,141 @@
+/*
+ * lazyev -- decode-time hot path of LazyEviction (arXiv 2506.15969) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer is marked (host) or (device).  The library owns no device memory:
+ * caches, statistics arrays and the workspace are allocated by the caller (for example as
+ * torch tensors) and must stay valid until lazyev_destroy.  All calls enqueue work on the
+ * stream given at init and return without waiting, except lazyev_stats, which waits for it.
+ * Calls on one context must come from one thread at a time.
+ *
+ * A "unit" is one (layer, sequence, KV head).  Each unit has its own cache of N entries
+ * (N is the same for all units of a layer), its own recurrence statistics and its own
+ * survivor set.  Notation of the paper: B budget, W observation window, alpha activation
+ * threshold, t decode step (1-based), TS timestamp vector, MRI maximum recurrence interval.
+ *
+ * Layouts (row-major, C = lazyev_capacity(cfg) entries per unit):
+ *   k_cache, v_cache   [n_layers][batch][n_kv_heads][C][head_dim]   fp32 or bf16
+ *   ts, mri, pos       [n_layers][batch][n_kv_heads][C]             int32
+ *   q, out             [batch][n_q_heads][head_dim]                 same dtype as the caches
+ *   k_new, v_new       [batch][n_kv_heads][head_dim]
+ *   p_out, p_override  [batch][n_q_heads][C]                        fp32
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ */
+#ifndef LAZYEV_H
+#define LAZYEV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LAZYEV_OK          0
+#define LAZYEV_EINVAL     -1   /* bad shape, null pointer, B <= W, step or layer out of order   */
+#define LAZYEV_ECAPACITY  -2   /* decode_step on a full cache: a due eviction was skipped        */
+#define LAZYEV_EWORKSPACE -3   /* workspace missing or smaller than lazyev_workspace_size        */
+#define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
+
+#define LAZYEV_DTYPE_FP32  0
+#define LAZYEV_DTYPE_BF16  1
+
+#define LAZYEV_SCORE_H1    1   /* use the H1 term of Eq. 3 */
+#define LAZYEV_SCORE_H2    2   /* use the H2 term of Eq. 3 */
+
+/* Largest number of eviction candidates (cache entries outside the last W) per unit that the
+ * selection kernel holds in LDS. */
+#define LAZYEV_MAX_CANDIDATES 8192
+
+typedef struct lazyev_ctx lazyev_ctx;              /* opaque, host memory */
+
+typedef struct {
+  int32_t n_layers, batch, n_q_heads, n_kv_heads;  /* n_q_heads % n_kv_heads == 0, group <= 8 */
+  int32_t head_dim;                                /* 64 or 128                                */
+  int32_t budget, window, prompt_len;              /* B > W >= 1 (Sec. 4: B >> W); P >= 0      */
+  float   alpha;                                   /* activation test is p >= alpha (Alg. 1)   */
+  float   softmax_scale;                           /* 0 selects 1/sqrt(head_dim) (Eq. 4)       */
+  int32_t dtype;                                   /* LAZYEV_DTYPE_*: storage of K, V, q, out  */
+  int32_t score_flags;                             /* LAZYEV_SCORE_* bits (Table 4 ablation)   */
+  void    *k_cache, *v_cache;                      /* (device) see layouts                     */
+  int32_t *ts, *mri, *pos;                         /* (device) see layouts                     */
+  void    *workspace;                              /* (device) scratch, 256-byte aligned       */
+  size_t  workspace_bytes;
+  void    *stream;                                 /* hipStream_t; NULL = the default stream   */
+} lazyev_config;
+
+typedef struct {
+  int32_t  n_layers;            /* in: length of the arrays below                               */
+  int32_t *len;                 /* (host, nullable) out: current N of each layer                 */
+  int32_t *last_step;           /* (host, nullable) out: last decode step seen by each layer     */
+  int64_t *n_evict_events;      /* (host, nullable) out: evictions that fired, per layer         */
+  int64_t *n_evicted;           /* (host, nullable) out: entries removed per unit, summed over
+                                   the layer's events                                           */
+  int64_t *n_activations;       /* (host, nullable) out: (entry, step) pairs with p >= alpha,
+                                   summed over the layer's units                                */
+} lazyev_stats_t;
+
+/* Entries of cache per unit: C = max(prompt_len, budget) + window.  0 if cfg is invalid. */
+int32_t lazyev_capacity(const lazyev_config *cfg /*host*/);
+
+/* Bytes of workspace the configuration needs (split partials, score scratch, gather lists,
+ * counters).  0 if cfg is invalid. */
+size_t lazyev_workspace_size(const lazyev_config *cfg /*host*/);
+
+/* Creates a context.  The caller has already written the prompt's K/V rows to entries
+ * 0..P-1 of every unit.  Enqueues: TS = 0, MRI = 0, pos = i for those entries (the state a
+ * token has "as if last important when prefill ended"; the paper starts MRI at 0, Sec. 4),
+ * and clears the counters.  N = P for every layer.
+ * Errors: EINVAL, EWORKSPACE, EHIP. */
+int lazyev_init(const lazyev_config *cfg /*host*/, lazyev_ctx **out /*host*/);
+
+/* One decode step of one layer (Eq. 4; Alg. 1 tracking loop; Eq. 1):
+ *   appends (k_new, v_new) as entry N with TS = t, MRI = 0, pos = P + t - 1;
+ *   out[h] = softmax(scale * q[h] K^T) V over the N+1 entries of the head's unit;
+ *   an entry is active if any query head of its group has probability >= alpha (fp32 compare);
+ *   active entries get MRI = max(MRI, t - TS), then TS = t.
+ * t must be the layer's previous step + 1 (first step is 1).
+ * p_out (device, nullable): receives the fp32 probabilities the threshold test used, entries
+ *   [0, N+1) of each row.
+ * p_override (device, nullable): probabilities to threshold INSTEAD of the computed ones (the
+ *   attention output is unaffected); lets a checker feed identical weights to two
+ *   implementations.
+ * Errors: EINVAL (order, range, null), ECAPACITY (N == C), EHIP. */
+int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
+                       const void *q /*device*/, const void *k_new /*device*/,
+                       const void *v_new /*device*/, void *out /*device*/,
+                       float *p_out /*device, nullable*/,
+                       const float *p_override /*device, nullable*/);
+
+/* Lagged eviction check after decode step t of a layer (Sec. 4; Eq. 3; Eq. 6; Alg. 1):
+ * does nothing unless t % W == 0 and N > B.  Otherwise every unit scores entries 0..N-W-1
+ * with I = H1 + H2 in binary64, keeps the B-W best (ties: the more recent entry wins) and
+ * the last W, and moves K, V, TS, MRI, pos of the survivors to entries 0..B-1 in their
+ * original order.  N becomes B.
+ * n_evicted (host, nullable): entries removed per unit (N - B, or 0).
+ * t must equal the layer's last decode step.
+ * Errors: EINVAL, EHIP. */
+int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
+
+/* Waits for the stream, then fills the non-null arrays of *out.  Errors: EINVAL, EHIP. */
+int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
+
+/* Score of Eq. 3 for n (t - TS, MRI) pairs, on the device, with the same code the eviction
+ * uses; result as binary64.  For checking the scoring arithmetic in isolation.
+ * Errors: EINVAL, EHIP. */
+int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*device*/,
+                       double *score /*device*/, int64_t n, int32_t score_flags,
+                       void *stream);
+
+/* Tuning knob: cache entries handled by one split block of the attention kernel (a power of
+ * two, 64..256).  Results do not depend on it beyond floating-point summation order.
+ * Errors: EINVAL. */
+int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
+
+void lazyev_destroy(lazyev_ctx *ctx);              /* frees host memory only; NULL is allowed */
+const char *lazyev_strerror(int code);
+int lazyev_last_hip_error(const lazyev_ctx *ctx);  /* hipError_t of the last EHIP, else 0 */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAZYEV_H */

@@ -191,7 +191,8 @@ class OracleUnit:
         p_override [G,N]: attention weights to threshold instead of the computed ones
         (tracking only; `out` always comes from the computed weights).  float32 input is
         compared in float32 against float32(alpha), anything else in fp64.
-        act_override [N] bool: take these activation decisions as given.
+        act_override: [N] bool array of activation decisions to take as given, or a callable
+        (p, act) -> act that sees the oracle's own weights and decisions first.
         """
         assert t == self.t + 1, "decode steps are consecutive"
         self.t = t
@@ -205,7 +206,7 @@ class OracleUnit:
 
         out, p = self.attention(q)
 
-        if act_override is not None:
+        if act_override is not None and not callable(act_override):
             act = np.asarray(act_override, dtype=bool)
         elif p_override is not None:
             pw = np.asarray(p_override)
@@ -213,6 +214,8 @@ class OracleUnit:
             act = (pw.reshape(self.G, -1) >= thr).any(axis=0)                        # R1, R5
         else:
             act = (p >= self.alpha).any(axis=0)                                      # R1, R5, R6
+        if callable(act_override):
+            act = np.asarray(act_override(p, act), dtype=bool)
         assert act.shape == (len(self),)
 
         ts_prev = self.TS.copy()

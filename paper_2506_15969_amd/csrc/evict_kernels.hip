@@ -1,0 +1,251 @@
+// Lagged eviction of one layer (Sec. 4 "MRI-Centric Eviction", Eq. 3, Eq. 6, Alg. 1 of the
+// paper), as two kernels:
+//   select  one block per unit: scores every candidate entry (all but the last W) in binary64,
+//           finds the (B-W)-th largest score with an 8-bit radix select over the score bit
+//           patterns held in LDS, breaks ties in favour of the more recent entry, prefix-scans
+//           the keep flags into destination slots, compacts TS / MRI / pos in place and leaves
+//           the gather list (source entry of every survivor) in the workspace.
+//   move    blocks per (unit, K|V, 128-byte column part): walk the gather list in order and
+//           move the rows whose slot changes; loads of a tile complete before its stores.
+//
+// This file is compiled with floating-point contraction off: the score is a fixed sequence of
+// individually rounded binary64 operations so that it can be reproduced bit for bit elsewhere.
+#include "kernels.h"
+
+namespace lazyev {
+namespace {
+
+constexpr int kSelBlock = 1024;
+constexpr int kSelWaves = kSelBlock / 64;
+constexpr int kMoveBlock = 256;
+
+// 2*sigmoid(-x) = 2/(1+e^x) for x >= 0.  e^x = 2^k * e^r with k = round(x/ln 2) and
+// r = x - k ln 2 taken in two pieces (the high piece of ln 2 has 32 significant bits, so
+// k * kLn2Hi is exact); e^r by the degree-13 Taylor polynomial in Horner form.  Every
+// multiply, add and divide below is a separate round-to-nearest operation.
+__device__ double two_sigmoid_neg(double x) {
+#pragma clang fp contract(off)
+  constexpr double kLog2e = 0x1.71547652b82fep+0;
+  constexpr double kLn2Hi = 0x1.62e42fee00000p-1;
+  constexpr double kLn2Lo = 0x1.a39ef35793c76p-33;
+  constexpr double kCoef[14] = {1.0 / 1.0, 1.0 / 1.0, 1.0 / 2.0, 1.0 / 6.0, 1.0 / 24.0,
+                                1.0 / 120.0, 1.0 / 720.0, 1.0 / 5040.0, 1.0 / 40320.0,
+                                1.0 / 362880.0, 1.0 / 3628800.0, 1.0 / 39916800.0,
+                                1.0 / 479001600.0, 1.0 / 6227020800.0};
+  if (!(x < 700.0)) return 0.0;
+  const double k = floor(x * kLog2e + 0.5);
+  const double r = (x - k * kLn2Hi) - k * kLn2Lo;
+  double p = kCoef[13];
+#pragma unroll
+  for (int n = 12; n >= 0; --n) {
+    p = p * r;
+    p = p + kCoef[n];
+  }
+  const double e = ldexp(p, static_cast<int>(k));
+  return 2.0 / (1.0 + e);
+}
+
+// Eq. 3.  delta_t = t - TS >= 0, mri >= 0.
+__device__ double mri_centric_score(int32_t delta_t, int32_t mri, int32_t flags) {
+#pragma clang fp contract(off)
+  double h1 = 0.0, h2 = 0.0;
+  if (flags & 1) {
+    if (mri > 0) h1 = two_sigmoid_neg(static_cast<double>(delta_t) / static_cast<double>(mri));
+    else h1 = (delta_t == 0) ? 1.0 : 0.0;
+  }
+  if ((flags & 2) && mri > 1) h2 = two_sigmoid_neg(1.0 / (static_cast<double>(mri) - 1.0));
+  return h1 + h2;
+}
+
+__global__ void score_pairs_kernel(const int32_t *dt, const int32_t *mri, double *score,
+                                   int64_t n, int32_t flags) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n) score[i] = mri_centric_score(dt[i], mri[i], flags);
+}
+
+__global__ void init_state_kernel(int32_t *ts, int32_t *mri, int32_t *pos, int64_t total,
+                                  int32_t capacity, int32_t prompt_len) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int32_t slot = static_cast<int32_t>(i % capacity);
+  ts[i] = 0;
+  mri[i] = 0;
+  pos[i] = slot < prompt_len ? slot : -1;
+}
+
+// Exclusive prefix sum of one value per thread over the whole block; `total` is the block sum.
+__device__ unsigned block_exclusive_scan(unsigned v, unsigned *wave_tot, unsigned &total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  unsigned base = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const unsigned x = wave_tot[w];
+    all += x;
+    if (w < wave) base += x;
+  }
+  __syncthreads();
+  total = all;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs a) {
+  extern __shared__ unsigned long long keys[];          // score bit pattern of each candidate
+  __shared__ unsigned hist[256];
+  __shared__ unsigned wave_tot[kSelWaves];
+  __shared__ unsigned sel_bin, sel_rem, sel_cnt;
+
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x;
+  const int n = a.n, n_cand = a.n - a.window, k_keep = a.budget - a.window;
+  int32_t *ts = a.ts + static_cast<size_t>(unit) * a.capacity;
+  int32_t *mri = a.mri + static_cast<size_t>(unit) * a.capacity;
+  int32_t *pos = a.pos + static_cast<size_t>(unit) * a.capacity;
+  int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
+
+  // scores (non-negative doubles order like their bit patterns)
+  for (int i = tid; i < n_cand; i += kSelBlock)
+    keys[i] = static_cast<unsigned long long>(
+        __double_as_longlong(mri_centric_score(a.t - ts[i], mri[i], a.score_flags)));
+  __syncthreads();
+
+  // radix select of the k_keep-th largest key, most significant byte first
+  unsigned long long prefix = 0, mask = 0;
+  unsigned k_rem = static_cast<unsigned>(k_keep);
+  unsigned ties_total = 0;
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_cand; i += kSelBlock) {
+      const unsigned long long key = keys[i];
+      if ((key & mask) == prefix) atomicAdd(&hist[static_cast<unsigned>(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    const unsigned bin = 255u - static_cast<unsigned>(tid);      // descending digit order
+    const unsigned v = tid < 256 ? hist[bin] : 0u;
+    unsigned total;
+    const unsigned above = block_exclusive_scan(v, wave_tot, total);   // keys in larger digits
+    if (tid < 256 && above < k_rem && k_rem <= above + v) {
+      sel_bin = bin;
+      sel_rem = k_rem - above;
+      sel_cnt = v;
+    }
+    __syncthreads();
+    prefix |= static_cast<unsigned long long>(sel_bin) << shift;
+    mask |= 255ull << shift;
+    k_rem = sel_rem;
+    ties_total = sel_cnt;
+    __syncthreads();
+  }
+  // prefix is now the threshold key; k_rem of the ties_total entries equal to it are kept,
+  // the most recent ones (largest slots) first.
+  const unsigned long long thr = prefix;
+  const unsigned drop_ties = ties_total - k_rem;
+
+  unsigned run_def = 0, run_tie = 0;
+  for (int base = 0; base < n; base += kSelBlock) {
+    const int slot = base + tid;
+    const bool valid = slot < n;
+    const bool cand = slot < n_cand;
+    const unsigned long long key = cand ? keys[slot] : 0ull;
+    const bool definite = valid && (!cand || key > thr);
+    const bool tie = cand && key == thr;
+    unsigned total;
+    const unsigned ex = block_exclusive_scan((tie ? 65536u : 0u) | (definite ? 1u : 0u),
+                                             wave_tot, total);
+    const unsigned tie_rank = run_tie + (ex >> 16);
+    const unsigned def_before = run_def + (ex & 0xFFFFu);
+    const bool keep = definite || (tie && tie_rank >= drop_ties);
+    const unsigned kept_ties_before = tie_rank > drop_ties ? tie_rank - drop_ties : 0u;
+    const unsigned dst = def_before + kept_ties_before;
+    int32_t v_ts = 0, v_mri = 0, v_pos = 0;
+    if (keep) { v_ts = ts[slot]; v_mri = mri[slot]; v_pos = pos[slot]; }
+    __syncthreads();                       // every read of this pass precedes its writes
+    if (keep) {
+      ts[dst] = v_ts; mri[dst] = v_mri; pos[dst] = v_pos;
+      src_index[dst] = slot;
+    }
+    run_def += total & 0xFFFFu;
+    run_tie += total >> 16;
+  }
+}
+
+// Moves rows of K (blockIdx.y = 0) or V (1): row j <- row src_index[j], j < budget.
+// Row parts are 128 bytes: 8 lanes of 16 bytes.
+__global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs a, int row_bytes) {
+  constexpr int LPP = 8;                       // lanes per row part
+  constexpr int ROWS = kMoveBlock / LPP;       // rows per block load
+  constexpr int U = 4;
+  const int tid = threadIdx.x;
+  const int part = blockIdx.x, unit = blockIdx.z;
+  char *slab = static_cast<char *>(blockIdx.y == 0 ? a.k_cache : a.v_cache) +
+               static_cast<size_t>(unit) * a.capacity * row_bytes + part * 128 + (tid % LPP) * 16;
+  const int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
+
+  for (int tile = 0; tile < a.budget; tile += ROWS * U) {
+    const int last = min(tile + ROWS * U, a.budget) - 1;
+    if (src_index[last] == last) continue;     // gather list is monotone: nothing moves yet
+    uint4 v[U];
+    bool moved[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = tile + u * ROWS + tid / LPP;
+      moved[u] = false;
+      if (j < a.budget) {
+        const int s = src_index[j];
+        if (s != j) {
+          v[u] = *reinterpret_cast<const uint4 *>(slab + static_cast<size_t>(s) * row_bytes);
+          moved[u] = true;
+        }
+      }
+    }
+    __syncthreads();                           // all loads of the tile have landed
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = tile + u * ROWS + tid / LPP;
+      if (moved[u]) *reinterpret_cast<uint4 *>(slab + static_cast<size_t>(j) * row_bytes) = v[u];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_evict(const EvictArgs &a, hipStream_t stream) {
+  const int n_cand = a.n - a.window;
+  if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
+  const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
+  hipLaunchKernelGGL(evict_select_kernel, dim3(a.units), dim3(kSelBlock), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int row_bytes = a.head_dim * (a.dtype == 0 ? 4 : 2);
+  dim3 grid(row_bytes / 128, 2, a.units);
+  hipLaunchKernelGGL(evict_move_kernel, grid, dim3(kMoveBlock), 0, stream, a, row_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
+                             int32_t capacity, int32_t prompt_len, hipStream_t stream) {
+  const int64_t total = n_units * capacity;
+  const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
+  hipLaunchKernelGGL(init_state_kernel, dim3(blocks), dim3(256), 0, stream, ts, mri, pos, total,
+                     capacity, prompt_len);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_pairs(const int32_t *dt, const int32_t *mri, double *score, int64_t n,
+                              int32_t flags, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const unsigned blocks = static_cast<unsigned>((n + 255) / 256);
+  hipLaunchKernelGGL(score_pairs_kernel, dim3(blocks), dim3(256), 0, stream, dt, mri, score, n,
+                     flags);
+  return hipGetLastError();
+}
+
+}  // namespace lazyev

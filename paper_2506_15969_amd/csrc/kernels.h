@@ -1,0 +1,56 @@
+// Internal launch interface between the host API (lazyev_api.hip) and the kernel files.
+// Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lazyev {
+
+// Workspace carve-up, all offsets 256-byte aligned.  One layer call uses it at a time (calls
+// are ordered by the stream), so nothing here is per layer except the counters.
+struct Workspace {
+  float    *part_acc;     // [units][n_split_max][G][D]  un-normalised partial outputs
+  float    *part_ml;      // [units][n_split_max][2][G]  partial row max, partial row sum
+  float    *p_tilde;      // [batch][n_q_heads][C]       exp(s - partial max) of every entry
+  int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
+  unsigned long long *activations;  // [n_layers]        running activation counts
+};
+
+struct DecodeArgs {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim, group;
+  int32_t capacity;       // C
+  int32_t n_old;          // N before the append; the new entry goes to slot n_old
+  int32_t t, prompt_len;
+  int32_t chunk, n_split; // entries per split block, number of split blocks per unit
+  int32_t n_split_max;    // stride of the partial arrays
+  float   alpha, scale;
+  int32_t dtype;
+  const void *q, *k_new, *v_new;
+  void *out;
+  void *k_cache, *v_cache;          // this layer's slab
+  int32_t *ts, *mri, *pos;          // this layer's slab
+  float *p_out;
+  const float *p_override;
+  Workspace ws;
+  unsigned long long *activation_counter;   // this layer's counter
+};
+
+struct EvictArgs {
+  int32_t units;          // batch * n_kv_heads
+  int32_t head_dim, dtype;
+  int32_t capacity;       // C
+  int32_t n, budget, window, t;
+  int32_t score_flags;
+  void *k_cache, *v_cache;
+  int32_t *ts, *mri, *pos;
+  Workspace ws;
+};
+
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
+hipError_t launch_evict(const EvictArgs &a, hipStream_t stream);
+hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
+                             int32_t capacity, int32_t prompt_len, hipStream_t stream);
+hipError_t launch_score_pairs(const int32_t *dt, const int32_t *mri, double *score, int64_t n,
+                              int32_t flags, hipStream_t stream);
+
+}  // namespace lazyev

@@ -1,0 +1,262 @@
+// Host side of the C ABI declared in include/lazyev.h: argument checks, the host mirror of
+// each layer's cache length (it evolves deterministically: +1 per decode step, back to B at an
+// eviction, so no device read-back is ever needed), workspace carve-up and kernel launches.
+#include "lazyev.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+namespace lazyev {
+int decode_chunk_max();
+int decode_split_max();
+}  // namespace lazyev
+
+using lazyev::Workspace;
+
+struct lazyev_ctx {
+  lazyev_config cfg;
+  int32_t capacity, group, units;
+  int32_t chunk, n_split_max;
+  float scale;
+  hipStream_t stream;
+  Workspace ws;
+  std::vector<int32_t> len, last_step;
+  std::vector<int64_t> n_evict_events, n_evicted;
+  int last_hip_error;
+};
+
+namespace {
+
+constexpr int kMinChunk = 64;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool config_ok(const lazyev_config *c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return false;
+  if (c->n_q_heads % c->n_kv_heads != 0) return false;
+  const int g = c->n_q_heads / c->n_kv_heads;
+  if (g < 1 || g > 8) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->window < 1 || c->budget <= c->window || c->prompt_len < 0) return false;
+  if (c->dtype != LAZYEV_DTYPE_FP32 && c->dtype != LAZYEV_DTYPE_BF16) return false;
+  if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2)) return false;
+  if (!(c->alpha >= 0.0f) || !(c->softmax_scale >= 0.0f)) return false;   // also rejects NaN
+  const long long cap = static_cast<long long>(c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
+  if (cap - c->window > LAZYEV_MAX_CANDIDATES) return false;
+  if (static_cast<long long>(c->batch) * c->n_kv_heads > 65535) return false;   // grid.y / grid.z
+  return true;
+}
+
+int32_t capacity_of(const lazyev_config *c) {
+  return (c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
+}
+
+struct Layout {
+  size_t part_acc, part_ml, p_tilde, src_index, activations, total;
+  int32_t n_split_max;
+};
+
+Layout layout_of(const lazyev_config *c) {
+  Layout l;
+  const size_t cap = capacity_of(c);
+  const size_t units = static_cast<size_t>(c->batch) * c->n_kv_heads;
+  const size_t g = c->n_q_heads / c->n_kv_heads;
+  l.n_split_max = static_cast<int32_t>((cap + kMinChunk - 1) / kMinChunk);
+  size_t off = 0;
+  l.part_acc = off; off = align_up(off + units * l.n_split_max * g * c->head_dim * sizeof(float));
+  l.part_ml = off;  off = align_up(off + units * l.n_split_max * 2 * g * sizeof(float));
+  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * cap * sizeof(float));
+  l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
+  l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * sizeof(unsigned long long));
+  l.total = off;
+  return l;
+}
+
+int fail_hip(lazyev_ctx *ctx, hipError_t e) {
+  ctx->last_hip_error = static_cast<int>(e);
+  return LAZYEV_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t lazyev_capacity(const lazyev_config *cfg) { return config_ok(cfg) ? capacity_of(cfg) : 0; }
+
+size_t lazyev_workspace_size(const lazyev_config *cfg) {
+  return config_ok(cfg) ? layout_of(cfg).total : 0;
+}
+
+int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
+  if (!out) return LAZYEV_EINVAL;
+  *out = nullptr;
+  if (!config_ok(cfg)) return LAZYEV_EINVAL;
+  if (!cfg->k_cache || !cfg->v_cache || !cfg->ts || !cfg->mri || !cfg->pos) return LAZYEV_EINVAL;
+  const Layout l = layout_of(cfg);
+  if (!cfg->workspace || cfg->workspace_bytes < l.total ||
+      reinterpret_cast<uintptr_t>(cfg->workspace) % kAlign != 0)
+    return LAZYEV_EWORKSPACE;
+
+  lazyev_ctx *ctx = new (std::nothrow) lazyev_ctx();
+  if (!ctx) return LAZYEV_EINVAL;
+  ctx->cfg = *cfg;
+  ctx->capacity = capacity_of(cfg);
+  ctx->group = cfg->n_q_heads / cfg->n_kv_heads;
+  ctx->units = cfg->batch * cfg->n_kv_heads;
+  ctx->n_split_max = l.n_split_max;
+  ctx->chunk = 128;
+  while ((ctx->capacity + ctx->chunk - 1) / ctx->chunk > lazyev::decode_split_max()) ctx->chunk *= 2;
+  ctx->scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale
+                                         : 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
+  ctx->stream = static_cast<hipStream_t>(cfg->stream);
+  char *base = static_cast<char *>(cfg->workspace);
+  ctx->ws.part_acc = reinterpret_cast<float *>(base + l.part_acc);
+  ctx->ws.part_ml = reinterpret_cast<float *>(base + l.part_ml);
+  ctx->ws.p_tilde = reinterpret_cast<float *>(base + l.p_tilde);
+  ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
+  ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
+  ctx->len.assign(cfg->n_layers, cfg->prompt_len);
+  ctx->last_step.assign(cfg->n_layers, 0);
+  ctx->n_evict_events.assign(cfg->n_layers, 0);
+  ctx->n_evicted.assign(cfg->n_layers, 0);
+  ctx->last_hip_error = 0;
+  if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
+
+  hipError_t e = hipMemsetAsync(ctx->ws.activations, 0,
+                                static_cast<size_t>(cfg->n_layers) * sizeof(unsigned long long),
+                                ctx->stream);
+  if (e == hipSuccess)
+    e = lazyev::launch_init_state(cfg->ts, cfg->mri, cfg->pos,
+                                  static_cast<int64_t>(cfg->n_layers) * ctx->units, ctx->capacity,
+                                  cfg->prompt_len, ctx->stream);
+  if (e != hipSuccess) { delete ctx; return LAZYEV_EHIP; }
+  *out = ctx;
+  return LAZYEV_OK;
+}
+
+int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk) {
+  if (!ctx || chunk < kMinChunk || chunk > lazyev::decode_chunk_max() || (chunk & (chunk - 1)))
+    return LAZYEV_EINVAL;
+  if ((ctx->capacity + chunk - 1) / chunk > lazyev::decode_split_max()) return LAZYEV_EINVAL;
+  ctx->chunk = chunk;
+  return LAZYEV_OK;
+}
+
+int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q, const void *k_new,
+                       const void *v_new, void *out, float *p_out, const float *p_override) {
+  if (!ctx || !q || !k_new || !v_new || !out) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
+  if (t != ctx->last_step[layer] + 1) return LAZYEV_EINVAL;
+  const int32_t n_old = ctx->len[layer];
+  if (n_old >= ctx->capacity) return LAZYEV_ECAPACITY;
+
+  const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
+  const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
+  lazyev::DecodeArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
+  a.head_dim = c.head_dim; a.group = ctx->group; a.capacity = ctx->capacity;
+  a.n_old = n_old; a.t = t; a.prompt_len = c.prompt_len;
+  a.chunk = ctx->chunk; a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
+  a.n_split_max = ctx->n_split_max;
+  a.alpha = c.alpha; a.scale = ctx->scale; a.dtype = c.dtype;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
+  a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
+  a.v_cache = static_cast<char *>(c.v_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
+  a.ts = c.ts + static_cast<size_t>(layer) * slab;
+  a.mri = c.mri + static_cast<size_t>(layer) * slab;
+  a.pos = c.pos + static_cast<size_t>(layer) * slab;
+  a.p_out = p_out; a.p_override = p_override;
+  a.ws = ctx->ws;
+  a.activation_counter = ctx->ws.activations + layer;
+
+  const hipError_t e = lazyev::launch_decode(a, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  ctx->len[layer] = n_old + 1;
+  ctx->last_step[layer] = t;
+  return LAZYEV_OK;
+}
+
+int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) {
+  if (n_evicted) *n_evicted = 0;
+  if (!ctx) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
+  if (t < 1 || t != ctx->last_step[layer]) return LAZYEV_EINVAL;
+  const int32_t n = ctx->len[layer];
+  if (t % c.window != 0 || n <= c.budget) return LAZYEV_OK;       // not due (Sec. 4)
+
+  const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
+  const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
+  lazyev::EvictArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.units = ctx->units; a.head_dim = c.head_dim; a.dtype = c.dtype; a.capacity = ctx->capacity;
+  a.n = n; a.budget = c.budget; a.window = c.window; a.t = t; a.score_flags = c.score_flags;
+  a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
+  a.v_cache = static_cast<char *>(c.v_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
+  a.ts = c.ts + static_cast<size_t>(layer) * slab;
+  a.mri = c.mri + static_cast<size_t>(layer) * slab;
+  a.pos = c.pos + static_cast<size_t>(layer) * slab;
+  a.ws = ctx->ws;
+  const hipError_t e = lazyev::launch_evict(a, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (n_evicted) *n_evicted = n - c.budget;
+  ctx->n_evict_events[layer] += 1;
+  ctx->n_evicted[layer] += n - c.budget;
+  ctx->len[layer] = c.budget;
+  return LAZYEV_OK;
+}
+
+int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
+  if (!ctx || !out || out->n_layers != ctx->cfg.n_layers) return LAZYEV_EINVAL;
+  const int L = ctx->cfg.n_layers;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (out->n_activations) {
+    std::vector<unsigned long long> tmp(L);
+    e = hipMemcpy(tmp.data(), ctx->ws.activations, L * sizeof(unsigned long long),
+                  hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    for (int i = 0; i < L; ++i) out->n_activations[i] = static_cast<int64_t>(tmp[i]);
+  }
+  for (int i = 0; i < L; ++i) {
+    if (out->len) out->len[i] = ctx->len[i];
+    if (out->last_step) out->last_step[i] = ctx->last_step[i];
+    if (out->n_evict_events) out->n_evict_events[i] = ctx->n_evict_events[i];
+    if (out->n_evicted) out->n_evicted[i] = ctx->n_evicted[i];
+  }
+  return LAZYEV_OK;
+}
+
+int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score, int64_t n,
+                       int32_t score_flags, void *stream) {
+  if (n < 0 || (n > 0 && (!delta_t || !mri || !score))) return LAZYEV_EINVAL;
+  if (score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2)) return LAZYEV_EINVAL;
+  const hipError_t e = lazyev::launch_score_pairs(delta_t, mri, score, n, score_flags,
+                                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;
+}
+
+void lazyev_destroy(lazyev_ctx *ctx) { delete ctx; }
+
+const char *lazyev_strerror(int code) {
+  switch (code) {
+    case LAZYEV_OK: return "ok";
+    case LAZYEV_EINVAL: return "invalid argument (shape, null pointer, budget <= window, step or layer out of order)";
+    case LAZYEV_ECAPACITY: return "cache full: a due eviction was skipped";
+    case LAZYEV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LAZYEV_EHIP: return "HIP runtime error";
+    default: return "unknown lazyev error code";
+  }
+}
+
+int lazyev_last_hip_error(const lazyev_ctx *ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+}  // extern "C"

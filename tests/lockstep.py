@@ -1,0 +1,185 @@
+"""Lock-step driver: the HIP library and the CPU oracle consume the same seeded inputs step by
+step and are compared after every step.  Helper for the GPU parity tests (not collected)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.lazyev_oracle import OracleUnit
+from paper_2506_15969_amd.workload import Workload, WorkloadConfig
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+
+
+def make_engine(binding, cfg: WorkloadConfig, wl: Workload, layers=None, score_flags=3,
+                chunk=None):
+    eng = binding.LazyEviction(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads,
+                               cfg.head_dim, cfg.budget, cfg.window, cfg.prompt_len, cfg.alpha,
+                               dtype=cfg.torch_dtype, score_flags=score_flags)
+    for layer in (range(cfg.n_layers) if layers is None else layers):
+        if cfg.prompt_len:
+            k, v = wl.prompt_kv(layer, device="cuda")
+            eng.load_prompt(layer, k, v)
+    eng.init()
+    if chunk:
+        eng.set_chunk(chunk)
+    return eng
+
+
+def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", score_flags=3,
+                 chunk=None, gen_block=32, check_rows_every=1, log=None):
+    """Runs `steps` decode steps (default: all) of the layers that `units` touch, full batch on
+    the GPU, the listed (layer, seq, kv_head) units in the oracle.
+
+    mode "e2e":       both compute their own weights; decisions may differ only within tol*alpha
+                      of the threshold (counted; the oracle then takes the library's decision).
+    mode "oracle_p":  the oracle's weights, rounded to fp32, are thresholded by both.
+    mode "synthetic": seeded random weights are thresholded by both.
+    Returns a dict of counters.  Raises AssertionError on any mismatch.
+    """
+    wl = Workload(cfg)
+    tol = TOL[cfg.dtype]
+    G, d, C = cfg.group, cfg.head_dim, cfg.capacity
+    steps = cfg.steps if steps is None else steps
+    layers = sorted({u[0] for u in units})
+    eng = make_engine(binding, cfg, wl, layers, score_flags, chunk)
+    dev = eng.device
+    orc = {}
+    for (l, s, h) in units:
+        k, v = wl.prompt_kv(l, seq=[s], kv_head=[h])
+        orc[(l, s, h)] = OracleUnit(k[0, 0].double().numpy(), v[0, 0].double().numpy(), G,
+                                    cfg.budget, cfg.window, cfg.alpha, score_flags=score_flags)
+    out = torch.empty((cfg.batch, cfg.n_q_heads, d), dtype=cfg.torch_dtype, device=dev)
+    p_out = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
+    p_in = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
+    stat = dict(steps=0, decisions=0, near_threshold=0, evictions=0, max_out_err=0.0,
+                max_p_err=0.0, activations=0)
+    rng = np.random.default_rng(cfg.seed + 12345)
+    alpha32 = np.float32(cfg.alpha)
+
+    for t0 in range(1, steps + 1, gen_block):
+        t1 = min(steps + 1, t0 + gen_block)
+        gpu_in = {l: wl.step_inputs(l, t0, t1, device="cuda") for l in layers}
+        cpu_in = {u: wl.step_inputs(u[0], t0, t1, seq=[u[1]], kv_head=[u[2]]) for u in units}
+        for t in range(t0, t1):
+            i = t - t0
+            for l in layers:
+                q, kn, vn = (x[i] for x in gpu_in[l])
+                mine = [u for u in units if u[0] == l]
+                n1 = len(orc[mine[0]]) + 1
+                if mode == "e2e":
+                    eng.decode_step(l, t, q, kn, vn, out, p_out=p_out)
+                    o_gpu = out.float().cpu().numpy().astype(np.float64)
+                    p_gpu = p_out.cpu().numpy()
+                    for u in mine:
+                        _, s, h = u
+                        rows = slice(h * G, (h + 1) * G)
+                        pg = p_gpu[s, rows, :n1]
+                        act_gpu = (pg >= alpha32).any(axis=0)
+
+                        def adopt(p, act, pg=pg, act_gpu=act_gpu):
+                            diff = np.nonzero(act != act_gpu)[0]
+                            for j in diff:
+                                near = np.abs(p[:, j] - cfg.alpha) <= tol * cfg.alpha
+                                assert near.any(), ("decision differs away from the threshold",
+                                                    u, t, j, p[:, j], pg[:, j], cfg.alpha)
+                            stat["near_threshold"] += len(diff)
+                            return act_gpu
+                        cq, ck, cv = (x[i, 0] for x in cpu_in[u])
+                        o, p, act = orc[u].decode_step(t, cq.double().numpy(),
+                                                       ck[0].double().numpy(),
+                                                       cv[0].double().numpy(), act_override=adopt)
+                        _compare_out(o_gpu[s, rows], o, tol, stat, (u, t))
+                        perr = np.abs(pg - p).max() / max(p.max(), 1e-30)
+                        stat["max_p_err"] = max(stat["max_p_err"], float(perr))
+                        assert np.all(np.abs(pg - p) <= tol * np.maximum(p, 1e-6) + 1e-9), (u, t)
+                        stat["decisions"] += n1
+                else:
+                    if mode == "synthetic":
+                        pw = (rng.random((cfg.batch, cfg.n_q_heads, n1), dtype=np.float32) ** 6
+                              * np.float32(12.0 * cfg.alpha))
+                        # a few values exactly at the threshold: the test is inclusive
+                        pw[:, :, rng.integers(0, n1, 3)] = alpha32
+                    else:
+                        pw = np.zeros((cfg.batch, cfg.n_q_heads, n1), dtype=np.float32)
+                    res = {}
+                    if mode == "oracle_p":
+                        for u in mine:
+                            _, s, h = u
+                            cq, ck, cv = (x[i, 0] for x in cpu_in[u])
+                            # decide in fp32 on the oracle's own rounded weights
+                            def from_own(p, act):
+                                return (p.astype(np.float32) >= alpha32).any(axis=0)
+                            o, p, act = orc[u].decode_step(t, cq.double().numpy(),
+                                                           ck[0].double().numpy(),
+                                                           cv[0].double().numpy(),
+                                                           act_override=from_own)
+                            pw[s, h * G:(h + 1) * G] = p.astype(np.float32)
+                            res[u] = o
+                    p_in[:, :, :n1].copy_(torch.from_numpy(pw))
+                    eng.decode_step(l, t, q, kn, vn, out, p_override=p_in)
+                    o_gpu = out.float().cpu().numpy().astype(np.float64)
+                    for u in mine:
+                        _, s, h = u
+                        rows = slice(h * G, (h + 1) * G)
+                        if mode == "synthetic":
+                            cq, ck, cv = (x[i, 0] for x in cpu_in[u])
+                            o, p, act = orc[u].decode_step(t, cq.double().numpy(),
+                                                           ck[0].double().numpy(),
+                                                           cv[0].double().numpy(),
+                                                           p_override=pw[s, rows])
+                        else:
+                            o = res[u]
+                        _compare_out(o_gpu[s, rows], o, tol, stat, (u, t))
+                        stat["decisions"] += n1
+                # recurrence state after the step: exact
+                ts_g = eng.ts[l].cpu().numpy()
+                mri_g = eng.mri[l].cpu().numpy()
+                for u in mine:
+                    _, s, h = u
+                    assert np.array_equal(ts_g[s, h, :n1], orc[u].TS), ("TS", u, t)
+                    assert np.array_equal(mri_g[s, h, :n1], orc[u].MRI), ("MRI", u, t)
+                # lagged eviction
+                n_ev = eng.evict(l, t)
+                gone = {u: orc[u].evict(t) for u in mine}
+                for u in mine:
+                    assert len(gone[u]) == n_ev, ("eviction count", u, t, n_ev, len(gone[u]))
+                if n_ev:
+                    stat["evictions"] += 1
+                    _compare_state(eng, l, mine, orc, t, rows=(stat["evictions"] % check_rows_every == 0))
+            stat["steps"] += 1
+        if log:
+            log("t=%d %s" % (t1 - 1, stat))
+    st = eng.stats()
+    for l in layers:
+        assert st["last_step"][l] == steps and st["len"][l] == len(orc[[u for u in units if u[0] == l][0]])
+    # final full comparison, rows included
+    for l in layers:
+        _compare_state(eng, l, [u for u in units if u[0] == l], orc, steps, rows=True)
+    stat["gpu_stats"] = st
+    stat["oracle_units"] = orc
+    stat["engine"] = eng
+    return stat
+
+
+def _compare_out(o_gpu, o, tol, stat, where):
+    err = np.linalg.norm(o_gpu - o, axis=-1) / np.maximum(np.linalg.norm(o, axis=-1), 1e-30)
+    stat["max_out_err"] = max(stat["max_out_err"], float(err.max()))
+    assert err.max() <= tol, ("attention output", where, err)
+
+
+def _compare_state(eng, l, mine, orc, t, rows):
+    pos_g = eng.pos[l].cpu().numpy()
+    ts_g = eng.ts[l].cpu().numpy()
+    mri_g = eng.mri[l].cpu().numpy()
+    for u in mine:
+        _, s, h = u
+        n = len(orc[u])
+        assert np.array_equal(pos_g[s, h, :n], orc[u].pos), ("survivor set", u, t)
+        assert np.array_equal(ts_g[s, h, :n], orc[u].TS), ("TS after eviction", u, t)
+        assert np.array_equal(mri_g[s, h, :n], orc[u].MRI), ("MRI after eviction", u, t)
+        if rows:
+            kg = eng.k_cache[l, s, h, :n].double().cpu().numpy()
+            vg = eng.v_cache[l, s, h, :n].double().cpu().numpy()
+            assert np.array_equal(kg, orc[u].K), ("K rows", u, t)
+            assert np.array_equal(vg, orc[u].V), ("V rows", u, t)

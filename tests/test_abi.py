@@ -1,0 +1,78 @@
+"""The C-ABI library loads, exports every declared symbol and rejects bad arguments on the host
+(no GPU work is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _good(b):
+    return b.Config(n_layers=2, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, budget=64,
+                    window=8, prompt_len=16, alpha=0.01, softmax_scale=0.0, dtype=b.DTYPE_BF16,
+                    score_flags=3)
+
+
+def test_every_declared_symbol_is_exported(lazyev_lib):
+    header = open(os.path.join(ROOT, "include", "lazyev.h")).read()
+    declared = set(re.findall(r"\b(lazyev_[a-z_]+)\s*\(", header))
+    assert declared == set(lazyev_lib.EXPORTS)
+    for name in declared:
+        assert hasattr(lazyev_lib.lib, name)
+
+
+def test_struct_layout_matches_header(lazyev_lib):
+    # 12 four-byte fields, 6 pointers, a size_t, a pointer
+    assert C.sizeof(lazyev_lib.Config) == 12 * 4 + 8 * 8
+    assert C.sizeof(lazyev_lib.Stats) == 8 + 5 * 8
+
+
+def test_capacity_and_workspace(lazyev_lib):
+    b = lazyev_lib
+    cfg = _good(b)
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 64 + 8
+    assert b.lib.lazyev_workspace_size(C.byref(cfg)) > 0
+    cfg.prompt_len = 100
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 108
+
+
+@pytest.mark.parametrize("field,value", [("n_q_heads", 7), ("head_dim", 96), ("window", 0),
+                                         ("budget", 8), ("dtype", 5), ("score_flags", 8),
+                                         ("n_layers", 0), ("alpha", float("nan")),
+                                         ("n_q_heads", 32), ("prompt_len", -1),
+                                         ("budget", 9000)])
+def test_invalid_configs_are_rejected(lazyev_lib, field, value):
+    b = lazyev_lib
+    cfg = _good(b)
+    setattr(cfg, field, value)
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 0
+    assert b.lib.lazyev_workspace_size(C.byref(cfg)) == 0
+    ctx = C.c_void_p()
+    assert b.lib.lazyev_init(C.byref(cfg), C.byref(ctx)) == b.EINVAL and not ctx
+
+
+def test_init_needs_buffers_and_workspace(lazyev_lib):
+    b = lazyev_lib
+    cfg = _good(b)
+    ctx = C.c_void_p()
+    assert b.lib.lazyev_init(C.byref(cfg), C.byref(ctx)) == b.EINVAL      # null caches
+    for f in ("k_cache", "v_cache", "ts", "mri", "pos"):
+        setattr(cfg, f, 256)
+    assert b.lib.lazyev_init(C.byref(cfg), C.byref(ctx)) == b.EWORKSPACE  # no workspace
+    cfg.workspace, cfg.workspace_bytes = 256, 16
+    assert b.lib.lazyev_init(C.byref(cfg), C.byref(ctx)) == b.EWORKSPACE  # too small
+    assert b.lib.lazyev_init(C.byref(cfg), None) == b.EINVAL
+
+
+def test_null_context_calls(lazyev_lib):
+    b = lazyev_lib
+    assert b.lib.lazyev_decode_step(None, 0, 1, 1, 1, 1, 1, None, None) == b.EINVAL
+    assert b.lib.lazyev_evict(None, 0, 1, None) == b.EINVAL
+    assert b.lib.lazyev_stats(None, None) == b.EINVAL
+    assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL
+    b.lib.lazyev_destroy(None)
+    assert b.lib.lazyev_last_hip_error(None) == 0
+    for code in (0, -1, -2, -3, -4, -99):
+        assert len(b.lib.lazyev_strerror(code)) > 0
