@@ -131,6 +131,16 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
  * Errors: EINVAL. */
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
 
+/* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels
+ * (decode_step, or an evict that is due) record HIP events on the stream before, between and
+ * after their two kernels.  lazyev_profile_read waits for the stream, adds up the elapsed
+ * times of the armed calls since the last read and forgets them:
+ *   index 0 attention split kernel, 1 combine + tracking kernel,
+ *         2 eviction score/select kernel, 3 eviction row-move kernel.
+ * ms_total, launches: (host) arrays of 4.  Errors: EINVAL, EHIP. */
+int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls);
+int lazyev_profile_read(lazyev_ctx *ctx, double ms_total[4], int64_t launches[4]);
+
 void lazyev_destroy(lazyev_ctx *ctx);              /* frees host memory only; NULL is allowed */
 const char *lazyev_strerror(int code);
 int lazyev_last_hip_error(const lazyev_ctx *ctx);  /* hipError_t of the last EHIP, else 0 */

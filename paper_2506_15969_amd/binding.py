@@ -41,6 +41,7 @@ class Stats(C.Structure):
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
            "lazyev_evict", "lazyev_stats", "lazyev_score_pairs", "lazyev_set_chunk",
+           "lazyev_profile_arm", "lazyev_profile_read",
            "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
 
 lib.lazyev_capacity.restype = C.c_int32
@@ -61,6 +62,10 @@ lib.lazyev_score_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64
                                    C.c_void_p]
 lib.lazyev_set_chunk.restype = C.c_int
 lib.lazyev_set_chunk.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_profile_arm.restype = C.c_int
+lib.lazyev_profile_arm.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_profile_read.restype = C.c_int
+lib.lazyev_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.lazyev_destroy.restype = None
 lib.lazyev_destroy.argtypes = [C.c_void_p]
 lib.lazyev_strerror.restype = C.c_char_p
@@ -174,6 +179,16 @@ class LazyEviction:
                                                          else C.c_int64)) for k, v in bufs.items()})
         _check(lib.lazyev_stats(self._ctx, C.byref(st)), "lazyev_stats")
         return {k: list(v) for k, v in bufs.items()}
+
+    def profile_arm(self, n_calls: int):
+        _check(lib.lazyev_profile_arm(self._ctx, n_calls), "lazyev_profile_arm")
+
+    def profile_read(self) -> dict:
+        """{kernel: (total ms, launches)} of the armed calls since the last read."""
+        ms, n = (C.c_double * 4)(), (C.c_int64 * 4)()
+        _check(lib.lazyev_profile_read(self._ctx, ms, n), "lazyev_profile_read")
+        names = ("split", "combine", "select", "move")
+        return {k: (ms[i], n[i]) for i, k in enumerate(names)}
 
     def close(self):
         if self._ctx:

@@ -345,12 +345,14 @@ __global__ __launch_bounds__(kBlock) void decode_combine_kernel(const DecodeArgs
 }
 
 template <typename T, int D, int G>
-hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream) {
+hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
   dim3 grid_s(a.n_split, units);
+  if (ev) hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL((decode_split_kernel<T, D, G>), grid_s, dim3(kBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (ev) hipEventRecord(ev[1], stream);
   const int n1 = a.n_old + 1;
   int n_slice = (n1 + kBlock - 1) / kBlock;
   const int min_slice = (G * D + kBlock - 1) / kBlock;
@@ -358,20 +360,22 @@ hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream) {
   if (n_slice > 64) n_slice = 64;
   dim3 grid_c(n_slice, units);
   hipLaunchKernelGGL((decode_combine_kernel<T, D, G>), grid_c, dim3(kBlock), 0, stream, a);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (ev) hipEventRecord(ev[2], stream);
+  return e;
 }
 
 template <typename T, int D>
-hipError_t launch_group(const DecodeArgs &a, hipStream_t stream) {
+hipError_t launch_group(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   switch (a.group) {
-    case 1: return launch_typed<T, D, 1>(a, stream);
-    case 2: return launch_typed<T, D, 2>(a, stream);
-    case 3: return launch_typed<T, D, 3>(a, stream);
-    case 4: return launch_typed<T, D, 4>(a, stream);
-    case 5: return launch_typed<T, D, 5>(a, stream);
-    case 6: return launch_typed<T, D, 6>(a, stream);
-    case 7: return launch_typed<T, D, 7>(a, stream);
-    case 8: return launch_typed<T, D, 8>(a, stream);
+    case 1: return launch_typed<T, D, 1>(a, stream, ev);
+    case 2: return launch_typed<T, D, 2>(a, stream, ev);
+    case 3: return launch_typed<T, D, 3>(a, stream, ev);
+    case 4: return launch_typed<T, D, 4>(a, stream, ev);
+    case 5: return launch_typed<T, D, 5>(a, stream, ev);
+    case 6: return launch_typed<T, D, 6>(a, stream, ev);
+    case 7: return launch_typed<T, D, 7>(a, stream, ev);
+    case 8: return launch_typed<T, D, 8>(a, stream, ev);
     default: return hipErrorInvalidValue;
   }
 }
@@ -381,16 +385,16 @@ hipError_t launch_group(const DecodeArgs &a, hipStream_t stream) {
 int decode_chunk_max() { return kChunkMax; }
 int decode_split_max() { return kSplitMaxLds; }
 
-hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream) {
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   if (a.chunk <= 0 || a.chunk > kChunkMax || a.n_split > kSplitMaxLds ||
       a.n_split > a.n_split_max || static_cast<long long>(a.n_split) * a.chunk < a.n_old + 1)
     return hipErrorInvalidValue;
   if (a.dtype == 0) {
-    if (a.head_dim == 64) return launch_group<float, 64>(a, stream);
-    if (a.head_dim == 128) return launch_group<float, 128>(a, stream);
+    if (a.head_dim == 64) return launch_group<float, 64>(a, stream, ev);
+    if (a.head_dim == 128) return launch_group<float, 128>(a, stream, ev);
   } else {
-    if (a.head_dim == 64) return launch_group<bf16_t, 64>(a, stream);
-    if (a.head_dim == 128) return launch_group<bf16_t, 128>(a, stream);
+    if (a.head_dim == 64) return launch_group<bf16_t, 64>(a, stream, ev);
+    if (a.head_dim == 128) return launch_group<bf16_t, 128>(a, stream, ev);
   }
   return hipErrorInvalidValue;
 }

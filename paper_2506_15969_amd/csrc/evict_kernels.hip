@@ -217,17 +217,21 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
 
 }  // namespace
 
-hipError_t launch_evict(const EvictArgs &a, hipStream_t stream) {
+hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int n_cand = a.n - a.window;
   if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
+  if (ev) hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL(evict_select_kernel, dim3(a.units), dim3(kSelBlock), lds, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (ev) hipEventRecord(ev[1], stream);
   const int row_bytes = a.head_dim * (a.dtype == 0 ? 4 : 2);
   dim3 grid(row_bytes / 128, 2, a.units);
   hipLaunchKernelGGL(evict_move_kernel, grid, dim3(kMoveBlock), 0, stream, a, row_bytes);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (ev) hipEventRecord(ev[2], stream);
+  return e;
 }
 
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,

@@ -46,8 +46,10 @@ struct EvictArgs {
   Workspace ws;
 };
 
-hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream);
-hipError_t launch_evict(const EvictArgs &a, hipStream_t stream);
+// `ev`, when not null, points at three events recorded before the first kernel, between the two
+// kernels and after the second (per-kernel timing for the profiling aid).
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
+hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
                              int32_t capacity, int32_t prompt_len, hipStream_t stream);
 hipError_t launch_score_pairs(const int32_t *dt, const int32_t *mri, double *score, int64_t n,

@@ -27,6 +27,10 @@ struct lazyev_ctx {
   std::vector<int32_t> len, last_step;
   std::vector<int64_t> n_evict_events, n_evicted;
   int last_hip_error;
+  // profiling aid: event triples of the calls that were armed, kind 0 = decode, 1 = evict
+  int32_t prof_armed;
+  struct Timed { int kind; hipEvent_t ev[3]; };
+  std::vector<Timed> prof;
 };
 
 namespace {
@@ -78,6 +82,27 @@ Layout layout_of(const lazyev_config *c) {
   return l;
 }
 
+// Returns the three events of an armed call (created here), or null when not armed.
+hipEvent_t *arm_events(lazyev_ctx *ctx, int kind) {
+  if (ctx->prof_armed <= 0) return nullptr;
+  lazyev_ctx::Timed t;
+  t.kind = kind;
+  for (int i = 0; i < 3; ++i)
+    if (hipEventCreate(&t.ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) hipEventDestroy(t.ev[j]);
+      return nullptr;
+    }
+  ctx->prof_armed -= 1;
+  ctx->prof.push_back(t);
+  return ctx->prof.back().ev;
+}
+
+void drop_events(lazyev_ctx *ctx) {
+  for (auto &t : ctx->prof)
+    for (int i = 0; i < 3; ++i) hipEventDestroy(t.ev[i]);
+  ctx->prof.clear();
+}
+
 int fail_hip(lazyev_ctx *ctx, hipError_t e) {
   ctx->last_hip_error = static_cast<int>(e);
   return LAZYEV_EHIP;
@@ -126,6 +151,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->n_evict_events.assign(cfg->n_layers, 0);
   ctx->n_evicted.assign(cfg->n_layers, 0);
   ctx->last_hip_error = 0;
+  ctx->prof_armed = 0;
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
 
   hipError_t e = hipMemsetAsync(ctx->ws.activations, 0,
@@ -177,7 +203,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.ws = ctx->ws;
   a.activation_counter = ctx->ws.activations + layer;
 
-  const hipError_t e = lazyev::launch_decode(a, ctx->stream);
+  const hipError_t e = lazyev::launch_decode(a, ctx->stream, arm_events(ctx, 0));
   if (e != hipSuccess) return fail_hip(ctx, e);
   ctx->len[layer] = n_old + 1;
   ctx->last_step[layer] = t;
@@ -205,7 +231,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.mri = c.mri + static_cast<size_t>(layer) * slab;
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
-  const hipError_t e = lazyev::launch_evict(a, ctx->stream);
+  const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));
   if (e != hipSuccess) return fail_hip(ctx, e);
   if (n_evicted) *n_evicted = n - c.budget;
   ctx->n_evict_events[layer] += 1;
@@ -244,7 +270,35 @@ int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score
   return e == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;
 }
 
-void lazyev_destroy(lazyev_ctx *ctx) { delete ctx; }
+int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls) {
+  if (!ctx || n_calls < 0) return LAZYEV_EINVAL;
+  ctx->prof_armed = n_calls;
+  return LAZYEV_OK;
+}
+
+int lazyev_profile_read(lazyev_ctx *ctx, double ms_total[4], int64_t launches[4]) {
+  if (!ctx || !ms_total || !launches) return LAZYEV_EINVAL;
+  for (int i = 0; i < 4; ++i) { ms_total[i] = 0.0; launches[i] = 0; }
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) { drop_events(ctx); return fail_hip(ctx, e); }
+  for (auto &t : ctx->prof) {
+    for (int i = 0; i < 2; ++i) {
+      float ms = 0.f;
+      e = hipEventElapsedTime(&ms, t.ev[i], t.ev[i + 1]);
+      if (e != hipSuccess) { drop_events(ctx); return fail_hip(ctx, e); }
+      ms_total[2 * t.kind + i] += ms;
+      launches[2 * t.kind + i] += 1;
+    }
+  }
+  drop_events(ctx);
+  return LAZYEV_OK;
+}
+
+void lazyev_destroy(lazyev_ctx *ctx) {
+  if (!ctx) return;
+  drop_events(ctx);
+  delete ctx;
+}
 
 const char *lazyev_strerror(int code) {
   switch (code) {
