@@ -126,10 +126,21 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
                        double *score /*device*/, int64_t n, int32_t score_flags,
                        void *stream);
 
-/* Tuning knob: cache entries handled by one split block of the attention kernel (a power of
- * two, 64..256).  Results do not depend on it beyond floating-point summation order.
+/* Tuning knobs for how a unit's cache is split over thread blocks.  Results do not depend on
+ * them beyond floating-point summation order.
+ *   lazyev_set_chunk: entries per block of the vector-ALU attention kernel (a power of two,
+ *     64..256; default 128).
+ *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernel aims for
+ *     (default 512 = two per compute unit); each unit gets round(n_blocks / units) blocks,
+ *     at least one, each owning at most 1024 entries.
  * Errors: EINVAL. */
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
+int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
+
+/* Tuning knob: attention kernel.  1 (default) uses the MFMA kernel where it applies (bf16,
+ * head_dim 128) and the vector-ALU kernel elsewhere; 0 always uses the vector-ALU kernel.
+ * Errors: EINVAL. */
+int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
 
 /* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels
  * (decode_step, or an evict that is due) record HIP events on the stream before, between and
@@ -140,6 +151,15 @@ int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
  * ms_total, launches: (host) arrays of 4.  Errors: EINVAL, EHIP. */
 int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls);
 int lazyev_profile_read(lazyev_ctx *ctx, double ms_total[4], int64_t launches[4]);
+
+/* Plain streaming kernels of known traffic, for the bandwidth a simple kernel reaches on the
+ * same chip and for calibrating hardware byte counters.  lazyev_stream_probe copies `bytes`
+ * (a multiple of 16) from src to dst; lazyev_stream_read_probe only reads src (sink: 4 bytes of
+ * device memory that is practically never written).  n_blocks blocks of 256 threads, grid-stride.
+ * All pointers are device memory.  Asynchronous on `stream`.  Errors: EINVAL, EHIP. */
+int lazyev_stream_probe(void *dst, const void *src, size_t bytes, int32_t n_blocks, void *stream);
+int lazyev_stream_read_probe(const void *src, size_t bytes, int32_t n_blocks, void *sink,
+                             void *stream);
 
 void lazyev_destroy(lazyev_ctx *ctx);              /* frees host memory only; NULL is allowed */
 const char *lazyev_strerror(int code);

@@ -41,7 +41,8 @@ class Stats(C.Structure):
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
            "lazyev_evict", "lazyev_stats", "lazyev_score_pairs", "lazyev_set_chunk",
-           "lazyev_profile_arm", "lazyev_profile_read",
+           "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
+           "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
            "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
 
 lib.lazyev_capacity.restype = C.c_int32
@@ -62,6 +63,14 @@ lib.lazyev_score_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64
                                    C.c_void_p]
 lib.lazyev_set_chunk.restype = C.c_int
 lib.lazyev_set_chunk.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_stream_probe.restype = C.c_int
+lib.lazyev_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+lib.lazyev_stream_read_probe.restype = C.c_int
+lib.lazyev_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+lib.lazyev_set_target_blocks.restype = C.c_int
+lib.lazyev_set_target_blocks.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_set_variant.restype = C.c_int
+lib.lazyev_set_variant.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_profile_arm.restype = C.c_int
 lib.lazyev_profile_arm.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_profile_read.restype = C.c_int
@@ -179,6 +188,12 @@ class LazyEviction:
                                                          else C.c_int64)) for k, v in bufs.items()})
         _check(lib.lazyev_stats(self._ctx, C.byref(st)), "lazyev_stats")
         return {k: list(v) for k, v in bufs.items()}
+
+    def set_target_blocks(self, n_blocks: int):
+        _check(lib.lazyev_set_target_blocks(self._ctx, n_blocks), "lazyev_set_target_blocks")
+
+    def set_variant(self, variant: int):
+        _check(lib.lazyev_set_variant(self._ctx, variant), "lazyev_set_variant")
 
     def profile_arm(self, n_calls: int):
         _check(lib.lazyev_profile_arm(self._ctx, n_calls), "lazyev_profile_arm")

@@ -19,7 +19,8 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
 constexpr int kChunkMax = 256;     // entries per split block (one per thread in the softmax phase)
-constexpr int kSplitMaxLds = 1024; // split partials the combine kernel can weight in LDS
+constexpr int kSliceMax = 64;      // combine blocks per unit (and activation-count slots)
+constexpr int kSplitMaxLds = 512;  // split partials the combine kernel can weight in LDS
 
 typedef unsigned short bf16_t;
 
@@ -172,13 +173,13 @@ __global__ __launch_bounds__(kBlock) void decode_split_kernel(const DecodeArgs a
   __syncthreads();
   {
     float *p_tilde = a.ws.p_tilde +
-                     (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * a.capacity;
+                     (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * a.p_stride;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float e = (tid < n_loc) ? expf(sv[g] - m_loc[g]) : 0.f;
       if (tid < n_loc) {
         s_lds[g][tid] = e;
-        p_tilde[static_cast<size_t>(g) * a.capacity + tok0 + tid] = e;
+        p_tilde[static_cast<size_t>(g) * a.p_stride + tok0 + tid] = e;
       }
       float v = wave_sum(e);
       if (lane == 0) red_lds[wave][g] = v;
@@ -260,88 +261,363 @@ __global__ __launch_bounds__(kBlock) void decode_split_kernel(const DecodeArgs a
 }
 
 // ---------------------------------------------------------------------------------- combine
-template <typename T, int D, int G>
+// One block handles kBlock consecutive entries of one unit and a share of the output row.
+// Every global value a thread needs is requested before the first barrier so that the whole
+// kernel costs about one memory round trip.
+template <typename T, int D>
 __global__ __launch_bounds__(kBlock) void decode_combine_kernel(const DecodeArgs a) {
-  __shared__ float m_s[8], invl_s[8];
-  __shared__ float w_lds[kSplitMaxLds][G];
+  __shared__ float m_s[16], invl_s[16];
   __shared__ unsigned cnt_lds[kWaves];
+  extern __shared__ float dyn_lds[];             // two arrays of [n_split][G]
+  constexpr int GMAX = 8;
+  constexpr int PRE = 24;                        // partial outputs requested before the barrier
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.y, slice = blockIdx.x, n_slice = gridDim.x;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const int G = a.group, n_split = a.n_split;
   const int n1 = a.n_old + 1;
   const float *ml = a.ws.part_ml + static_cast<size_t>(unit) * a.n_split_max * (2 * G);
+  const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
+  const float *p_tilde = a.ws.p_tilde + head0 * a.p_stride;
+  int32_t *ts = a.ts + static_cast<size_t>(unit) * a.capacity;
+  int32_t *mri = a.mri + static_cast<size_t>(unit) * a.capacity;
+  float *w_lds = dyn_lds;                        // partial max, later the weight of the partial
+  float *l_lds = dyn_lds + n_split * G;          // partial sum
 
-  if (wave == 0) {
+  // requests first: this thread's share of the partial outputs ...
+  const int per = (G * D + n_slice - 1) / n_slice;
+  const int e0 = slice * per + tid;
+  const bool has_out = tid < per && e0 < G * D;
+  const float *pa = a.ws.part_acc + static_cast<size_t>(unit) * a.n_split_max * (G * D) + e0;
+  float px[PRE];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float m = -INFINITY;
-      for (int j = lane; j < a.n_split; j += 64) m = fmaxf(m, ml[j * (2 * G) + g]);
-      m = wave_max(m);
-      float l = 0.f;
-      for (int j = lane; j < a.n_split; j += 64)
-        l += ml[j * (2 * G) + G + g] * expf(ml[j * (2 * G) + g] - m);
-      l = wave_sum(l);
-      if (lane == 0) { m_s[g] = m; invl_s[g] = 1.0f / l; }
-    }
+  for (int j = 0; j < PRE; ++j)
+    px[j] = (has_out && j < n_split) ? pa[static_cast<size_t>(j) * (G * D)] : 0.f;
+  // ... this thread's entry ...
+  const int i0 = slice * kBlock + tid;
+  float pt[GMAX];
+  int32_t ts0 = 0, mri0 = 0;
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g)
+    pt[g] = (g < G && i0 < n1) ? p_tilde[static_cast<size_t>(g) * a.p_stride + i0] : 0.f;
+  if (i0 < a.n_old) { ts0 = ts[i0]; mri0 = mri[i0]; }
+  // ... and the partial statistics of the unit
+  for (int i = tid; i < n_split * G; i += kBlock) {
+    const int j = i / G, g = i - j * G;
+    w_lds[i] = ml[j * (2 * G) + g];
+    l_lds[i] = ml[j * (2 * G) + G + g];
   }
   __syncthreads();
-  for (int i = tid; i < a.n_split * G; i += kBlock) {
-    const int j = i / G, g = i % G;
-    w_lds[j][g] = expf(ml[j * (2 * G) + g] - m_s[g]) * invl_s[g];
+  for (int g = wave; g < G; g += kWaves) {
+    float m = -INFINITY;
+    for (int j = lane; j < n_split; j += 64) m = fmaxf(m, w_lds[j * G + g]);
+    m = wave_max(m);
+    float l = 0.f;
+    for (int j = lane; j < n_split; j += 64) l += l_lds[j * G + g] * expf(w_lds[j * G + g] - m);
+    l = wave_sum(l);
+    if (lane == 0) { m_s[g] = m; invl_s[g] = 1.0f / l; }
+  }
+  __syncthreads();
+  for (int i = tid; i < n_split * G; i += kBlock) {
+    const int g = i % G;
+    w_lds[i] = expf(w_lds[i] - m_s[g]) * invl_s[g];
   }
   __syncthreads();
 
-  // output row: out[g][dd] = sum_j w[j][g] * acc_j[g][dd]
-  {
-    const float *pa = a.ws.part_acc + static_cast<size_t>(unit) * a.n_split_max * (G * D);
-    T *out = static_cast<T *>(a.out) +
-             (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * D;
-    for (int e = slice * kBlock + tid; e < G * D; e += n_slice * kBlock) {
+  // output row: out[g][dd] = sum_j w[j][g] * acc_j[g][dd]; the slices share the G*D elements
+  if (has_out) {
+    const int g = e0 / D;
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < PRE; ++j)
+      if (j < n_split) v = fmaf(w_lds[j * G + g], px[j], v);
+    for (int j = PRE; j < n_split; ++j) v = fmaf(w_lds[j * G + g], pa[static_cast<size_t>(j) * (G * D)], v);
+    Elem<T>::store(static_cast<T *>(a.out) + head0 * D + e0, v);
+  }
+  for (int k = tid + kBlock; k < per; k += kBlock) {     // only when G*D > n_slice * kBlock
+    const int e = slice * per + k;
+    if (e < G * D) {
       const int g = e / D;
+      const float *pe = a.ws.part_acc + static_cast<size_t>(unit) * a.n_split_max * (G * D) + e;
       float v = 0.f;
-      for (int j = 0; j < a.n_split; ++j) v = fmaf(w_lds[j][g], pa[static_cast<size_t>(j) * (G * D) + e], v);
-      Elem<T>::store(out + e, v);
+      for (int j = 0; j < n_split; ++j) v = fmaf(w_lds[j * G + g], pe[static_cast<size_t>(j) * (G * D)], v);
+      Elem<T>::store(static_cast<T *>(a.out) + head0 * D + e, v);
     }
   }
 
   // probabilities, activation test (Alg. 1) and Eq. 1 for this block's entries
-  const size_t row0 = (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * a.capacity;
-  const float *p_tilde = a.ws.p_tilde + row0;
-  int32_t *ts = a.ts + static_cast<size_t>(unit) * a.capacity;
-  int32_t *mri = a.mri + static_cast<size_t>(unit) * a.capacity;
   unsigned n_act = 0;
-  for (int i = slice * kBlock + tid; i < n1; i += n_slice * kBlock) {
+  for (int i = i0; i < n1; i += n_slice * kBlock) {
+    if (i != i0) {                               // only when a unit has more than 64 blocks' worth
+#pragma unroll
+      for (int g = 0; g < GMAX; ++g)
+        pt[g] = g < G ? p_tilde[static_cast<size_t>(g) * a.p_stride + i] : 0.f;
+      if (i < a.n_old) { ts0 = ts[i]; mri0 = mri[i]; }
+    }
     const int j = i / a.chunk;
     bool act = false;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float p = p_tilde[static_cast<size_t>(g) * a.capacity + i] * w_lds[j][g];
-      if (a.p_out) a.p_out[row0 + static_cast<size_t>(g) * a.capacity + i] = p;
-      if (a.p_override) p = a.p_override[row0 + static_cast<size_t>(g) * a.capacity + i];
-      act = act || (p >= a.alpha);
+    for (int g = 0; g < GMAX; ++g) {
+      if (g < G) {
+        float p = pt[g] * w_lds[j * G + g];
+        const size_t at = (head0 + g) * a.capacity + i;
+        if (a.p_out) a.p_out[at] = p;
+        if (a.p_override) p = a.p_override[at];
+        act = act || (p >= a.alpha);
+      }
     }
-    if (i == a.n_old) {                       // the appended entry starts here (Sec. 4)
+    if (i == a.n_old) {                          // the appended entry starts here (Sec. 4)
       ts[i] = a.t;
       mri[i] = 0;
       a.pos[static_cast<size_t>(unit) * a.capacity + i] = a.prompt_len + a.t - 1;
     } else if (act) {
-      const int32_t prev = ts[i];
-      const int32_t gap = a.t - prev;
-      if (gap > mri[i]) mri[i] = gap;         // Eq. 1
-      ts[i] = a.t;                            // Alg. 1
+      const int32_t gap = a.t - ts0;
+      if (gap > mri0) mri[i] = gap;              // Eq. 1
+      ts[i] = a.t;                               // Alg. 1
     }
     n_act += act ? 1u : 0u;
   }
-  // activation count of the layer
+  // activation count: every (unit, slice) block owns one slot, so no atomics are needed
   for (int o = 32; o > 0; o >>= 1) n_act += __shfl_xor(n_act, o);
   if (lane == 0) cnt_lds[wave] = n_act;
   __syncthreads();
   if (tid == 0) {
     unsigned total = 0;
     for (int w = 0; w < kWaves; ++w) total += cnt_lds[w];
-    if (total) atomicAdd(a.activation_counter, static_cast<unsigned long long>(total));
+    if (total) a.activation_counter[unit * kSliceMax + slice] += total;
   }
+}
+
+// ------------------------------------------------------------------------------ split, MFMA
+// bf16, head_dim 128.  The G query rows of a unit are padded to the 16 rows of an MFMA tile,
+// which takes the arithmetic off the vector ALU (the vector-ALU kernel above needs about 70
+// wave instructions per cached entry, more than the memory system leaves time for).
+//
+// v_mfma_f32_16x16x32_bf16 operand layout (lane l, c = l % 16, g = l / 16):
+//   A[row c][k = 8g..8g+7]   B[k = 8g..8g+7][col c]   C[row 4g+i][col c], i = 0..3
+//
+// logits   S^T[entry][head] = K[entry][d] * Q^T[d][head]: A = 16 entries x 32 d of K (one
+//          16-byte load per lane), B = Q^T.  A lane ends up with head c and, per 32-entry
+//          tile, the 8 entries {16*st + 4g + i}.
+// output   O[head][d] = P[head][entry] * V[entry][d]: A = P, which is exactly what the lane
+//          already holds (head c, its 8 entries, rounded to bf16); B = V for those same 8
+//          entries and one column per lane, built from eight 16-byte row loads by an in-lane
+//          8x8 transpose (v_perm_b32).  Instruction e produces columns d = 8c + e.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+
+// A block owns `tiles_per_block` consecutive 32-entry tiles of one unit; its four waves take
+// them round-robin, MAX_IT tiles per wave at most.  Two software-pipelined passes keep row
+// loads in flight while the previous tile is being multiplied: K tiles -> logits (kept in
+// registers), block-wide max, then V tiles -> exp, p_tilde store, output product.
+template <int MAX_IT>
+__global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeArgs a) {
+  constexpr int D = 128, KC = D / 32, EV = 8;
+  __shared__ float red_lds[kWaves][16];
+  __shared__ float acc_lds[kWaves][8 * D];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int unit = blockIdx.y, split = blockIdx.x;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const int G = a.group;
+  const int n_old = a.n_old, n1 = a.n_old + 1;
+  const int tpb = a.chunk >> 5;
+  const int n_tiles = (n1 + 31) >> 5;
+  const int tile0 = split * tpb;
+  const int tile1 = min(n_tiles, tile0 + tpb);
+
+  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
+  const bf16_t *vc = static_cast<const bf16_t *>(a.v_cache) + static_cast<size_t>(unit) * a.capacity * D;
+  const bf16_t *k_new = static_cast<const bf16_t *>(a.k_new) + static_cast<size_t>(unit) * D;
+  const bf16_t *v_new = static_cast<const bf16_t *>(a.v_new) + static_cast<size_t>(unit) * D;
+
+  if ((n_old >> 5) >= tile0 && (n_old >> 5) < tile1) {      // appended row goes to slot N
+    if (tid < 16) {
+      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(kc) + static_cast<size_t>(n_old) * D)[tid] =
+          reinterpret_cast<const uint4 *>(k_new)[tid];
+    } else if (tid >= 64 && tid < 80) {
+      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[tid - 64] =
+          reinterpret_cast<const uint4 *>(v_new)[tid - 64];
+    }
+  }
+
+  // B operand of the logits: Q^T, head c (zero rows beyond the group)
+  u32x4_t qb[KC];
+  {
+    const bf16_t *q = static_cast<const bf16_t *>(a.q) +
+                      (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * D;
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      qb[kk] = u32x4_t{0, 0, 0, 0};
+      if (c < G) qb[kk] = *reinterpret_cast<const u32x4_t *>(q + c * D + kk * 32 + g * 8);
+    }
+  }
+
+  // rows past the end are clamped to the appended row (and masked later)
+  auto load_k = [&](u32x4_t (&dst)[2][KC], int tile) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const int row = min(tile * 32 + st * 16 + c, n_old);
+      const bf16_t *src = (row == n_old) ? k_new : kc + static_cast<size_t>(row) * D;
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk)
+        dst[st][kk] = *reinterpret_cast<const u32x4_t *>(src + kk * 32 + g * 8);
+    }
+  };
+  auto load_v = [&](u32x4_t (&dst)[EV], int tile) {
+#pragma unroll
+    for (int jp = 0; jp < EV; ++jp) {
+      const int row = min(tile * 32 + (jp >> 2) * 16 + 4 * g + (jp & 3), n_old);
+      const bf16_t *src = (row == n_old) ? v_new : vc + static_cast<size_t>(row) * D;
+      dst[jp] = *reinterpret_cast<const u32x4_t *>(src + c * 8);
+    }
+  };
+
+  // ---- pass 1: logits of head c for this lane's entries {32*tile + 16*st + 4g + i}
+  float sv[MAX_IT][2][4];
+  float mx = -INFINITY;
+  {
+    u32x4_t kbuf[2][2][KC];
+    if (tile0 + wave < tile1) load_k(kbuf[0], tile0 + wave);
+#pragma unroll
+    for (int it = 0; it < MAX_IT; ++it) {
+      const int tile = tile0 + wave + 4 * it;
+      if (it + 1 < MAX_IT && tile + 4 < tile1) load_k(kbuf[(it + 1) & 1], tile + 4);
+      if (tile < tile1) {
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KC; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8_t, kbuf[it & 1][st][kk]),
+                __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int tok = tile * 32 + st * 16 + 4 * g + i;
+            const float v = tok < n1 ? acc[i] * a.scale : -INFINITY;
+            sv[it][st][i] = v;
+            mx = fmaxf(mx, v);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sv[it][st][i] = -INFINITY;
+      }
+    }
+  }
+
+  // ---- pass 2, with its first V tile requested before the block-wide max is known
+  u32x4_t vbuf[2][EV];
+  if (tile0 + wave < tile1) load_v(vbuf[0], tile0 + wave);
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  if (g == 0) red_lds[wave][c] = mx;
+  __syncthreads();
+  float m_loc = red_lds[0][c];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) m_loc = fmaxf(m_loc, red_lds[w][c]);
+  __syncthreads();
+
+  float lsum = 0.f;
+  f32x4_t o[EV];
+#pragma unroll
+  for (int e = 0; e < EV; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float *p_tilde = a.ws.p_tilde +
+                   (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G + c) * a.p_stride;
+#pragma unroll
+  for (int it = 0; it < MAX_IT; ++it) {
+    const int tile = tile0 + wave + 4 * it;
+    if (it + 1 < MAX_IT && tile + 4 < tile1) load_v(vbuf[(it + 1) & 1], tile + 4);
+    if (tile < tile1) {
+      // exp(s - local max): fp32 for the tracking, rounded to bf16 for the output product
+      bf16x8_t pa;
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const int tokb = tile * 32 + st * 16 + 4 * g;
+        float e[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          e[i] = __expf(sv[it][st][i] - m_loc);
+          lsum += e[i];
+          pa[st * 4 + i] = static_cast<__bf16>(e[i]);
+        }
+        if (c < G) {
+          if (tokb + 4 <= n1) {
+            *reinterpret_cast<float4 *>(p_tilde + tokb) = make_float4(e[0], e[1], e[2], e[3]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (tokb + i < n1) p_tilde[tokb + i] = e[i];
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < EV; ++e) {
+        u32x4_t vb;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          vb[w] = __builtin_amdgcn_perm(vbuf[it & 1][2 * w + 1][e >> 1], vbuf[it & 1][2 * w][e >> 1],
+                                        (e & 1) ? 0x07060302u : 0x05040100u);
+        o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8_t, vb), o[e], 0, 0, 0);
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 16);
+  lsum += __shfl_xor(lsum, 32);
+  if (g == 0) red_lds[wave][c] = lsum;
+
+  // o[e][i] = O[head 4g+i][d = 8c+e]: add up the four waves, store the block's partial
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int head = 4 * g + i;
+    if (head < G) {
+      float *dst = &acc_lds[wave][head * D + 8 * c];
+      *reinterpret_cast<float4 *>(dst) = make_float4(o[0][i], o[1][i], o[2][i], o[3][i]);
+      *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][i], o[5][i], o[6][i], o[7][i]);
+    }
+  }
+  __syncthreads();
+  const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
+  float *pacc = a.ws.part_acc + part * (G * D);
+  for (int i = tid; i < G * D; i += kBlock) {
+    float v = acc_lds[0][i];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) v += acc_lds[w][i];
+    pacc[i] = v;
+  }
+  if (tid < G) {                               // wave 0, g == 0, c == tid: this lane's head
+    float l_loc = red_lds[0][tid];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) l_loc += red_lds[w][tid];
+    float *ml = a.ws.part_ml + part * (2 * G);
+    ml[tid] = m_loc;
+    ml[G + tid] = l_loc;
+  }
+}
+
+template <int MAX_IT>
+hipError_t launch_mfma(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
+  const int units = a.batch * a.n_kv_heads;
+  dim3 grid_s(a.n_split, units);
+  if (ev) hipEventRecord(ev[0], stream);
+  hipLaunchKernelGGL((decode_split_mfma_kernel<MAX_IT>), grid_s, dim3(kBlock), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (ev) hipEventRecord(ev[1], stream);
+  int n_slice = (a.n_old + 1 + kBlock - 1) / kBlock;
+  if (n_slice > kSliceMax) n_slice = kSliceMax;
+  dim3 grid_c(n_slice, units);
+  hipLaunchKernelGGL((decode_combine_kernel<bf16_t, 128>), grid_c, dim3(kBlock),
+                     2 * a.n_split * a.group * sizeof(float), stream, a);
+  e = hipGetLastError();
+  if (ev) hipEventRecord(ev[2], stream);
+  return e;
 }
 
 template <typename T, int D, int G>
@@ -355,11 +631,10 @@ hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev)
   if (ev) hipEventRecord(ev[1], stream);
   const int n1 = a.n_old + 1;
   int n_slice = (n1 + kBlock - 1) / kBlock;
-  const int min_slice = (G * D + kBlock - 1) / kBlock;
-  if (n_slice < min_slice) n_slice = min_slice;
-  if (n_slice > 64) n_slice = 64;
+  if (n_slice > kSliceMax) n_slice = kSliceMax;
   dim3 grid_c(n_slice, units);
-  hipLaunchKernelGGL((decode_combine_kernel<T, D, G>), grid_c, dim3(kBlock), 0, stream, a);
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), grid_c, dim3(kBlock),
+                     2 * a.n_split * a.group * sizeof(float), stream, a);
   e = hipGetLastError();
   if (ev) hipEventRecord(ev[2], stream);
   return e;
@@ -384,11 +659,19 @@ hipError_t launch_group(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev)
 
 int decode_chunk_max() { return kChunkMax; }
 int decode_split_max() { return kSplitMaxLds; }
+int decode_slice_max() { return kSliceMax; }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
-  if (a.chunk <= 0 || a.chunk > kChunkMax || a.n_split > kSplitMaxLds ||
+  const bool mfma = a.variant == 1 && a.dtype == 1 && a.head_dim == 128;
+  if (a.chunk <= 0 || (!mfma && a.chunk > kChunkMax) || a.n_split > kSplitMaxLds ||
       a.n_split > a.n_split_max || static_cast<long long>(a.n_split) * a.chunk < a.n_old + 1)
     return hipErrorInvalidValue;
+  if (a.variant == 1 && a.dtype == 1 && a.head_dim == 128) {
+    // chunk is a multiple of 32 here; a wave takes every fourth tile of the block
+    const int its = ((a.chunk >> 5) + kWaves - 1) / kWaves;
+    if (a.chunk % 32 != 0 || its > 8) return hipErrorInvalidValue;
+    return its <= 4 ? launch_mfma<4>(a, stream, ev) : launch_mfma<8>(a, stream, ev);
+  }
   if (a.dtype == 0) {
     if (a.head_dim == 64) return launch_group<float, 64>(a, stream, ev);
     if (a.head_dim == 128) return launch_group<float, 128>(a, stream, ev);

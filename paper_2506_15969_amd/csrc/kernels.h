@@ -11,9 +11,9 @@ namespace lazyev {
 struct Workspace {
   float    *part_acc;     // [units][n_split_max][G][D]  un-normalised partial outputs
   float    *part_ml;      // [units][n_split_max][2][G]  partial row max, partial row sum
-  float    *p_tilde;      // [batch][n_q_heads][C]       exp(s - partial max) of every entry
+  float    *p_tilde;      // [batch][n_q_heads][p_stride] exp(s - partial max) of every entry
   int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
-  unsigned long long *activations;  // [n_layers]        running activation counts
+  unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
 };
 
 struct DecodeArgs {
@@ -23,6 +23,8 @@ struct DecodeArgs {
   int32_t t, prompt_len;
   int32_t chunk, n_split; // entries per split block, number of split blocks per unit
   int32_t n_split_max;    // stride of the partial arrays
+  int32_t p_stride;       // row stride of p_tilde (C rounded up to a multiple of 4)
+  int32_t variant;        // attention kernel: 0 vector ALU, 1 MFMA (bf16, head_dim 128)
   float   alpha, scale;
   int32_t dtype;
   const void *q, *k_new, *v_new;
@@ -32,7 +34,7 @@ struct DecodeArgs {
   float *p_out;
   const float *p_override;
   Workspace ws;
-  unsigned long long *activation_counter;   // this layer's counter
+  unsigned long long *activation_counter;   // this layer's [units][slice_max] counters
 };
 
 struct EvictArgs {

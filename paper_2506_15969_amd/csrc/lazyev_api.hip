@@ -13,6 +13,7 @@
 namespace lazyev {
 int decode_chunk_max();
 int decode_split_max();
+int decode_slice_max();
 }  // namespace lazyev
 
 using lazyev::Workspace;
@@ -20,7 +21,7 @@ using lazyev::Workspace;
 struct lazyev_ctx {
   lazyev_config cfg;
   int32_t capacity, group, units;
-  int32_t chunk, n_split_max;
+  int32_t chunk, n_split_max, variant, target_blocks;
   float scale;
   hipStream_t stream;
   Workspace ws;
@@ -36,6 +37,7 @@ struct lazyev_ctx {
 namespace {
 
 constexpr int kMinChunk = 64;
+constexpr int kTile = 32;            // entries per MFMA tile; finest split granularity
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -71,13 +73,13 @@ Layout layout_of(const lazyev_config *c) {
   const size_t cap = capacity_of(c);
   const size_t units = static_cast<size_t>(c->batch) * c->n_kv_heads;
   const size_t g = c->n_q_heads / c->n_kv_heads;
-  l.n_split_max = static_cast<int32_t>((cap + kMinChunk - 1) / kMinChunk);
+  l.n_split_max = static_cast<int32_t>((cap + kTile - 1) / kTile);
   size_t off = 0;
   l.part_acc = off; off = align_up(off + units * l.n_split_max * g * c->head_dim * sizeof(float));
   l.part_ml = off;  off = align_up(off + units * l.n_split_max * 2 * g * sizeof(float));
-  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * cap * sizeof(float));
+  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * ((cap + 3) / 4 * 4) * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
-  l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * sizeof(unsigned long long));
+  l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.total = off;
   return l;
 }
@@ -136,6 +138,8 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->units = cfg->batch * cfg->n_kv_heads;
   ctx->n_split_max = l.n_split_max;
   ctx->chunk = 128;
+  ctx->variant = 1;
+  ctx->target_blocks = 512;          // two blocks per compute unit
   while ((ctx->capacity + ctx->chunk - 1) / ctx->chunk > lazyev::decode_split_max()) ctx->chunk *= 2;
   ctx->scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale
                                          : 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
@@ -155,7 +159,8 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
 
   hipError_t e = hipMemsetAsync(ctx->ws.activations, 0,
-                                static_cast<size_t>(cfg->n_layers) * sizeof(unsigned long long),
+                                static_cast<size_t>(cfg->n_layers) * ctx->units *
+                                    lazyev::decode_slice_max() * sizeof(unsigned long long),
                                 ctx->stream);
   if (e == hipSuccess)
     e = lazyev::launch_init_state(cfg->ts, cfg->mri, cfg->pos,
@@ -171,6 +176,18 @@ int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk) {
     return LAZYEV_EINVAL;
   if ((ctx->capacity + chunk - 1) / chunk > lazyev::decode_split_max()) return LAZYEV_EINVAL;
   ctx->chunk = chunk;
+  return LAZYEV_OK;
+}
+
+int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
+  if (!ctx || n_blocks < 1) return LAZYEV_EINVAL;
+  ctx->target_blocks = n_blocks;
+  return LAZYEV_OK;
+}
+
+int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant) {
+  if (!ctx || variant < 0 || variant > 1) return LAZYEV_EINVAL;
+  ctx->variant = variant;
   return LAZYEV_OK;
 }
 
@@ -190,8 +207,25 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
   a.head_dim = c.head_dim; a.group = ctx->group; a.capacity = ctx->capacity;
   a.n_old = n_old; a.t = t; a.prompt_len = c.prompt_len;
-  a.chunk = ctx->chunk; a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
+  if (ctx->variant == 1 && c.dtype == LAZYEV_DTYPE_BF16 && c.head_dim == 128) {
+    // MFMA kernel: blocks own whole 32-entry tiles, spread evenly, at most 32 tiles each
+    const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
+    int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
+    if (n_split < 1) n_split = 1;
+    if (n_split > n_tiles) n_split = n_tiles;
+    int tpb = (n_tiles + n_split - 1) / n_split;
+    const int tpb_min = (n_tiles + lazyev::decode_split_max() - 1) / lazyev::decode_split_max();
+    if (tpb < tpb_min) tpb = tpb_min;
+    if (tpb > 32) tpb = 32;
+    a.chunk = tpb * kTile;
+    a.n_split = (n_tiles + tpb - 1) / tpb;
+  } else {
+    a.chunk = ctx->chunk;
+    a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
+  }
   a.n_split_max = ctx->n_split_max;
+  a.p_stride = (ctx->capacity + 3) / 4 * 4;
+  a.variant = ctx->variant;
   a.alpha = c.alpha; a.scale = ctx->scale; a.dtype = c.dtype;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
   a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
@@ -201,7 +235,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.p_out = p_out; a.p_override = p_override;
   a.ws = ctx->ws;
-  a.activation_counter = ctx->ws.activations + layer;
+  a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
 
   const hipError_t e = lazyev::launch_decode(a, ctx->stream, arm_events(ctx, 0));
   if (e != hipSuccess) return fail_hip(ctx, e);
@@ -246,11 +280,16 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
   if (out->n_activations) {
-    std::vector<unsigned long long> tmp(L);
-    e = hipMemcpy(tmp.data(), ctx->ws.activations, L * sizeof(unsigned long long),
+    const size_t per_layer = static_cast<size_t>(ctx->units) * lazyev::decode_slice_max();
+    std::vector<unsigned long long> tmp(per_layer * L);
+    e = hipMemcpy(tmp.data(), ctx->ws.activations, tmp.size() * sizeof(unsigned long long),
                   hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail_hip(ctx, e);
-    for (int i = 0; i < L; ++i) out->n_activations[i] = static_cast<int64_t>(tmp[i]);
+    for (int i = 0; i < L; ++i) {
+      unsigned long long sum = 0;
+      for (size_t k = 0; k < per_layer; ++k) sum += tmp[i * per_layer + k];
+      out->n_activations[i] = static_cast<int64_t>(sum);
+    }
   }
   for (int i = 0; i < L; ++i) {
     if (out->len) out->len[i] = ctx->len[i];

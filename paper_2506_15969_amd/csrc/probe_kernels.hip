@@ -1,0 +1,56 @@
+// Plain streaming kernels of known traffic: the denominators the decode path is compared with
+// (what a simple read or copy achieves on the same chip) and the calibration of hardware byte
+// counters.  Not on the decode path.
+#include "lazyev.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+// Every lane reads 16 bytes per step, consecutive lanes consecutive addresses; grid-stride.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src, size_t n_vec,
+                                                          unsigned *sink) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  unsigned acc = 0;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n_vec; i += stride) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (acc == 0x9E3779B9u) sink[0] = acc;        // practically never: keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *dst, const uint4 *src, size_t n_vec) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" int lazyev_stream_probe(void *dst, const void *src, size_t bytes, int32_t n_blocks,
+                                   void *stream) {
+  if (!src || bytes == 0 || bytes % 16 != 0 || n_blocks < 1 || !dst) return LAZYEV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dst == src) return LAZYEV_EINVAL;
+  hipLaunchKernelGGL(stream_copy_kernel, dim3(n_blocks), dim3(256), 0, s, static_cast<uint4 *>(dst),
+                     static_cast<const uint4 *>(src), bytes / 16);
+  return hipGetLastError() == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;
+}
+
+extern "C" int lazyev_stream_read_probe(const void *src, size_t bytes, int32_t n_blocks,
+                                        void *sink, void *stream) {
+  if (!src || !sink || bytes == 0 || bytes % 16 != 0 || n_blocks < 1) return LAZYEV_EINVAL;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(n_blocks), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4 *>(src), bytes / 16,
+                     static_cast<unsigned *>(sink));
+  return hipGetLastError() == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;
+}

@@ -12,7 +12,7 @@ TOL = {"fp32": 1e-5, "bf16": 2e-2}
 
 
 def make_engine(binding, cfg: WorkloadConfig, wl: Workload, layers=None, score_flags=3,
-                chunk=None):
+                chunk=None, variant=None, target_blocks=None):
     eng = binding.LazyEviction(cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads,
                                cfg.head_dim, cfg.budget, cfg.window, cfg.prompt_len, cfg.alpha,
                                dtype=cfg.torch_dtype, score_flags=score_flags)
@@ -23,11 +23,16 @@ def make_engine(binding, cfg: WorkloadConfig, wl: Workload, layers=None, score_f
     eng.init()
     if chunk:
         eng.set_chunk(chunk)
+    if variant is not None:
+        eng.set_variant(variant)
+    if target_blocks:
+        eng.set_target_blocks(target_blocks)
     return eng
 
 
 def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", score_flags=3,
-                 chunk=None, gen_block=32, check_rows_every=1, log=None):
+                 chunk=None, variant=None, target_blocks=None, gen_block=32,
+                 check_rows_every=1, log=None):
     """Runs `steps` decode steps (default: all) of the layers that `units` touch, full batch on
     the GPU, the listed (layer, seq, kv_head) units in the oracle.
 
@@ -42,7 +47,7 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
     G, d, C = cfg.group, cfg.head_dim, cfg.capacity
     steps = cfg.steps if steps is None else steps
     layers = sorted({u[0] for u in units})
-    eng = make_engine(binding, cfg, wl, layers, score_flags, chunk)
+    eng = make_engine(binding, cfg, wl, layers, score_flags, chunk, variant, target_blocks)
     dev = eng.device
     orc = {}
     for (l, s, h) in units:

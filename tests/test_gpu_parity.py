@@ -44,15 +44,20 @@ def test_cfg1_fp32_every_unit_every_step(lazyev_lib, mode):
     assert stat["gpu_stats"]["n_evicted"][0] == 28 * 16
 
 
-@pytest.mark.parametrize("mode,chunk", [("e2e", 64), ("e2e", 128), ("oracle_p", 256),
-                                        ("synthetic", 64)])
-def test_cfg2_shapes_scaled_down(lazyev_lib, mode, chunk):
-    """bf16, 28/4 heads, d=128; cache 160+32 entries: several split blocks and a ragged tail."""
+@pytest.mark.parametrize("mode,variant,knob", [("e2e", 1, 8), ("e2e", 1, 16), ("e2e", 1, 56),
+                                               ("e2e", 1, 1000), ("e2e", 0, 128), ("e2e", 0, 64),
+                                               ("oracle_p", 1, 24), ("synthetic", 1, 40),
+                                               ("synthetic", 0, 256)])
+def test_cfg2_shapes_scaled_down(lazyev_lib, mode, variant, knob):
+    """bf16, 28/4 heads, d=128; cache up to 170+32 entries (7 tiles of 32, ragged tail).
+    variant 1 is the MFMA kernel, `knob` its target block count (8 units: 1, 2, 7 blocks per
+    unit); variant 0 is the vector-ALU kernel, `knob` its chunk."""
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=100, steps=330, budget=170, window=32,
                                  interval_lo=20, interval_hi=120)
-    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode=mode, chunk=chunk)
-    _report("cfg2-small/%s/chunk%d" % (mode, chunk), stat)
+    kw = dict(target_blocks=knob) if variant == 1 else dict(chunk=knob)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode=mode, variant=variant, **kw)
+    _report("cfg2-small/%s/variant%d/knob%d" % (mode, variant, knob), stat)
     assert stat["evictions"] == len([t for t in range(32, 331, 32) if 100 + t > 170])
 
 
@@ -98,7 +103,7 @@ def test_budget_at_least_sequence_is_full_attention(lazyev_lib):
     """No eviction ever fires, the cache just grows: plain attention over all tokens so far."""
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg2"].scaled(batch=1, prompt_len=40, steps=300, budget=340, window=16)
-    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e", chunk=64)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e", target_blocks=12)
     assert stat["evictions"] == 0 and stat["gpu_stats"]["len"][0] == 340
 
 
