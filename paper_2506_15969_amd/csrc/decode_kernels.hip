@@ -408,11 +408,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 
-// A block owns `tiles_per_block` consecutive 32-entry tiles of one unit; its four waves take
-// them round-robin, MAX_IT tiles per wave at most.  Two software-pipelined passes keep row
-// loads in flight while the previous tile is being multiplied: K tiles -> logits (kept in
-// registers), block-wide max, then V tiles -> exp, p_tilde store, output product.
-template <int MAX_IT>
+// A block owns 4 * N_IT consecutive 32-entry tiles of one unit; its four waves take them
+// round-robin.  Two software-pipelined passes keep row loads in flight while the previous tile
+// is being multiplied: K tiles -> logits (kept in registers), block-wide max, then V tiles ->
+// exp, p_tilde store, output product.  The loops contain no branches: tiles past the end of
+// the cache are clamped to the last row (their logits are masked to -inf), so the hardware
+// load counter the compiler waits on is exact and the next tile's loads really stay in flight.
+template <int N_IT>
 __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeArgs a) {
   constexpr int D = 128, KC = D / 32, EV = 8;
   __shared__ float red_lds[kWaves][16];
@@ -424,39 +426,26 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int G = a.group;
   const int n_old = a.n_old, n1 = a.n_old + 1;
-  const int tpb = a.chunk >> 5;
-  const int n_tiles = (n1 + 31) >> 5;
-  const int tile0 = split * tpb;
-  const int tile1 = min(n_tiles, tile0 + tpb);
+  const int tile0 = split * (4 * N_IT) + wave;          // this wave's tiles: tile0 + 4 * it
 
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
   const bf16_t *vc = static_cast<const bf16_t *>(a.v_cache) + static_cast<size_t>(unit) * a.capacity * D;
   const bf16_t *k_new = static_cast<const bf16_t *>(a.k_new) + static_cast<size_t>(unit) * D;
   const bf16_t *v_new = static_cast<const bf16_t *>(a.v_new) + static_cast<size_t>(unit) * D;
 
-  if ((n_old >> 5) >= tile0 && (n_old >> 5) < tile1) {      // appended row goes to slot N
-    if (tid < 16) {
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(kc) + static_cast<size_t>(n_old) * D)[tid] =
-          reinterpret_cast<const uint4 *>(k_new)[tid];
-    } else if (tid >= 64 && tid < 80) {
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[tid - 64] =
-          reinterpret_cast<const uint4 *>(v_new)[tid - 64];
-    }
-  }
-
   // B operand of the logits: Q^T, head c (zero rows beyond the group)
   u32x4_t qb[KC];
   {
     const bf16_t *q = static_cast<const bf16_t *>(a.q) +
-                      (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * D;
+                      (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * D +
+                      min(c, G - 1) * D + g * 8;
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) {
-      qb[kk] = u32x4_t{0, 0, 0, 0};
-      if (c < G) qb[kk] = *reinterpret_cast<const u32x4_t *>(q + c * D + kk * 32 + g * 8);
+      const u32x4_t v = *reinterpret_cast<const u32x4_t *>(q + kk * 32);
+      qb[kk] = c < G ? v : u32x4_t{0, 0, 0, 0};
     }
   }
 
-  // rows past the end are clamped to the appended row (and masked later)
   auto load_k = [&](u32x4_t (&dst)[2][KC], int tile) {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
@@ -477,44 +466,38 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
   };
 
   // ---- pass 1: logits of head c for this lane's entries {32*tile + 16*st + 4g + i}
-  float sv[MAX_IT][2][4];
+  float sv[N_IT][2][4];
   float mx = -INFINITY;
+  u32x4_t vbuf[2][EV];
   {
     u32x4_t kbuf[2][2][KC];
-    if (tile0 + wave < tile1) load_k(kbuf[0], tile0 + wave);
+    load_k(kbuf[0], tile0);
 #pragma unroll
-    for (int it = 0; it < MAX_IT; ++it) {
-      const int tile = tile0 + wave + 4 * it;
-      if (it + 1 < MAX_IT && tile + 4 < tile1) load_k(kbuf[(it + 1) & 1], tile + 4);
-      if (tile < tile1) {
+    for (int it = 0; it < N_IT; ++it) {
+      const int tile = tile0 + 4 * it;
+      if (it + 1 < N_IT) load_k(kbuf[(it + 1) & 1], tile + 4);
+      else load_v(vbuf[0], tile0);                      // first V tile rides behind the last K tile
+      __builtin_amdgcn_sched_barrier(0);                // issue the loads before this tile's math
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+      for (int st = 0; st < 2; ++st) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int kk = 0; kk < KC; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8_t, kbuf[it & 1][st][kk]),
-                __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+        for (int kk = 0; kk < KC; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, kbuf[it & 1][st][kk]),
+              __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int tok = tile * 32 + st * 16 + 4 * g + i;
-            const float v = tok < n1 ? acc[i] * a.scale : -INFINITY;
-            sv[it][st][i] = v;
-            mx = fmaxf(mx, v);
-          }
+        for (int i = 0; i < 4; ++i) {
+          const int tok = tile * 32 + st * 16 + 4 * g + i;
+          const float v = tok < n1 ? acc[i] * a.scale : -INFINITY;
+          sv[it][st][i] = v;
+          mx = fmaxf(mx, v);
         }
-      } else {
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) sv[it][st][i] = -INFINITY;
       }
     }
   }
 
-  // ---- pass 2, with its first V tile requested before the block-wide max is known
-  u32x4_t vbuf[2][EV];
-  if (tile0 + wave < tile1) load_v(vbuf[0], tile0 + wave);
+  // ---- block-wide max per head (every block holds at least one real entry)
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   if (g == 0) red_lds[wave][c] = mx;
@@ -524,48 +507,48 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
   for (int w = 1; w < kWaves; ++w) m_loc = fmaxf(m_loc, red_lds[w][c]);
   __syncthreads();
 
+  // ---- pass 2
   float lsum = 0.f;
   f32x4_t o[EV];
 #pragma unroll
   for (int e = 0; e < EV; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float *p_tilde = a.ws.p_tilde +
-                   (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G + c) * a.p_stride;
+                   (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G + min(c, G - 1)) * a.p_stride;
 #pragma unroll
-  for (int it = 0; it < MAX_IT; ++it) {
-    const int tile = tile0 + wave + 4 * it;
-    if (it + 1 < MAX_IT && tile + 4 < tile1) load_v(vbuf[(it + 1) & 1], tile + 4);
-    if (tile < tile1) {
-      // exp(s - local max): fp32 for the tracking, rounded to bf16 for the output product
-      bf16x8_t pa;
+  for (int it = 0; it < N_IT; ++it) {
+    const int tile = tile0 + 4 * it;
+    if (it + 1 < N_IT) load_v(vbuf[(it + 1) & 1], tile + 4);
+    __builtin_amdgcn_sched_barrier(0);
+    // exp(s - local max): fp32 for the tracking, rounded to bf16 for the output product
+    bf16x8_t pa;
 #pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        const int tokb = tile * 32 + st * 16 + 4 * g;
-        float e[4];
+    for (int st = 0; st < 2; ++st) {
+      const int tokb = tile * 32 + st * 16 + 4 * g;
+      float e[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          e[i] = __expf(sv[it][st][i] - m_loc);
-          lsum += e[i];
-          pa[st * 4 + i] = static_cast<__bf16>(e[i]);
-        }
-        if (c < G) {
-          if (tokb + 4 <= n1) {
-            *reinterpret_cast<float4 *>(p_tilde + tokb) = make_float4(e[0], e[1], e[2], e[3]);
-          } else {
+      for (int i = 0; i < 4; ++i) {
+        e[i] = __expf(sv[it][st][i] - m_loc);
+        lsum += e[i];
+        pa[st * 4 + i] = static_cast<__bf16>(e[i]);
+      }
+      if (c < G) {
+        if (tokb + 4 <= n1) {
+          *reinterpret_cast<float4 *>(p_tilde + tokb) = make_float4(e[0], e[1], e[2], e[3]);
+        } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (tokb + i < n1) p_tilde[tokb + i] = e[i];
-          }
+          for (int i = 0; i < 4; ++i)
+            if (tokb + i < n1) p_tilde[tokb + i] = e[i];
         }
       }
+    }
 #pragma unroll
-      for (int e = 0; e < EV; ++e) {
-        u32x4_t vb;
+    for (int e = 0; e < EV; ++e) {
+      u32x4_t vb;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-          vb[w] = __builtin_amdgcn_perm(vbuf[it & 1][2 * w + 1][e >> 1], vbuf[it & 1][2 * w][e >> 1],
-                                        (e & 1) ? 0x07060302u : 0x05040100u);
-        o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8_t, vb), o[e], 0, 0, 0);
-      }
+      for (int w = 0; w < 4; ++w)
+        vb[w] = __builtin_amdgcn_perm(vbuf[it & 1][2 * w + 1][e >> 1], vbuf[it & 1][2 * w][e >> 1],
+                                      (e & 1) ? 0x07060302u : 0x05040100u);
+      o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8_t, vb), o[e], 0, 0, 0);
     }
   }
   lsum += __shfl_xor(lsum, 16);
@@ -599,14 +582,25 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
     ml[tid] = m_loc;
     ml[G + tid] = l_loc;
   }
+
+  // the block that owns slot N stores the appended row (everybody read it from k_new / v_new)
+  if (n_old / (128 * N_IT) == split) {
+    if (tid < 16) {
+      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(kc) + static_cast<size_t>(n_old) * D)[tid] =
+          reinterpret_cast<const uint4 *>(k_new)[tid];
+    } else if (tid >= 64 && tid < 80) {
+      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[tid - 64] =
+          reinterpret_cast<const uint4 *>(v_new)[tid - 64];
+    }
+  }
 }
 
-template <int MAX_IT>
+template <int N_IT>
 hipError_t launch_mfma(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
   dim3 grid_s(a.n_split, units);
   if (ev) hipEventRecord(ev[0], stream);
-  hipLaunchKernelGGL((decode_split_mfma_kernel<MAX_IT>), grid_s, dim3(kBlock), 0, stream, a);
+  hipLaunchKernelGGL((decode_split_mfma_kernel<N_IT>), grid_s, dim3(kBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev) hipEventRecord(ev[1], stream);
@@ -666,11 +660,20 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev
   if (a.chunk <= 0 || (!mfma && a.chunk > kChunkMax) || a.n_split > kSplitMaxLds ||
       a.n_split > a.n_split_max || static_cast<long long>(a.n_split) * a.chunk < a.n_old + 1)
     return hipErrorInvalidValue;
-  if (a.variant == 1 && a.dtype == 1 && a.head_dim == 128) {
-    // chunk is a multiple of 32 here; a wave takes every fourth tile of the block
-    const int its = ((a.chunk >> 5) + kWaves - 1) / kWaves;
-    if (a.chunk % 32 != 0 || its > 8) return hipErrorInvalidValue;
-    return its <= 4 ? launch_mfma<4>(a, stream, ev) : launch_mfma<8>(a, stream, ev);
+  if (mfma) {
+    // chunk = 128 * N_IT entries per block
+    if (a.chunk % 128 != 0) return hipErrorInvalidValue;
+    switch (a.chunk / 128) {
+      case 1: return launch_mfma<1>(a, stream, ev);
+      case 2: return launch_mfma<2>(a, stream, ev);
+      case 3: return launch_mfma<3>(a, stream, ev);
+      case 4: return launch_mfma<4>(a, stream, ev);
+      case 5: return launch_mfma<5>(a, stream, ev);
+      case 6: return launch_mfma<6>(a, stream, ev);
+      case 7: return launch_mfma<7>(a, stream, ev);
+      case 8: return launch_mfma<8>(a, stream, ev);
+      default: return hipErrorInvalidValue;
+    }
   }
   if (a.dtype == 0) {
     if (a.head_dim == 64) return launch_group<float, 64>(a, stream, ev);

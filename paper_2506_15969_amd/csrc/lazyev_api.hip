@@ -208,17 +208,15 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.head_dim = c.head_dim; a.group = ctx->group; a.capacity = ctx->capacity;
   a.n_old = n_old; a.t = t; a.prompt_len = c.prompt_len;
   if (ctx->variant == 1 && c.dtype == LAZYEV_DTYPE_BF16 && c.head_dim == 128) {
-    // MFMA kernel: blocks own whole 32-entry tiles, spread evenly, at most 32 tiles each
+    // MFMA kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
     const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
     int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
     if (n_split < 1) n_split = 1;
-    if (n_split > n_tiles) n_split = n_tiles;
-    int tpb = (n_tiles + n_split - 1) / n_split;
-    const int tpb_min = (n_tiles + lazyev::decode_split_max() - 1) / lazyev::decode_split_max();
-    if (tpb < tpb_min) tpb = tpb_min;
-    if (tpb > 32) tpb = 32;
-    a.chunk = tpb * kTile;
-    a.n_split = (n_tiles + tpb - 1) / tpb;
+    int n_it = (n_tiles + 4 * n_split - 1) / (4 * n_split);
+    while (n_it < 8 && (n_tiles + 4 * n_it - 1) / (4 * n_it) > lazyev::decode_split_max()) ++n_it;
+    if (n_it > 8) n_it = 8;
+    a.chunk = 4 * n_it * kTile;
+    a.n_split = (n_tiles + 4 * n_it - 1) / (4 * n_it);
   } else {
     a.chunk = ctx->chunk;
     a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
