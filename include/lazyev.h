@@ -137,8 +137,13 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
 int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
 
-/* Tuning knob: attention kernel.  1 (default) uses the MFMA kernel where it applies (bf16,
- * head_dim 128) and the vector-ALU kernel elsewhere; 0 always uses the vector-ALU kernel.
+/* Tuning knob: attention kernel.
+ *   0  vector-ALU split kernel + merge kernel (any supported shape);
+ *   2  MFMA split kernel + merge kernel (bf16, head_dim 128);
+ *   3  one MFMA block per unit, no merge kernel and no workspace traffic (bf16, head_dim 128,
+ *      group * capacity small enough for the logits of a unit to stay in LDS);
+ *   1  (default) picks 2 when it applies, else 0.
+ * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0.
  * Errors: EINVAL. */
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
 

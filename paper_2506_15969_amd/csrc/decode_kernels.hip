@@ -656,7 +656,8 @@ int decode_split_max() { return kSplitMaxLds; }
 int decode_slice_max() { return kSliceMax; }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
-  const bool mfma = a.variant == 1 && a.dtype == 1 && a.head_dim == 128;
+  if (a.variant == 3) return launch_decode_unit(a, stream, ev);
+  const bool mfma = a.variant == 2 && a.dtype == 1 && a.head_dim == 128;
   if (a.chunk <= 0 || (!mfma && a.chunk > kChunkMax) || a.n_split > kSplitMaxLds ||
       a.n_split > a.n_split_max || static_cast<long long>(a.n_split) * a.chunk < a.n_old + 1)
     return hipErrorInvalidValue;

@@ -156,6 +156,11 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->n_evicted.assign(cfg->n_layers, 0);
   ctx->last_hip_error = 0;
   ctx->prof_armed = 0;
+  if (cfg->dtype == LAZYEV_DTYPE_BF16 && cfg->head_dim == 128 &&
+      lazyev::decode_unit_prepare() != hipSuccess) {
+    delete ctx;
+    return LAZYEV_EHIP;
+  }
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
 
   hipError_t e = hipMemsetAsync(ctx->ws.activations, 0,
@@ -186,7 +191,7 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
 }
 
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant) {
-  if (!ctx || variant < 0 || variant > 1) return LAZYEV_EINVAL;
+  if (!ctx || variant < 0 || variant > 3) return LAZYEV_EINVAL;
   ctx->variant = variant;
   return LAZYEV_OK;
 }
@@ -207,8 +212,19 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
   a.head_dim = c.head_dim; a.group = ctx->group; a.capacity = ctx->capacity;
   a.n_old = n_old; a.t = t; a.prompt_len = c.prompt_len;
-  if (ctx->variant == 1 && c.dtype == LAZYEV_DTYPE_BF16 && c.head_dim == 128) {
-    // MFMA kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
+  // which attention kernel: see lazyev_set_variant
+  const bool mfma_shape = c.dtype == LAZYEV_DTYPE_BF16 && c.head_dim == 128;
+  const int lds_stride = (ctx->capacity + 31) / 32 * 32 + 8;
+  const bool unit_fits = mfma_shape && lazyev::decode_unit_lds_bytes(ctx->group, lds_stride) <= 150 * 1024;
+  int kind = 0;
+  if (mfma_shape && ctx->variant != 0) {
+    kind = 2;
+    if (unit_fits && ctx->variant == 3) kind = 3;
+  }
+  a.lds_stride = lds_stride;
+  a.lds_stage_offset = static_cast<int32_t>(lazyev::decode_unit_stage_offset(ctx->group, lds_stride));
+  if (kind == 2) {
+    // MFMA split kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
     const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
     int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
     if (n_split < 1) n_split = 1;
@@ -223,7 +239,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   }
   a.n_split_max = ctx->n_split_max;
   a.p_stride = (ctx->capacity + 3) / 4 * 4;
-  a.variant = ctx->variant;
+  a.variant = kind;
   a.alpha = c.alpha; a.scale = ctx->scale; a.dtype = c.dtype;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
   a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
