@@ -26,6 +26,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the attention split kernel at the steady-state cache length, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/; the
+# counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb).
+MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 67180 * 1024 + 9188 * 1024}
+
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
     """Bytes one layer's decode step must move with n1 cached entries (after the append):
@@ -111,6 +116,13 @@ def main():
     ap.add_argument("--profile-every", type=int, default=16,
                     help="time one layer call with HIP events every this many steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prompt-len", type=int, default=-1,
+                    help="override the workload's prompt length (prompt = budget puts the cache "
+                         "in its steady state from the first step; used for short profiling runs)")
+    ap.add_argument("--variant", type=int, default=-1, help="attention kernel override (lazyev_set_variant)")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="after the timed region, run one plain copy kernel of this many MiB "
+                         "(a known traffic to scale hardware byte counters with)")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
     args = ap.parse_args()
@@ -126,6 +138,8 @@ def main():
 
     cfg = CONFIGS[args.config]
     K = args.steps or cfg.steps
+    if args.prompt_len >= 0:
+        cfg = cfg.scaled(prompt_len=args.prompt_len, name="%s-prompt%d" % (cfg.name, args.prompt_len))
     if args.no_evict:
         cfg = cfg.scaled(budget=cfg.prompt_len + K, name=cfg.name + "-fullkv")
     wl = Workload(cfg)
@@ -148,6 +162,8 @@ def main():
         eng.init()
         if args.chunk:
             eng.set_chunk(args.chunk)
+        if args.variant >= 0:
+            eng.set_variant(args.variant)
 
     # ---- inputs resident in HBM
     per_step = L * S * (Hq + 2 * Hkv) * d * esz
@@ -219,8 +235,20 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
 
+    if args.calibrate_copy_mb:
+        nbytes = args.calibrate_copy_mb << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        lib.lazyev_stream_probe(dst.data_ptr(), src.data_ptr(), nbytes, 2048,
+                                torch.cuda.current_stream(dev).cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
     prof = eng.profile_read()
     st = eng.stats()
+    # what a pair of HIP events adds to the kernel it brackets (empty kernel, same stream)
+    ov = C.c_double(0.0)
+    lib.lazyev_event_overhead(200, C.c_void_p(torch.cuda.current_stream(dev).cuda_stream), C.byref(ov))
+    ov_ms = ov.value
     # bytes of the profiled decode calls
     prof_steps = [t for t in range(1, K + 1) if args.profile_every and t % args.profile_every == 0]
     dec_bytes = sum(algorithmic_bytes_decode(cfg, n1_at(t)) for t in prof_steps)
@@ -247,24 +275,30 @@ def main():
         "input_generation_s": t_gen,
     }
     if split_n:
-        ach = dec_bytes / (split_ms * 1e-3) / 1e9
+        # event intervals minus the fixed cost of the event pair itself
+        split_k = split_ms - ov_ms * split_n
+        call_k = split_ms + comb_ms - 2 * ov_ms * split_n
+        ach = dec_bytes / (split_k * 1e-3) / 1e9
         result["roofline"] = {
-            "kernel": "decode_split_kernel", "bound": "hbm", "achieved": ach,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
-            "avg_us": 1e3 * split_ms / split_n, "launches_timed": split_n,
+            "kernel": "attention split kernel (first kernel of lazyev_decode_step)",
+            "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "avg_us": 1e3 * split_k / split_n, "avg_us_between_events": 1e3 * split_ms / split_n,
+            "event_pair_overhead_us": 1e3 * ov_ms, "launches_timed": split_n,
             "algorithmic_bytes_per_launch": dec_bytes / split_n,
-            "decode_call": {"avg_us": 1e3 * (split_ms + comb_ms) / split_n,
-                            "achieved": dec_bytes / ((split_ms + comb_ms) * 1e-3) / 1e9,
-                            "frac": dec_bytes / ((split_ms + comb_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "decode_call": {"avg_us": 1e3 * call_k / split_n,
+                            "achieved": dec_bytes / (call_k * 1e-3) / 1e9,
+                            "frac": dec_bytes / (call_k * 1e-3) / 1e9 / HBM_PEAK_GBS},
         }
         if mov_n:
             mb = algorithmic_bytes_move(cfg)
+            mov_k = mov_ms - ov_ms * mov_n
             result["roofline"]["compaction"] = {
-                "kernel": "evict_move_kernel", "avg_us": 1e3 * mov_ms / mov_n,
-                "select_avg_us": 1e3 * sel_ms / sel_n, "launches_timed": mov_n,
+                "kernel": "evict_move_kernel", "avg_us": 1e3 * mov_k / mov_n,
+                "select_avg_us": 1e3 * (sel_ms - ov_ms * sel_n) / sel_n, "launches_timed": mov_n,
                 "algorithmic_bytes_per_launch_upper_bound": mb,
-                "achieved": mb / (mov_ms / mov_n * 1e-3) / 1e9,
-                "frac": mb / (mov_ms / mov_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                "achieved": mb / (mov_k / mov_n * 1e-3) / 1e9,
+                "frac": mb / (mov_k / mov_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
         # whole-step view: all algorithmic decode bytes of the run over the wall time
         tot = sum(algorithmic_bytes_decode(cfg, n1_at(t)) for t in range(1, K + 1)) * L
         result["roofline"]["whole_run_frac"] = tot / elapsed / 1e9 / HBM_PEAK_GBS

@@ -166,6 +166,11 @@ int lazyev_stream_probe(void *dst, const void *src, size_t bytes, int32_t n_bloc
 int lazyev_stream_read_probe(const void *src, size_t bytes, int32_t n_blocks, void *sink,
                              void *stream);
 
+/* Average time, in milliseconds, between two HIP events recorded back to back on `stream`
+ * with nothing between them: the fixed cost an event pair adds to the interval measured around
+ * a kernel.  Waits for the stream.  ms_avg: (host).  Errors: EINVAL, EHIP. */
+int lazyev_event_overhead(int32_t n_pairs, void *stream, double *ms_avg);
+
 void lazyev_destroy(lazyev_ctx *ctx);              /* frees host memory only; NULL is allowed */
 const char *lazyev_strerror(int code);
 int lazyev_last_hip_error(const lazyev_ctx *ctx);  /* hipError_t of the last EHIP, else 0 */

@@ -43,6 +43,7 @@ EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_de
            "lazyev_evict", "lazyev_stats", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
+           "lazyev_event_overhead",
            "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
 
 lib.lazyev_capacity.restype = C.c_int32
@@ -67,6 +68,8 @@ lib.lazyev_stream_probe.restype = C.c_int
 lib.lazyev_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
 lib.lazyev_stream_read_probe.restype = C.c_int
 lib.lazyev_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+lib.lazyev_event_overhead.restype = C.c_int
+lib.lazyev_event_overhead.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
 lib.lazyev_set_target_blocks.restype = C.c_int
 lib.lazyev_set_target_blocks.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_set_variant.restype = C.c_int

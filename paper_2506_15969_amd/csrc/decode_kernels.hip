@@ -53,6 +53,15 @@ template <> struct Elem<bf16_t> {
   __device__ static void store(bf16_t *p, float x) { *p = float_to_bf16(x); }
 };
 
+// Barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for
+// its global loads and stores (which __syncthreads would also drain).
+__device__ __forceinline__ void lds_barrier() {
+  __asm__ volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0), vmcnt and expcnt untouched
+  __builtin_amdgcn_s_barrier();
+  __asm__ volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -501,11 +510,11 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   if (g == 0) red_lds[wave][c] = mx;
-  __syncthreads();
+  lds_barrier();
   float m_loc = red_lds[0][c];
 #pragma unroll
   for (int w = 1; w < kWaves; ++w) m_loc = fmaxf(m_loc, red_lds[w][c]);
-  __syncthreads();
+  lds_barrier();
 
   // ---- pass 2
   float lsum = 0.f;
@@ -565,7 +574,7 @@ __global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeA
       *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][i], o[5][i], o[6][i], o[7][i]);
     }
   }
-  __syncthreads();
+  lds_barrier();
   const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
   float *pacc = a.ws.part_acc + part * (G * D);
   for (int i = tid; i < G * D; i += kBlock) {

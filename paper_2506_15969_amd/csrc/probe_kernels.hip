@@ -34,7 +34,34 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *dst, const uint
   for (; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+__global__ void empty_kernel() {}
+
 }  // namespace
+
+// Average elapsed time, in milliseconds, between two HIP events recorded back to back with no
+// work between them (behind a kernel, as in a busy stream): what an event pair adds to the
+// interval measured around a kernel.
+extern "C" int lazyev_event_overhead(int32_t n_pairs, void *stream, double *ms_avg) {
+  if (n_pairs < 1 || !ms_avg) return LAZYEV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return LAZYEV_EHIP;
+  if (hipEventCreate(&b) != hipSuccess) { hipEventDestroy(a); return LAZYEV_EHIP; }
+  double total = 0.0;
+  int rc = LAZYEV_OK;
+  for (int i = 0; i < n_pairs && rc == LAZYEV_OK; ++i) {
+    hipLaunchKernelGGL(empty_kernel, dim3(256), dim3(256), 0, s);      // keep the queue busy first
+    hipEventRecord(a, s);
+    hipEventRecord(b, s);
+    float ms = 0.f;
+    if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) rc = LAZYEV_EHIP;
+    total += ms;
+  }
+  hipEventDestroy(a);
+  hipEventDestroy(b);
+  *ms_avg = total / n_pairs;
+  return rc;
+}
 
 extern "C" int lazyev_stream_probe(void *dst, const void *src, size_t bytes, int32_t n_blocks,
                                    void *stream) {
