@@ -130,9 +130,9 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
  * them beyond floating-point summation order.
  *   lazyev_set_chunk: entries per block of the vector-ALU attention kernel (a power of two,
  *     64..256; default 128).
- *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernel aims for
+ *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernels aim for
  *     (default 512 = two per compute unit); each unit gets round(n_blocks / units) blocks,
- *     at least one, each owning at most 1024 entries.
+ *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64).
  * Errors: EINVAL. */
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
 int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
@@ -142,8 +142,10 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
  *   2  MFMA split kernel + merge kernel (bf16, head_dim 128);
  *   3  one MFMA block per unit, no merge kernel and no workspace traffic (bf16, head_dim 128,
  *      group * capacity small enough for the logits of a unit to stay in LDS);
- *   1  (default) picks 2 when it applies, else 0.
- * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0.
+ *   4  one launch: MFMA split blocks, the block that finishes a unit last merges the partials
+ *      and does the tracking (bf16, head_dim 128);
+ *   1  (default) picks 4 when it applies, else 0.
+ * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0, 4 -> 0.
  * Errors: EINVAL. */
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
 

@@ -14,6 +14,7 @@ struct Workspace {
   float    *p_tilde;      // [batch][n_q_heads][p_stride] exp(s - partial max) of every entry
   int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
+  int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
 };
 
 struct DecodeArgs {
@@ -27,7 +28,8 @@ struct DecodeArgs {
   int32_t lds_stride;     // unit kernel: row stride of the logits in LDS
   int32_t lds_stage_offset;  // unit kernel: byte offset of the K staging areas in dynamic LDS
   int32_t variant;        // attention kernel actually launched: 0 vector ALU + merge,
-                          // 2 MFMA split + merge, 3 one MFMA block per unit
+                          // 2 MFMA split + merge, 3 one MFMA block per unit, 4 fused MFMA
+  int32_t xcd_map;        // fused kernel: place the blocks of a unit on one XCD
   float   alpha, scale;
   int32_t dtype;
   const void *q, *k_new, *v_new;
@@ -38,6 +40,7 @@ struct DecodeArgs {
   const float *p_override;
   Workspace ws;
   unsigned long long *activation_counter;   // this layer's [units][slice_max] counters
+  int32_t *ticket;                          // [units], zero between launches
 };
 
 struct EvictArgs {
@@ -56,6 +59,10 @@ struct EvictArgs {
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 // One block per unit, no workspace traffic (bf16, head_dim 128, logits of a unit fit in LDS).
 hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
+// One launch per call: split blocks, the last block of a unit merges and tracks (bf16, d 128).
+hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
+int decode_fused_split_max();
+int decode_fused_run_max();
 hipError_t decode_unit_prepare();
 size_t decode_unit_lds_bytes(int group, int lds_stride);
 size_t decode_unit_stage_offset(int group, int lds_stride);

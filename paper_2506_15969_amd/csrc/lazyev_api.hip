@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -64,7 +65,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, src_index, activations, total;
+  size_t part_acc, part_ml, p_tilde, src_index, activations, ticket, total;
   int32_t n_split_max;
 };
 
@@ -77,9 +78,10 @@ Layout layout_of(const lazyev_config *c) {
   size_t off = 0;
   l.part_acc = off; off = align_up(off + units * l.n_split_max * g * c->head_dim * sizeof(float));
   l.part_ml = off;  off = align_up(off + units * l.n_split_max * 2 * g * sizeof(float));
-  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * ((cap + 3) / 4 * 4) * sizeof(float));
+  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * ((cap + 15) / 16 * 16) * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
+  l.ticket = off; off = align_up(off + units * sizeof(int32_t));
   l.total = off;
   return l;
 }
@@ -150,6 +152,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.p_tilde = reinterpret_cast<float *>(base + l.p_tilde);
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
+  ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
   ctx->len.assign(cfg->n_layers, cfg->prompt_len);
   ctx->last_step.assign(cfg->n_layers, 0);
   ctx->n_evict_events.assign(cfg->n_layers, 0);
@@ -167,6 +170,8 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
                                 static_cast<size_t>(cfg->n_layers) * ctx->units *
                                     lazyev::decode_slice_max() * sizeof(unsigned long long),
                                 ctx->stream);
+  if (e == hipSuccess)
+    e = hipMemsetAsync(ctx->ws.ticket, 0, static_cast<size_t>(ctx->units) * sizeof(int32_t), ctx->stream);
   if (e == hipSuccess)
     e = lazyev::launch_init_state(cfg->ts, cfg->mri, cfg->pos,
                                   static_cast<int64_t>(cfg->n_layers) * ctx->units, ctx->capacity,
@@ -191,7 +196,7 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
 }
 
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant) {
-  if (!ctx || variant < 0 || variant > 3) return LAZYEV_EINVAL;
+  if (!ctx || variant < 0 || variant > 4) return LAZYEV_EINVAL;
   ctx->variant = variant;
   return LAZYEV_OK;
 }
@@ -219,11 +224,27 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   int kind = 0;
   if (mfma_shape && ctx->variant != 0) {
     kind = 2;
-    if (unit_fits && ctx->variant == 3) kind = 3;
+    if (ctx->variant == 4) kind = 4;
+    if (ctx->variant == 3) kind = unit_fits ? 3 : 2;
   }
   a.lds_stride = lds_stride;
   a.lds_stage_offset = static_cast<int32_t>(lazyev::decode_unit_stage_offset(ctx->group, lds_stride));
-  if (kind == 2) {
+  if (kind == 4) {
+    // fused kernel: n_split blocks of four waves per unit, every wave a run of 16-entry sub-tiles
+    const int n_sub = (n_old + 1 + 15) / 16;
+    int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
+    if (n_split > (n_sub + 3) / 4) n_split = (n_sub + 3) / 4;
+    if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();
+    if (n_split > ctx->n_split_max) n_split = ctx->n_split_max;
+    if (n_split < 1) n_split = 1;
+    // a wave's run of sub-tiles must fit the longest instantiated run
+    const int run_max = lazyev::decode_fused_run_max();
+    while ((n_sub + 4 * n_split - 1) / (4 * n_split) > run_max) ++n_split;
+    a.n_split = n_split;
+    a.chunk = getenv("LAZYEV_DEBUG") ? atoi(getenv("LAZYEV_DEBUG")) : 0;   // TEMP diagnosis
+    a.xcd_map = ctx->units % 8 == 0 ? 1 : 0;
+    if (a.chunk & 64) a.xcd_map = 0;   // TEMP diagnosis
+  } else if (kind == 2) {
     // MFMA split kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
     const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
     int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
@@ -238,7 +259,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
   }
   a.n_split_max = ctx->n_split_max;
-  a.p_stride = (ctx->capacity + 3) / 4 * 4;
+  a.p_stride = (ctx->capacity + 15) / 16 * 16;
   a.variant = kind;
   a.alpha = c.alpha; a.scale = ctx->scale; a.dtype = c.dtype;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
@@ -249,6 +270,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.p_out = p_out; a.p_override = p_override;
   a.ws = ctx->ws;
+  a.ticket = ctx->ws.ticket;
   a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
 
   const hipError_t e = lazyev::launch_decode(a, ctx->stream, arm_events(ctx, 0));

@@ -48,16 +48,21 @@ def test_cfg1_fp32_every_unit_every_step(lazyev_lib, mode):
                                                ("e2e", 2, 1000), ("e2e", 0, 128), ("e2e", 0, 64),
                                                ("oracle_p", 2, 24), ("synthetic", 2, 40),
                                                ("synthetic", 0, 256), ("e2e", 3, 0),
-                                               ("oracle_p", 3, 0), ("synthetic", 3, 0)])
+                                               ("oracle_p", 3, 0), ("synthetic", 3, 0),
+                                               ("e2e", 4, 8), ("e2e", 4, 16), ("e2e", 4, 24),
+                                               ("e2e", 4, 1000), ("oracle_p", 4, 32),
+                                               ("synthetic", 4, 40)])
 def test_cfg2_shapes_scaled_down(lazyev_lib, mode, variant, knob):
     """bf16, 28/4 heads, d=128; cache up to 170+32 entries (7 tiles of 32, ragged tail).
     variant 2 is the MFMA split kernel, `knob` its target block count (8 units: 1, 2, 7 blocks
-    per unit); variant 3 is the one-block-per-unit MFMA kernel; variant 0 is the vector-ALU
-    kernel, `knob` its chunk."""
+    per unit); variant 3 is the one-block-per-unit MFMA kernel; variant 4 is the single-launch
+    MFMA kernel, `knob` its target block count (1, 2, 3 blocks per unit, and as many as the
+    cache length allows: waves with one or no sub-tile); variant 0 is the vector-ALU kernel,
+    `knob` its chunk."""
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=100, steps=330, budget=170, window=32,
                                  interval_lo=20, interval_hi=120)
-    kw = dict(target_blocks=knob) if variant == 2 else (dict(chunk=knob) if variant == 0 else {})
+    kw = dict(target_blocks=knob) if variant in (2, 4) else (dict(chunk=knob) if variant == 0 else {})
     stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode=mode, variant=variant, **kw)
     _report("cfg2-small/%s/variant%d/knob%d" % (mode, variant, knob), stat)
     assert stat["evictions"] == len([t for t in range(32, 331, 32) if 100 + t > 170])
@@ -109,9 +114,11 @@ def test_budget_at_least_sequence_is_full_attention(lazyev_lib):
     assert stat["evictions"] == 0 and stat["gpu_stats"]["len"][0] == 340
     stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e", variant=3)
     assert stat["evictions"] == 0 and stat["gpu_stats"]["len"][0] == 340
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e", variant=4, target_blocks=3)
+    assert stat["evictions"] == 0 and stat["gpu_stats"]["len"][0] == 340
 
 
-@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("variant", [2, 3, 4])
 def test_two_runs_are_bitwise_identical(lazyev_lib, variant):
     from lockstep import make_engine
     from paper_2506_15969_amd.workload import Workload
