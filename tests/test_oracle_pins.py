@@ -38,6 +38,18 @@ def test_score_matches_printed_formula(dt, mri):
     assert abs(Decimal(got) - (h1 + h2)) <= Decimal(4) * Decimal(math.ulp(got))
 
 
+def test_score_matches_golden_file():
+    """tests/golden/eq3_values.txt: Eq. 3 from the printed formulas in decimal arithmetic."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "eq3_values.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) >= 10
+    t = 40000
+    for dt, mri, want in rows:
+        got = float(mri_centric_score(t, [t - int(dt)], [int(mri)])[0])
+        assert abs(got - float(want)) <= 1e-12, (dt, mri, got, want)
+
+
 def test_score_known_constants():
     """Values that follow by hand: f(0)=1, f(1)=2/(1+e); MRI=1 has no H2; MRI=0 rules."""
     t = 100
