@@ -12,9 +12,27 @@ struct Workspace {
   float    *part_acc;     // [units][n_split_max][G][D]  un-normalised partial outputs
   float    *part_ml;      // [units][n_split_max][2][G]  partial row max, partial row sum
   float    *p_tilde;      // [batch][n_q_heads][p_stride] exp(s - partial max) of every entry
+                          // (split + merge kernels); the first logits buffer lies over it
+  float    *logits[2];    // [units][p_stride][8]        fused kernel: scaled logits, double-buffered
+  float    *stat[2];      // [units][8][2]               fused kernel: softmax max and 1 / sum per head
   int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
   int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
+};
+
+// Tracking of one finished decode call (Alg. 1 first loop, Eq. 1) from its stored logits and
+// softmax statistics; the fused kernel runs it one call late.
+struct TrackArgs {
+  int32_t valid;
+  int32_t n_old, t, prompt_len;
+  int32_t capacity, group, n_q_heads, n_kv_heads, units;
+  int32_t p_stride;                 // entries per unit in the logits buffer
+  float   alpha;
+  int32_t *ts, *mri, *pos;          // the call's layer slab
+  const float *logits, *stat;
+  float *p_out;
+  const float *p_override;
+  unsigned long long *activation_counter;   // the call's layer
 };
 
 struct DecodeArgs {
@@ -29,7 +47,6 @@ struct DecodeArgs {
   int32_t lds_stage_offset;  // unit kernel: byte offset of the K staging areas in dynamic LDS
   int32_t variant;        // attention kernel actually launched: 0 vector ALU + merge,
                           // 2 MFMA split + merge, 3 one MFMA block per unit, 4 fused MFMA
-  int32_t xcd_map;        // fused kernel: place the blocks of a unit on one XCD
   float   alpha, scale;
   int32_t dtype;
   const void *q, *k_new, *v_new;
@@ -41,6 +58,9 @@ struct DecodeArgs {
   Workspace ws;
   unsigned long long *activation_counter;   // this layer's [units][slice_max] counters
   int32_t *ticket;                          // [units], zero between launches
+  // fused kernel: where this call's logits and statistics go, and the previous call to track
+  float *logits_out, *stat_out;
+  TrackArgs track;
 };
 
 struct EvictArgs {
@@ -62,7 +82,9 @@ hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_
 // One launch per call: split blocks, the last block of a unit merges and tracks (bf16, d 128).
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 int decode_fused_split_max();
+int decode_fused_head_pad();
 int decode_fused_run_max();
+hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
 hipError_t decode_unit_prepare();
 size_t decode_unit_lds_bytes(int group, int lds_stride);
 size_t decode_unit_stage_offset(int group, int lds_stride);

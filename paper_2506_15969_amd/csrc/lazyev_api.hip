@@ -5,7 +5,6 @@
 
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -29,6 +28,9 @@ struct lazyev_ctx {
   std::vector<int32_t> len, last_step;
   std::vector<int64_t> n_evict_events, n_evicted;
   int last_hip_error;
+  // fused kernel: the call whose tracking has not been applied yet, and the buffer pair in turn
+  lazyev::TrackArgs pend;
+  int cur_buf;
   // profiling aid: event triples of the calls that were armed, kind 0 = decode, 1 = evict
   int32_t prof_armed;
   struct Timed { int kind; hipEvent_t ev[3]; };
@@ -65,7 +67,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, src_index, activations, ticket, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, ticket, total;
   int32_t n_split_max;
 };
 
@@ -78,7 +80,12 @@ Layout layout_of(const lazyev_config *c) {
   size_t off = 0;
   l.part_acc = off; off = align_up(off + units * l.n_split_max * g * c->head_dim * sizeof(float));
   l.part_ml = off;  off = align_up(off + units * l.n_split_max * 2 * g * sizeof(float));
-  l.p_tilde = off;  off = align_up(off + static_cast<size_t>(c->batch) * c->n_q_heads * ((cap + 15) / 16 * 16) * sizeof(float));
+  // two logits buffers of [units][C16][8] floats; the split + merge kernels use the first as
+  // [batch][n_q_heads][C16]
+  const size_t logits_bytes = units * ((cap + 15) / 16 * 16) * 8 * sizeof(float);
+  l.p_tilde = off;  off = align_up(off + logits_bytes);
+  l.logits1 = off;  off = align_up(off + logits_bytes);
+  l.stat = off;     off = align_up(off + 2 * units * 16 * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
@@ -110,6 +117,14 @@ void drop_events(lazyev_ctx *ctx) {
 int fail_hip(lazyev_ctx *ctx, hipError_t e) {
   ctx->last_hip_error = static_cast<int>(e);
   return LAZYEV_EHIP;
+}
+
+// Applies the tracking of the last fused decode call if it is still pending.
+hipError_t flush_tracking(lazyev_ctx *ctx) {
+  if (!ctx->pend.valid) return hipSuccess;
+  const hipError_t e = lazyev::launch_track(ctx->pend, ctx->stream);
+  if (e == hipSuccess) ctx->pend.valid = 0;
+  return e;
 }
 
 }  // namespace
@@ -150,6 +165,12 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.part_acc = reinterpret_cast<float *>(base + l.part_acc);
   ctx->ws.part_ml = reinterpret_cast<float *>(base + l.part_ml);
   ctx->ws.p_tilde = reinterpret_cast<float *>(base + l.p_tilde);
+  ctx->ws.logits[0] = ctx->ws.p_tilde;
+  ctx->ws.logits[1] = reinterpret_cast<float *>(base + l.logits1);
+  ctx->ws.stat[0] = reinterpret_cast<float *>(base + l.stat);
+  ctx->ws.stat[1] = ctx->ws.stat[0] + static_cast<size_t>(cfg->batch) * cfg->n_kv_heads * 16;
+  std::memset(&ctx->pend, 0, sizeof(ctx->pend));
+  ctx->cur_buf = 0;
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
@@ -223,8 +244,8 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   const bool unit_fits = mfma_shape && lazyev::decode_unit_lds_bytes(ctx->group, lds_stride) <= 150 * 1024;
   int kind = 0;
   if (mfma_shape && ctx->variant != 0) {
-    kind = 2;
-    if (ctx->variant == 4) kind = 4;
+    kind = 4;
+    if (ctx->variant == 2) kind = 2;
     if (ctx->variant == 3) kind = unit_fits ? 3 : 2;
   }
   a.lds_stride = lds_stride;
@@ -237,13 +258,14 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();
     if (n_split > ctx->n_split_max) n_split = ctx->n_split_max;
     if (n_split < 1) n_split = 1;
-    // a wave's run of sub-tiles must fit the longest instantiated run
+    // the logits of a wave's run of sub-tiles stay in LDS until the run ends
     const int run_max = lazyev::decode_fused_run_max();
     while ((n_sub + 4 * n_split - 1) / (4 * n_split) > run_max) ++n_split;
     a.n_split = n_split;
-    a.chunk = getenv("LAZYEV_DEBUG") ? atoi(getenv("LAZYEV_DEBUG")) : 0;   // TEMP diagnosis
-    a.xcd_map = ctx->units % 8 == 0 ? 1 : 0;
-    if (a.chunk & 64) a.xcd_map = 0;   // TEMP diagnosis
+    a.chunk = 16;
+    a.logits_out = ctx->ws.logits[ctx->cur_buf];
+    a.stat_out = ctx->ws.stat[ctx->cur_buf];
+    a.track = ctx->pend;                           // the previous call's tracking rides along
   } else if (kind == 2) {
     // MFMA split kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
     const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
@@ -273,10 +295,32 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.ticket = ctx->ws.ticket;
   a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
 
+  if (kind != 4) {                                 // the other kernels track in the same call
+    const hipError_t ef = flush_tracking(ctx);
+    if (ef != hipSuccess) return fail_hip(ctx, ef);
+  }
   const hipError_t e = lazyev::launch_decode(a, ctx->stream, arm_events(ctx, 0));
   if (e != hipSuccess) return fail_hip(ctx, e);
   ctx->len[layer] = n_old + 1;
   ctx->last_step[layer] = t;
+  if (kind == 4) {
+    lazyev::TrackArgs &k = ctx->pend;              // this call's tracking: with the next launch
+    std::memset(&k, 0, sizeof(k));
+    k.valid = 1;
+    k.n_old = n_old; k.t = t; k.prompt_len = c.prompt_len;
+    k.capacity = ctx->capacity; k.group = ctx->group; k.n_q_heads = c.n_q_heads;
+    k.n_kv_heads = c.n_kv_heads; k.units = ctx->units; k.p_stride = a.p_stride;
+    k.alpha = c.alpha;
+    k.ts = a.ts; k.mri = a.mri; k.pos = a.pos;
+    k.logits = a.logits_out; k.stat = a.stat_out;
+    k.p_out = p_out; k.p_override = p_override;
+    k.activation_counter = a.activation_counter;
+    ctx->cur_buf ^= 1;
+    if (p_out || p_override) {                     // the caller looks at the weights now
+      const hipError_t ef = flush_tracking(ctx);
+      if (ef != hipSuccess) return fail_hip(ctx, ef);
+    }
+  }
   return LAZYEV_OK;
 }
 
@@ -301,6 +345,8 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.mri = c.mri + static_cast<size_t>(layer) * slab;
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
+  const hipError_t ef = flush_tracking(ctx);       // scores use TS and MRI of step t (Alg. 1 order)
+  if (ef != hipSuccess) return fail_hip(ctx, ef);
   const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));
   if (e != hipSuccess) return fail_hip(ctx, e);
   if (n_evicted) *n_evicted = n - c.budget;
@@ -313,7 +359,9 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
   if (!ctx || !out || out->n_layers != ctx->cfg.n_layers) return LAZYEV_EINVAL;
   const int L = ctx->cfg.n_layers;
-  hipError_t e = hipStreamSynchronize(ctx->stream);
+  hipError_t e = flush_tracking(ctx);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
   if (out->n_activations) {
     const size_t per_layer = static_cast<size_t>(ctx->units) * lazyev::decode_slice_max();

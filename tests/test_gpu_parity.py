@@ -147,3 +147,37 @@ def test_two_runs_are_bitwise_identical(lazyev_lib, variant):
         assert float((diff / out_a.float().abs().clamp_min(1e-3)).max()) <= 2 ** -6   # two bf16 ulps
     else:
         assert torch.equal(out_a, out_b)
+
+
+def test_deferred_tracking_equals_immediate(lazyev_lib):
+    """The single-launch kernel applies the tracking of a call with the NEXT launch (or at the
+    next lazyev_evict / lazyev_stats) unless the caller asks for the weights.  Both routes must
+    leave identical state: one engine is driven with p_out (tracked at once, the route the
+    lock-step tests check against the oracle), the other without, two layers interleaved."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=2, batch=2, prompt_len=100, steps=140, budget=170, window=32)
+    wl = Workload(cfg)
+    runs = []
+    for immediate in (True, False):
+        eng = make_engine(lazyev_lib, cfg, wl, variant=4, target_blocks=24)
+        out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+        p_out = torch.zeros((cfg.batch, cfg.n_q_heads, cfg.capacity), dtype=torch.float32, device="cuda")
+        ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
+        outs, n_ev = [], 0
+        for t in range(1, cfg.steps + 1):
+            for l in range(cfg.n_layers):
+                q, kn, vn = ins[l]
+                eng.decode_step(l, t, q[t - 1], kn[t - 1], vn[t - 1], out,
+                                p_out=p_out if immediate else None)
+                outs.append(out.clone())
+            for l in range(cfg.n_layers):
+                n_ev += 1 if eng.evict(l, t) else 0
+        st = eng.stats()                                  # applies what is still pending
+        runs.append((torch.stack(outs), eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(),
+                     eng.mri.clone(), eng.pos.clone(), st, n_ev))
+    a, b = runs
+    assert a[7] == b[7] == 2 * len([t for t in range(32, 141, 32) if 100 + t > 170])
+    for x, y in zip(a[:6], b[:6]):
+        assert torch.equal(x, y)
+    assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
