@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the attention split kernel at the steady-state cache length, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/; the
 # counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 67180 * 1024 + 9188 * 1024}
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
@@ -42,11 +42,12 @@ def algorithmic_bytes_decode(cfg, n1: int) -> int:
     return kv + qo + app
 
 
-def algorithmic_bytes_move(cfg) -> int:
-    """Upper bound of what a stable compaction to B entries moves: B rows of K and of V read
+def algorithmic_bytes_move(cfg, rows_moved_per_event: float) -> float:
+    """What a stable in-place compaction must move: every surviving entry that changes slot
+    (counted by the library, summed over the layer's units) has its K row and its V row read
     and written once."""
     esz = 4 if cfg.dtype == "fp32" else 2
-    return 2 * 2 * cfg.batch * cfg.n_kv_heads * cfg.budget * cfg.head_dim * esz
+    return 2 * 2 * rows_moved_per_event * cfg.head_dim * esz
 
 
 def _oracle_worker(job):
@@ -280,7 +281,7 @@ def main():
         call_k = split_ms + comb_ms - 2 * ov_ms * split_n
         ach = dec_bytes / (split_k * 1e-3) / 1e9
         result["roofline"] = {
-            "kernel": "attention split kernel (first kernel of lazyev_decode_step)",
+            "kernel": "decode_fused_kernel (the one kernel of lazyev_decode_step)",
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
             "avg_us": 1e3 * split_k / split_n, "avg_us_between_events": 1e3 * split_ms / split_n,
@@ -291,12 +292,14 @@ def main():
                             "frac": dec_bytes / (call_k * 1e-3) / 1e9 / HBM_PEAK_GBS},
         }
         if mov_n:
-            mb = algorithmic_bytes_move(cfg)
+            events = sum(st["n_evict_events"])
+            mb = algorithmic_bytes_move(cfg, sum(st["n_rows_moved"]) / max(events, 1))
             mov_k = mov_ms - ov_ms * mov_n
             result["roofline"]["compaction"] = {
                 "kernel": "evict_move_kernel", "avg_us": 1e3 * mov_k / mov_n,
                 "select_avg_us": 1e3 * (sel_ms - ov_ms * sel_n) / sel_n, "launches_timed": mov_n,
-                "algorithmic_bytes_per_launch_upper_bound": mb,
+                "algorithmic_bytes_per_launch": mb,
+                "rows_moved_per_unit_event": sum(st["n_rows_moved"]) / max(events, 1) / (S * Hkv),
                 "achieved": mb / (mov_k / mov_n * 1e-3) / 1e9,
                 "frac": mb / (mov_k / mov_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
         # whole-step view: all algorithmic decode bytes of the run over the wall time

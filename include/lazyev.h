@@ -72,6 +72,9 @@ typedef struct {
                                    the layer's events                                           */
   int64_t *n_activations;       /* (host, nullable) out: (entry, step) pairs with p >= alpha,
                                    summed over the layer's units                                */
+  int64_t *n_rows_moved;        /* (host, nullable) out: surviving entries that an eviction moved
+                                   to a lower slot, summed over the layer's units and events:
+                                   each is one K row and one V row read and written             */
 } lazyev_stats_t;
 
 /* Entries of cache per unit: C = max(prompt_len, budget) + window.  0 if cfg is invalid. */

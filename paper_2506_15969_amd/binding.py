@@ -36,7 +36,8 @@ class Config(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("len", C.POINTER(C.c_int32)),
                 ("last_step", C.POINTER(C.c_int32)), ("n_evict_events", C.POINTER(C.c_int64)),
-                ("n_evicted", C.POINTER(C.c_int64)), ("n_activations", C.POINTER(C.c_int64))]
+                ("n_evicted", C.POINTER(C.c_int64)), ("n_activations", C.POINTER(C.c_int64)),
+                ("n_rows_moved", C.POINTER(C.c_int64))]
 
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
@@ -186,7 +187,7 @@ class LazyEviction:
         a32 = lambda: (C.c_int32 * L)()
         a64 = lambda: (C.c_int64 * L)()
         bufs = dict(len=a32(), last_step=a32(), n_evict_events=a64(), n_evicted=a64(),
-                    n_activations=a64())
+                    n_activations=a64(), n_rows_moved=a64())
         st = Stats(n_layers=L, **{k: C.cast(v, C.POINTER(C.c_int32 if k in ("len", "last_step")
                                                          else C.c_int64)) for k, v in bufs.items()})
         _check(lib.lazyev_stats(self._ctx, C.byref(st)), "lazyev_stats")

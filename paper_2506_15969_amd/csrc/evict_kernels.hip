@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   const unsigned long long thr = prefix;
   const unsigned drop_ties = ties_total - k_rem;
 
-  unsigned run_def = 0, run_tie = 0;
+  unsigned run_def = 0, run_tie = 0, n_moved = 0;
   for (int base = 0; base < n; base += kSelBlock) {
     const int slot = base + tid;
     const bool valid = slot < n;
@@ -171,47 +171,86 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
     if (keep) {
       ts[dst] = v_ts; mri[dst] = v_mri; pos[dst] = v_pos;
       src_index[dst] = slot;
+      if (dst != static_cast<unsigned>(slot)) n_moved += 1;
     }
     run_def += total & 0xFFFFu;
     run_tie += total >> 16;
   }
+  // how many survivors change slot (what the row move has to copy); one writer per unit
+  for (int o = 32; o > 0; o >>= 1) n_moved += __shfl_xor(n_moved, o);
+  __syncthreads();
+  if ((tid & 63) == 0) wave_tot[tid >> 6] = n_moved;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned all = 0;
+    for (int w = 0; w < kSelWaves; ++w) all += wave_tot[w];
+    a.rows_moved[unit] += all;
+  }
 }
 
 // Moves rows of K (blockIdx.y = 0) or V (1): row j <- row src_index[j], j < budget.
-// Row parts are 128 bytes: 8 lanes of 16 bytes.
+// Row parts are 128 bytes: 8 lanes of 16 bytes.  A block owns one part of every row of one
+// unit and walks the rows in tiles of 32 * U; inside a tile every load completes before the
+// first store (a destination row may be another thread's source row), and because sources
+// never lie below their destinations and both grow with j, a tile's stores cannot touch what
+// a later tile still has to read.  The loads of the next tile are requested before this tile
+// is stored, so the block always has reads in flight.
+template <int U>
 __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs a, int row_bytes) {
   constexpr int LPP = 8;                       // lanes per row part
   constexpr int ROWS = kMoveBlock / LPP;       // rows per block load
-  constexpr int U = 4;
   const int tid = threadIdx.x;
   const int part = blockIdx.x, unit = blockIdx.z;
   char *slab = static_cast<char *>(blockIdx.y == 0 ? a.k_cache : a.v_cache) +
                static_cast<size_t>(unit) * a.capacity * row_bytes + part * 128 + (tid % LPP) * 16;
   const int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
 
-  for (int tile = 0; tile < a.budget; tile += ROWS * U) {
-    const int last = min(tile + ROWS * U, a.budget) - 1;
-    if (src_index[last] == last) continue;     // gather list is monotone: nothing moves yet
-    uint4 v[U];
-    bool moved[U];
+  // rows below the first evicted slot stay where they are: start at the tile that holds it
+  int first = 0;
+  while (first + ROWS * U < a.budget && src_index[first + ROWS * U - 1] == first + ROWS * U - 1)
+    first += ROWS * U;
+
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+  struct Tile { u32x4_t v[U]; int src[U]; };
+  auto load = [&](Tile &t, int tile) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = tile + u * ROWS + tid / LPP;
-      moved[u] = false;
-      if (j < a.budget) {
-        const int s = src_index[j];
-        if (s != j) {
-          v[u] = *reinterpret_cast<const uint4 *>(slab + static_cast<size_t>(s) * row_bytes);
-          moved[u] = true;
-        }
-      }
+      t.src[u] = j < a.budget ? src_index[j] : -1;
+      t.v[u] = u32x4_t{0, 0, 0, 0};
     }
-    __syncthreads();                           // all loads of the tile have landed
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = tile + u * ROWS + tid / LPP;
-      if (moved[u]) *reinterpret_cast<uint4 *>(slab + static_cast<size_t>(j) * row_bytes) = v[u];
+      if (t.src[u] >= 0 && t.src[u] != j)
+        t.v[u] = *reinterpret_cast<const u32x4_t *>(slab + static_cast<size_t>(t.src[u]) * row_bytes);
     }
+  };
+  // the tile's loads have landed in every thread (touching the values makes the compiler wait
+  // for exactly those loads), then the barrier, then its stores
+  auto store = [&](Tile &t, int tile) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) __asm__ volatile("" : "+v"(t.v[u]));
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = tile + u * ROWS + tid / LPP;
+      if (t.src[u] >= 0 && t.src[u] != j)
+        *reinterpret_cast<u32x4_t *>(slab + static_cast<size_t>(j) * row_bytes) = t.v[u];
+    }
+  };
+
+  Tile t0, t1;
+  load(t0, first);
+  for (int tile = first; tile < a.budget; tile += 2 * ROWS * U) {
+    const bool more1 = tile + ROWS * U < a.budget;
+    if (more1) load(t1, tile + ROWS * U);
+    store(t0, tile);
+    if (!more1) break;
+    const bool more2 = tile + 2 * ROWS * U < a.budget;
+    if (more2) load(t0, tile + 2 * ROWS * U);
+    store(t1, tile + ROWS * U);
+    if (!more2) break;
   }
 }
 
@@ -228,7 +267,7 @@ hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) 
   if (ev) hipEventRecord(ev[1], stream);
   const int row_bytes = a.head_dim * (a.dtype == 0 ? 4 : 2);
   dim3 grid(row_bytes / 128, 2, a.units);
-  hipLaunchKernelGGL(evict_move_kernel, grid, dim3(kMoveBlock), 0, stream, a, row_bytes);
+  hipLaunchKernelGGL(evict_move_kernel<8>, grid, dim3(kMoveBlock), 0, stream, a, row_bytes);
   e = hipGetLastError();
   if (ev) hipEventRecord(ev[2], stream);
   return e;

@@ -17,6 +17,7 @@ struct Workspace {
   float    *stat[2];      // [units][8][2]               fused kernel: softmax max and 1 / sum per head
   int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
+  unsigned long long *rows_moved;   // [n_layers][units]             entries an eviction moved to a new slot
   int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
 };
 
@@ -72,6 +73,7 @@ struct EvictArgs {
   void *k_cache, *v_cache;
   int32_t *ts, *mri, *pos;
   Workspace ws;
+  unsigned long long *rows_moved;   // this layer's [units] counters
 };
 
 // `ev`, when not null, points at three events recorded before the first kernel, between the two

@@ -67,7 +67,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, ticket, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, total;
   int32_t n_split_max;
 };
 
@@ -88,6 +88,7 @@ Layout layout_of(const lazyev_config *c) {
   l.stat = off;     off = align_up(off + 2 * units * 16 * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
+  l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
   l.total = off;
   return l;
@@ -173,6 +174,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->cur_buf = 0;
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
+  ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
   ctx->len.assign(cfg->n_layers, cfg->prompt_len);
   ctx->last_step.assign(cfg->n_layers, 0);
@@ -187,12 +189,8 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   }
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
 
-  hipError_t e = hipMemsetAsync(ctx->ws.activations, 0,
-                                static_cast<size_t>(cfg->n_layers) * ctx->units *
-                                    lazyev::decode_slice_max() * sizeof(unsigned long long),
-                                ctx->stream);
-  if (e == hipSuccess)
-    e = hipMemsetAsync(ctx->ws.ticket, 0, static_cast<size_t>(ctx->units) * sizeof(int32_t), ctx->stream);
+  // activation counters, moved-row counters and tickets lie next to each other
+  hipError_t e = hipMemsetAsync(ctx->ws.activations, 0, l.total - l.activations, ctx->stream);
   if (e == hipSuccess)
     e = lazyev::launch_init_state(cfg->ts, cfg->mri, cfg->pos,
                                   static_cast<int64_t>(cfg->n_layers) * ctx->units, ctx->capacity,
@@ -345,6 +343,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.mri = c.mri + static_cast<size_t>(layer) * slab;
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
+  a.rows_moved = ctx->ws.rows_moved + static_cast<size_t>(layer) * ctx->units;
   const hipError_t ef = flush_tracking(ctx);       // scores use TS and MRI of step t (Alg. 1 order)
   if (ef != hipSuccess) return fail_hip(ctx, ef);
   const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));
@@ -373,6 +372,17 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
       unsigned long long sum = 0;
       for (size_t k = 0; k < per_layer; ++k) sum += tmp[i * per_layer + k];
       out->n_activations[i] = static_cast<int64_t>(sum);
+    }
+  }
+  if (out->n_rows_moved) {
+    std::vector<unsigned long long> tmp(static_cast<size_t>(ctx->units) * L);
+    e = hipMemcpy(tmp.data(), ctx->ws.rows_moved, tmp.size() * sizeof(unsigned long long),
+                  hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    for (int i = 0; i < L; ++i) {
+      unsigned long long sum = 0;
+      for (int k = 0; k < ctx->units; ++k) sum += tmp[static_cast<size_t>(i) * ctx->units + k];
+      out->n_rows_moved[i] = static_cast<int64_t>(sum);
     }
   }
   for (int i = 0; i < L; ++i) {

@@ -58,7 +58,7 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
     p_out = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
     p_in = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
     stat = dict(steps=0, decisions=0, near_threshold=0, evictions=0, max_out_err=0.0,
-                max_p_err=0.0, activations=0)
+                max_p_err=0.0, activations=0, rows_moved=0)
     rng = np.random.default_rng(cfg.seed + 12345)
     alpha32 = np.float32(cfg.alpha)
 
@@ -146,7 +146,10 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
                     assert np.array_equal(mri_g[s, h, :n1], orc[u].MRI), ("MRI", u, t)
                 # lagged eviction
                 n_ev = eng.evict(l, t)
+                before = {u: orc[u].pos.copy() for u in mine}
                 gone = {u: orc[u].evict(t) for u in mine}
+                for u in mine:                       # survivors that changed slot (order is kept)
+                    stat["rows_moved"] += int((orc[u].pos != before[u][:len(orc[u])]).sum()) if gone[u] else 0
                 for u in mine:
                     assert len(gone[u]) == n_ev, ("eviction count", u, t, n_ev, len(gone[u]))
                 if n_ev:

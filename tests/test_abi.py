@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lazyev_lib):
 def test_struct_layout_matches_header(lazyev_lib):
     # 12 four-byte fields, 6 pointers, a size_t, a pointer
     assert C.sizeof(lazyev_lib.Config) == 12 * 4 + 8 * 8
-    assert C.sizeof(lazyev_lib.Stats) == 8 + 5 * 8
+    assert C.sizeof(lazyev_lib.Stats) == 8 + 6 * 8
 
 
 def test_capacity_and_workspace(lazyev_lib):

@@ -42,6 +42,7 @@ def test_cfg1_fp32_every_unit_every_step(lazyev_lib, mode):
     assert stat["gpu_stats"]["n_activations"][0] == acts
     assert stat["gpu_stats"]["n_evict_events"][0] == 28
     assert stat["gpu_stats"]["n_evicted"][0] == 28 * 16
+    assert stat["gpu_stats"]["n_rows_moved"][0] == stat["rows_moved"] > 0
 
 
 @pytest.mark.parametrize("mode,variant,knob", [("e2e", 2, 8), ("e2e", 2, 16), ("e2e", 2, 56),
