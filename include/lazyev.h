@@ -80,8 +80,8 @@ typedef struct {
 /* Entries of cache per unit: C = max(prompt_len, budget) + window.  0 if cfg is invalid. */
 int32_t lazyev_capacity(const lazyev_config *cfg /*host*/);
 
-/* Bytes of workspace the configuration needs (split partials, score scratch, gather lists,
- * counters).  0 if cfg is invalid. */
+/* Bytes of workspace the configuration needs (split partials, two buffers of per-entry logits,
+ * gather lists, counters, tickets).  0 if cfg is invalid. */
 size_t lazyev_workspace_size(const lazyev_config *cfg /*host*/);
 
 /* Creates a context.  The caller has already written the prompt's K/V rows to entries
@@ -96,6 +96,11 @@ int lazyev_init(const lazyev_config *cfg /*host*/, lazyev_ctx **out /*host*/);
  *   out[h] = softmax(scale * q[h] K^T) V over the N+1 entries of the head's unit;
  *   an entry is active if any query head of its group has probability >= alpha (fp32 compare);
  *   active entries get MRI = max(MRI, t - TS), then TS = t.
+ * `out` and the appended K/V rows are complete when the call's work on the stream is.  The
+ * single-launch attention kernel (see lazyev_set_variant) applies the updates of ts / mri / pos
+ * with the NEXT call on the context (any layer), with lazyev_evict when an eviction is due, or
+ * with lazyev_stats, whichever comes first, and at once when p_out or p_override is given.  A
+ * caller that reads ts / mri / pos itself calls lazyev_stats first.
  * t must be the layer's previous step + 1 (first step is 1).
  * p_out (device, nullable): receives the fp32 probabilities the threshold test used, entries
  *   [0, N+1) of each row.
@@ -119,7 +124,8 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * Errors: EINVAL, EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
-/* Waits for the stream, then fills the non-null arrays of *out.  Errors: EINVAL, EHIP. */
+/* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of
+ * *out.  Errors: EINVAL, EHIP. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
 
 /* Score of Eq. 3 for n (t - TS, MRI) pairs, on the device, with the same code the eviction
@@ -135,7 +141,8 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
  *     64..256; default 128).
  *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernels aim for
  *     (default 512 = two per compute unit); each unit gets round(n_blocks / units) blocks,
- *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64).
+ *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64 blocks,
+ *     each wave at most 20 sub-tiles of 16 entries).
  * Errors: EINVAL. */
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
 int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
@@ -145,8 +152,8 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
  *   2  MFMA split kernel + merge kernel (bf16, head_dim 128);
  *   3  one MFMA block per unit, no merge kernel and no workspace traffic (bf16, head_dim 128,
  *      group * capacity small enough for the logits of a unit to stay in LDS);
- *   4  one launch: MFMA split blocks, the block that finishes a unit last merges the partials
- *      and does the tracking (bf16, head_dim 128);
+ *   4  one launch: MFMA stream blocks, the block that finishes a unit last merges the partials
+ *      into the output; the tracking rides with the next launch (bf16, head_dim 128);
  *   1  (default) picks 4 when it applies, else 0.
  * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0, 4 -> 0.
  * Errors: EINVAL. */
@@ -156,7 +163,7 @@ int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
  * (decode_step, or an evict that is due) record HIP events on the stream before, between and
  * after their two kernels.  lazyev_profile_read waits for the stream, adds up the elapsed
  * times of the armed calls since the last read and forgets them:
- *   index 0 attention split kernel, 1 combine + tracking kernel,
+ *   index 0 attention kernel (the only one of kernels 3 and 4), 1 combine + tracking kernel,
  *         2 eviction score/select kernel, 3 eviction row-move kernel.
  * ms_total, launches: (host) arrays of 4.  Errors: EINVAL, EHIP. */
 int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls);
