@@ -88,11 +88,21 @@ __device__ __forceinline__ float load_f32_device(const float *p) {
 // ----------------------------------------------------------------------------- tracking
 // Alg. 1 (first loop) and Eq. 1 for a share of one unit of a finished decode call:
 // probabilities from the stored logits and statistics, >= alpha over the query group, TS / MRI
-// update, start of the appended entry.  Part `part` of `n_parts` takes entries
-// part * 256 + tid + r * n_parts * 256, r = 0, 1, ...
+// update, start of the appended entry.  Part `part` of `n_parts` takes the entries
+// track_entry(part, n_parts, r), r = 0, 1, ...
 struct TrackBatch {
   float4 sa[kTrackRows], sb[kTrackRows];
 };
+
+// Entry that thread `tid` of part `part` (of n_parts) handles in round r: the parts own the
+// 16-entry sub-tiles exactly as the stream blocks of a launch with n_parts blocks per unit do
+// (sub-tile 4 * part + w + 4 * n_parts * k for wave w), so a tracking block that runs on the
+// XCD of the stream block with the same index finds the logits that block wrote in its L2.
+__device__ __forceinline__ int track_entry(int part, int n_parts, int r) {
+  const int j = r * (kBlock / 16) + (static_cast<int>(threadIdx.x) >> 4);   // the part's j-th sub-tile
+  const int sub = kWaves * part + (j % kWaves) + kWaves * n_parts * (j / kWaves);
+  return sub * 16 + (static_cast<int>(threadIdx.x) & 15);
+}
 
 __device__ __forceinline__ void track_load(const TrackArgs &k, int unit, int part, int n_parts, int r0,
                                            TrackBatch &b) {
@@ -100,7 +110,7 @@ __device__ __forceinline__ void track_load(const TrackArgs &k, int unit, int par
   const int n1 = k.n_old + 1;
 #pragma unroll
   for (int r = 0; r < kTrackRows; ++r) {
-    const int i = (part + (r0 + r) * n_parts) * kBlock + static_cast<int>(threadIdx.x);
+    const int i = track_entry(part, n_parts, r0 + r);
     b.sa[r] = b.sb[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < n1) {
       b.sa[r] = *reinterpret_cast<const float4 *>(lg + static_cast<size_t>(i) * kHeadPad);
@@ -121,7 +131,7 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
   unsigned n_act = 0;
 #pragma unroll
   for (int r = 0; r < kTrackRows; ++r) {
-    const int i = (part + (r0 + r) * n_parts) * kBlock + static_cast<int>(threadIdx.x);
+    const int i = track_entry(part, n_parts, r0 + r);
     if (i >= n1) continue;
     const float s[kHeadPad] = {b.sa[r].x, b.sa[r].y, b.sa[r].z, b.sa[r].w,
                                b.sb[r].x, b.sb[r].y, b.sb[r].z, b.sb[r].w};
@@ -311,7 +321,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     qb[kk] = c < G ? v : u32x4_t{0, 0, 0, 0};
   }
 
-  auto load = [&](SubTile &t, int it) {
+  auto load_k = [&](SubTile &t, int it) {
     const int sub = wv + it * n_wv;
     // K: whole rows, 16 lanes per row (row 4j+g, 16-byte chunk c); re-laid out through LDS
 #pragma unroll
@@ -320,6 +330,9 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
       const bf16_t *src = (row == n_old) ? k_new : kc + static_cast<size_t>(row) * D;
       t.k[j] = *reinterpret_cast<const u32x4_t *>(src + c * 8);
     }
+  };
+  auto load_v = [&](SubTile &t, int it) {
+    const int sub = wv + it * n_wv;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = min(sub * 16 + 4 * g + i, n_old);
@@ -328,7 +341,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     }
   };
 
-  auto compute = [&](const SubTile &t, int it) {
+  auto compute = [&](SubTile &t, int it) {
     const int sub = wv + it * n_wv;
     // K rows -> MFMA A layout (lane (c, g): row c, chunks 4kk+g).  Chunk x of row r sits at
     // slot x ^ r of the row, so both the row-wise writes and the column-wise reads touch
@@ -345,6 +358,8 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
 #pragma unroll
       for (int kk = 0; kk < KC; ++kk) ka[kk] = stage[c * 16 + ((4 * kk + g) ^ c)];
     }
+    // the K registers are free again: the next sub-tile's K rows travel during the arithmetic
+    if (it + 1 < cnt) load_k(t, it + 1);
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk)
@@ -393,14 +408,13 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
       vb[1] = __builtin_amdgcn_perm(t.v[3][e >> 1], t.v[2][e >> 1], sel);
       o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(s16x4_t, vb), o[e], 0, 0, 0);
     }
+    if (it + 1 < cnt) load_v(t, it + 1);
   };
 
   SubTile buf;
   // ---- the stream
-  for (int it = 0; it < cnt; ++it) {
-    load(buf, it);
-    compute(buf, it);
-  }
+  if (cnt > 0) { load_k(buf, 0); load_v(buf, 0); }
+  for (int it = 0; it < cnt; ++it) compute(buf, it);
 
   {                                                // this wave's logits -> workspace, 512 bytes per sub-tile
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
