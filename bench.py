@@ -215,7 +215,8 @@ def main():
                 rc = decode(ctx, l, t, q_base + i * q_sz, k_base + i * kv_sz, v_base + i * kv_sz,
                             o_base + l * q_sz, None, None)
                 if rc:
-                    raise binding.LazyevError(rc, "lazyev_decode_step(layer %d, t %d)" % (l, t))
+                    raise binding.LazyevError(rc, "lazyev_decode_step(layer %d, t %d), HIP error %d"
+                                              % (l, t, lib.lazyev_last_hip_error(ctx)))
             if t % W == 0:
                 due = n1_at(t) > cfg.budget
                 for l in range(L):

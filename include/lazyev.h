@@ -32,7 +32,8 @@ extern "C" {
 
 #define LAZYEV_OK          0
 #define LAZYEV_EINVAL     -1   /* bad shape, null pointer, B <= W, step or layer out of order   */
-#define LAZYEV_ECAPACITY  -2   /* decode_step on a full cache: a due eviction was skipped        */
+#define LAZYEV_ECAPACITY  -2   /* decode_step on a full cache (a due eviction was skipped), or an
+                                  eviction with more than LAZYEV_MAX_CANDIDATES candidates        */
 #define LAZYEV_EWORKSPACE -3   /* workspace missing or smaller than lazyev_workspace_size        */
 #define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
 
@@ -43,7 +44,9 @@ extern "C" {
 #define LAZYEV_SCORE_H2    2   /* use the H2 term of Eq. 3 */
 
 /* Largest number of eviction candidates (cache entries outside the last W) per unit that the
- * selection kernel holds in LDS. */
+ * selection kernel holds in LDS.  A configuration whose budget or prompt is longer can still
+ * decode (a budget that covers the whole generation is the full-cache baseline of Sec. 5), but
+ * an eviction that becomes due with more candidates returns LAZYEV_ECAPACITY. */
 #define LAZYEV_MAX_CANDIDATES 8192
 
 typedef struct lazyev_ctx lazyev_ctx;              /* opaque, host memory */
@@ -121,7 +124,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * original order.  N becomes B.
  * n_evicted (host, nullable): entries removed per unit (N - B, or 0).
  * t must equal the layer's last decode step.
- * Errors: EINVAL, EHIP. */
+ * Errors: EINVAL, ECAPACITY (more than LAZYEV_MAX_CANDIDATES candidates), EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
 /* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of

@@ -57,7 +57,7 @@ bool config_ok(const lazyev_config *c) {
   if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2)) return false;
   if (!(c->alpha >= 0.0f) || !(c->softmax_scale >= 0.0f)) return false;   // also rejects NaN
   const long long cap = static_cast<long long>(c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
-  if (cap - c->window > LAZYEV_MAX_CANDIDATES) return false;
+  if (cap > (1ll << 20)) return false;
   if (static_cast<long long>(c->batch) * c->n_kv_heads > 65535) return false;   // grid.y / grid.z
   return true;
 }
@@ -259,11 +259,15 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     // the logits of a wave's run of sub-tiles stay in LDS until the run ends
     const int run_max = lazyev::decode_fused_run_max();
     while ((n_sub + 4 * n_split - 1) / (4 * n_split) > run_max) ++n_split;
+    if (n_split > lazyev::decode_fused_split_max() || n_split > ctx->n_split_max) kind = 2;   // cache too long
     a.n_split = n_split;
     a.chunk = 16;
     a.logits_out = ctx->ws.logits[ctx->cur_buf];
     a.stat_out = ctx->ws.stat[ctx->cur_buf];
     a.track = ctx->pend;                           // the previous call's tracking rides along
+  }
+  if (kind == 4) {
+    // set up above
   } else if (kind == 2) {
     // MFMA split kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
     const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
@@ -330,6 +334,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   if (t < 1 || t != ctx->last_step[layer]) return LAZYEV_EINVAL;
   const int32_t n = ctx->len[layer];
   if (t % c.window != 0 || n <= c.budget) return LAZYEV_OK;       // not due (Sec. 4)
+  if (n - c.window > LAZYEV_MAX_CANDIDATES) return LAZYEV_ECAPACITY;   // more than the selection holds
 
   const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
   const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
@@ -437,7 +442,7 @@ const char *lazyev_strerror(int code) {
   switch (code) {
     case LAZYEV_OK: return "ok";
     case LAZYEV_EINVAL: return "invalid argument (shape, null pointer, budget <= window, step or layer out of order)";
-    case LAZYEV_ECAPACITY: return "cache full: a due eviction was skipped";
+    case LAZYEV_ECAPACITY: return "cache full (a due eviction was skipped), or more eviction candidates than the selection kernel holds";
     case LAZYEV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LAZYEV_EHIP: return "HIP runtime error";
     default: return "unknown lazyev error code";

@@ -42,7 +42,7 @@ def test_capacity_and_workspace(lazyev_lib):
                                          ("budget", 8), ("dtype", 5), ("score_flags", 8),
                                          ("n_layers", 0), ("alpha", float("nan")),
                                          ("n_q_heads", 32), ("prompt_len", -1),
-                                         ("budget", 9000)])
+                                         ("budget", 2_000_000)])
 def test_invalid_configs_are_rejected(lazyev_lib, field, value):
     b = lazyev_lib
     cfg = _good(b)
