@@ -50,7 +50,7 @@ constexpr int kFusedSplitMax = 64;      // blocks per unit
 constexpr float kRaise = 8.0f;          // the reference maximum moves when exceeded by this much
 constexpr int kTrackRows = 3;           // entries per thread per tracking batch
 constexpr int kHeadPad = 8;             // logits and statistics are stored for 8 heads per unit
-constexpr int kRunMax = 20;             // sub-tiles per wave whose logits fit its share of LDS (10 KB)
+constexpr int kRunMax = 20;             // sub-tiles whose logits a wave keeps in LDS (10 KB) before it writes them out
 
 typedef unsigned short bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
   // one 16-row K sub-tile per wave while streaming; afterwards the wave's output accumulator
   __shared__ u32x4_t stage_lds[kWaves][16 * 16];
-  extern __shared__ float logit_lds[];             // [kWaves][run][16 entries][8 heads]
+  extern __shared__ float logit_lds[];             // [kWaves][min(run, kRunMax)][16 entries][8 heads]
   __shared__ unsigned cnt_lds[kWaves];
   __shared__ int last_flag;
 
@@ -304,8 +304,9 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   const bf16_t *k_new = static_cast<const bf16_t *>(a.k_new) + static_cast<size_t>(unit) * D;
   const bf16_t *v_new = static_cast<const bf16_t *>(a.v_new) + static_cast<size_t>(unit) * D;
   const bf16_t *q_row = static_cast<const bf16_t *>(a.q) + (head0 + hc) * D + g * 8;
-  const int run = (n_sub + kWaves * n_split - 1) / (kWaves * n_split);
+  const int run = min((n_sub + kWaves * n_split - 1) / (kWaves * n_split), kRunMax);
   float *my_logits = logit_lds + static_cast<size_t>(wave) * run * (16 * kHeadPad);
+  int seg0 = 0;                                    // first of this wave's sub-tiles whose logits are still in LDS
   float *logits_out = a.logits_out + static_cast<size_t>(unit) * a.p_stride * kHeadPad;
 
   float m_ref = -INFINITY, lsum = 0.f;
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     // logits of the sub-tile -> [entry][head] in LDS; written out when the wave's run ends (a
     // store among the loads would hold up the in-order load counter)
     if (c < kHeadPad) {
-      float *dst = my_logits + it * (16 * kHeadPad);
+      float *dst = my_logits + (it - seg0) * (16 * kHeadPad);
 #pragma unroll
       for (int i = 0; i < 4; ++i) dst[(4 * g + i) * kHeadPad + c] = s[i];
     }
@@ -414,16 +415,23 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   SubTile buf;
   // ---- the stream
   if (cnt > 0) { load_k(buf, 0); load_v(buf, 0); }
-  for (int it = 0; it < cnt; ++it) compute(buf, it);
-
-  {                                                // this wave's logits -> workspace, 512 bytes per sub-tile
+  // this wave's logits -> workspace, 512 bytes per sub-tile: when the run ends, and for a
+  // long run every kRunMax sub-tiles
+  auto flush = [&](int it0, int it1) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    for (int it = lane >> 5; it < cnt; it += 2)
+    for (int it = it0 + (lane >> 5); it < it1; it += 2)
       *reinterpret_cast<float4 *>(logits_out + static_cast<size_t>(wv + it * n_wv) * (16 * kHeadPad) + (lane & 31) * 4) =
-          *reinterpret_cast<const float4 *>(my_logits + it * (16 * kHeadPad) + (lane & 31) * 4);
+          *reinterpret_cast<const float4 *>(my_logits + (it - it0) * (16 * kHeadPad) + (lane & 31) * 4);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  for (int it = 0; it < cnt; ++it) {
+    compute(buf, it);
+    if (it + 1 - seg0 == kRunMax && it + 1 < cnt) { flush(seg0, it + 1); seg0 = it + 1; }
   }
+  flush(seg0, cnt);
   // ---- the four waves of the block -> one partial
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
@@ -496,7 +504,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
 
 int decode_fused_split_max() { return kFusedSplitMax; }
 int decode_fused_head_pad() { return kHeadPad; }
-int decode_fused_run_max() { return kRunMax; }
 
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
   if (!k.valid || k.units < 1 || k.group > kHeadPad || !k.logits || !k.stat ||
@@ -518,8 +525,8 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
     return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
   const int n_sub = (a.n_old + 1 + 15) / 16;
-  const int run = (n_sub + kWaves * a.n_split - 1) / (kWaves * a.n_split);
-  if (run > kRunMax) return hipErrorInvalidValue;   // the host raises n_split first
+  int run = (n_sub + kWaves * a.n_split - 1) / (kWaves * a.n_split);
+  if (run > kRunMax) run = kRunMax;
   const size_t lds_all = static_cast<size_t>(kWaves) * run * 16 * kHeadPad * sizeof(float);
   const int sb = a.n_split * units;
   hipLaunchKernelGGL(decode_fused_kernel, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);

@@ -85,7 +85,6 @@ hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 int decode_fused_split_max();
 int decode_fused_head_pad();
-int decode_fused_run_max();
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
 hipError_t decode_unit_prepare();
 size_t decode_unit_lds_bytes(int group, int lds_stride);

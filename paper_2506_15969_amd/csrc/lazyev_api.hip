@@ -256,10 +256,6 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();
     if (n_split > ctx->n_split_max) n_split = ctx->n_split_max;
     if (n_split < 1) n_split = 1;
-    // the logits of a wave's run of sub-tiles stay in LDS until the run ends
-    const int run_max = lazyev::decode_fused_run_max();
-    while ((n_sub + 4 * n_split - 1) / (4 * n_split) > run_max) ++n_split;
-    if (n_split > lazyev::decode_fused_split_max() || n_split > ctx->n_split_max) kind = 2;   // cache too long
     a.n_split = n_split;
     a.chunk = 16;
     a.logits_out = ctx->ws.logits[ctx->cur_buf];

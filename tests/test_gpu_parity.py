@@ -182,3 +182,17 @@ def test_deferred_tracking_equals_immediate(lazyev_lib):
     for x, y in zip(a[:6], b[:6]):
         assert torch.equal(x, y)
     assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
+
+
+def test_long_runs_per_wave(lazyev_lib):
+    """One block per unit over a cache of 1400..1532 entries: every wave owns 22-24 sub-tiles,
+    more than it keeps logits for in LDS, so the logits go out in two instalments."""
+    from lockstep import run_lockstep
+    cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=1400, steps=70, budget=1500, window=32,
+                                 interval_lo=10, interval_hi=40)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e", variant=4, target_blocks=8)
+    _report("cfg2-long-runs", stat)
+    assert stat["evictions"] == 0 and stat["near_threshold"] <= 2
+    cfg = cfg.scaled(budget=1416, steps=40)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="oracle_p", variant=4, target_blocks=8)
+    assert stat["evictions"] == 1 and stat["near_threshold"] == 0
