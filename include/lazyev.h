@@ -42,6 +42,10 @@ extern "C" {
 
 #define LAZYEV_SCORE_H1    1   /* use the H1 term of Eq. 3 */
 #define LAZYEV_SCORE_H2    2   /* use the H2 term of Eq. 3 */
+/* With LAZYEV_SCORE_H2: use 1 - H2 (and 1 at MRI = 1, 0 at MRI = 0) in place of H2.  The H2 of
+ * Sec. 4 item 2 as printed grows with MRI; the sentence introducing it and App. D describe a
+ * term that falls with MRI.  Default is the printed formula; this bit selects the other reading. */
+#define LAZYEV_SCORE_H2_DECREASING 16
 
 /* Largest number of eviction candidates (cache entries outside the last W) per unit that the
  * selection kernel holds in LDS.  A configuration whose budget or prompt is longer can still

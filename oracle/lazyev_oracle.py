@@ -100,6 +100,7 @@ def two_sigmoid_neg_libm(x) -> np.ndarray:
 
 USE_H1 = 1
 USE_H2 = 2
+H2_DECREASING = 16      # H2 reflected: 1 - f(1/(MRI-1)), the reading under which Sec. 4 item 2's prose holds
 
 
 def mri_centric_score(t: int, ts, mri, score_flags: int = USE_H1 | USE_H2,
@@ -108,7 +109,10 @@ def mri_centric_score(t: int, ts, mri, score_flags: int = USE_H1 | USE_H2,
 
     H1 = f((t - TS)/MRI)         Sec. 4 item 1;   MRI = 0: 1 if t == TS else 0 (R8)
     H2 = f(1/(MRI - 1))          Sec. 4 item 2;   0 for MRI <= 1 (R8)
-    `score_flags` switches the two terms for the ablation of Table 4.
+    `score_flags` switches the two terms for the ablation of Table 4.  With H2_DECREASING the
+    second term is 1 - f(1/(MRI - 1)) for MRI >= 1 (1 at MRI = 1, falling towards 0) and 0 for
+    MRI = 0: the printed H2 grows with MRI, while the sentence that introduces it and App. D
+    ask for a term that falls with MRI (R6); the reflection keeps the printed building block.
     """
     ts = np.asarray(ts, dtype=np.int64)
     mri = np.asarray(mri, dtype=np.int64)
@@ -126,6 +130,8 @@ def mri_centric_score(t: int, ts, mri, score_flags: int = USE_H1 | USE_H2,
         has = mri > 1
         inv = np.divide(1.0, m - 1.0, out=np.zeros_like(m), where=has)
         h2 = np.where(has, f(inv), 0.0)
+        if score_flags & H2_DECREASING:
+            h2 = np.where(mri >= 1, 1.0 - h2, 0.0)  # one more correctly rounded subtraction
 
     return h1 + h2
 

@@ -20,6 +20,7 @@ lib = C.CDLL(_LIB_PATH)
 OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
+SCORE_H2_DECREASING = 16
 MAX_CANDIDATES = 8192
 
 

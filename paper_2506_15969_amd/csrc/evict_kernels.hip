@@ -54,6 +54,8 @@ __device__ double mri_centric_score(int32_t delta_t, int32_t mri, int32_t flags)
     else h1 = (delta_t == 0) ? 1.0 : 0.0;
   }
   if ((flags & 2) && mri > 1) h2 = two_sigmoid_neg(1.0 / (static_cast<double>(mri) - 1.0));
+  // reflected second term (falls with MRI, as the prose of Sec. 4 item 2 and App. D ask)
+  if ((flags & 2) && (flags & 16)) h2 = (mri >= 1) ? 1.0 - h2 : 0.0;
   return h1 + h2;
 }
 

@@ -54,7 +54,7 @@ bool config_ok(const lazyev_config *c) {
   if (c->head_dim != 64 && c->head_dim != 128) return false;
   if (c->window < 1 || c->budget <= c->window || c->prompt_len < 0) return false;
   if (c->dtype != LAZYEV_DTYPE_FP32 && c->dtype != LAZYEV_DTYPE_BF16) return false;
-  if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2)) return false;
+  if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2 | LAZYEV_SCORE_H2_DECREASING)) return false;
   if (!(c->alpha >= 0.0f) || !(c->softmax_scale >= 0.0f)) return false;   // also rejects NaN
   const long long cap = static_cast<long long>(c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
   if (cap > (1ll << 20)) return false;
@@ -398,7 +398,7 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
 int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score, int64_t n,
                        int32_t score_flags, void *stream) {
   if (n < 0 || (n > 0 && (!delta_t || !mri || !score))) return LAZYEV_EINVAL;
-  if (score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2)) return LAZYEV_EINVAL;
+  if (score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2 | LAZYEV_SCORE_H2_DECREASING)) return LAZYEV_EINVAL;
   const hipError_t e = lazyev::launch_score_pairs(delta_t, mri, score, n, score_flags,
                                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;

@@ -83,7 +83,7 @@ def test_other_head_shapes(lazyev_lib, name, dtype, hq, hkv, d):
     assert stat["evictions"] > 0
 
 
-@pytest.mark.parametrize("flags", [0, 1, 2])
+@pytest.mark.parametrize("flags", [0, 1, 2, 2 | 16, 3 | 16])
 def test_score_ablation_flags(lazyev_lib, flags):
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg1"].scaled(steps=200)

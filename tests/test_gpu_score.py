@@ -25,11 +25,18 @@ def test_exhaustive_grid(lazyev_lib):
         _check(lazyev_lib, D.ravel(), M.ravel())
 
 
+def test_reflected_h2_grid(lazyev_lib):
+    mri = np.arange(0, 40000)
+    for dt in (0, 1, 63, 5000):
+        _check(lazyev_lib, np.full_like(mri, dt), mri, 3 | 16)
+    _check(lazyev_lib, np.zeros_like(mri), mri, 2 | 16)
+
+
 def test_random_pairs_and_flags(lazyev_lib):
     rng = np.random.default_rng(0)
     dt = rng.integers(0, 32769, 1_000_000)
     mri = rng.integers(0, 32769, 1_000_000)
-    for flags in (3, 1, 2, 0):
+    for flags in (3, 1, 2, 0, 2 | 16, 3 | 16, 1 | 16):
         _check(lazyev_lib, dt, mri, flags)
     # very stale entries: x = dt/mri beyond the cut-off of the exponential
     _check(lazyev_lib, np.array([2_000_000_000, 700, 699, 1399, 1400]), np.array([1, 1, 1, 2, 2]))

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle.lazyev_oracle import (USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
+from oracle.lazyev_oracle import (H2_DECREASING, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
                                   mri_centric_score, select_survivors, two_sigmoid_neg,
                                   two_sigmoid_neg_libm)
 from paper_2506_15969_amd.workload import CONFIGS, Workload
@@ -78,6 +78,31 @@ def test_score_ranges_and_monotonicity():
     assert np.all((s2 >= 0) & (s2 < 1)) and s2[0] == 0 and s2[1] == 0
     assert np.all(np.diff(s2[2:]) > 0)                    # the printed H2 increases with MRI
     assert 0.5378 < s2[2] < 0.5379
+
+
+def test_reflected_h2_is_tanh_and_decreases():
+    """1 - 2/(1+e^x) = tanh(x/2): the reflected second term against the C library's tanh and
+    decimals; it falls with MRI (what Sec. 4 item 2's prose and App. D ask of H2), is 1 at
+    MRI = 1 and 0 for a never re-activated entry, and leaves H1 alone."""
+    t = 9000
+    m = np.arange(0, 6000)
+    flags = USE_H2 | H2_DECREASING
+    s = mri_centric_score(t, np.zeros_like(m), m, flags)
+    assert s[0] == 0.0 and s[1] == 1.0
+    want = np.tanh(0.5 / (m[2:] - 1.0))
+    assert np.max(np.abs(s[2:] - want)) <= 5e-16            # 4 ulp of f near 1, then the subtraction
+    assert np.all(np.diff(s[1:]) < 0) and np.all((s >= 0) & (s <= 1))
+    for mri in (2, 3, 10, 175, 4096):
+        exact = 1 - _f_exact(Decimal(1) / Decimal(mri - 1))
+        assert abs(Decimal(float(s[mri])) - exact) <= Decimal(2) ** -51
+    # printed + reflected = 1 for MRI > 1; the bit alone (without H2) changes nothing
+    printed = mri_centric_score(t, np.zeros_like(m), m, USE_H2)
+    assert np.max(np.abs(printed[2:] + s[2:] - 1.0)) <= 2.3e-16     # one rounding
+    both = mri_centric_score(t, t - m, np.maximum(m, 1), USE_H1 | flags)
+    h1 = mri_centric_score(t, t - m, np.maximum(m, 1), USE_H1)
+    assert np.array_equal(both, h1 + mri_centric_score(t, t - m, np.maximum(m, 1), flags))
+    assert np.array_equal(mri_centric_score(t, t - m, m, USE_H1 | H2_DECREASING),
+                          mri_centric_score(t, t - m, m, USE_H1))
 
 
 def test_fixed_sequence_exp_against_libm_and_decimal():
