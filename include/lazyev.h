@@ -4,7 +4,8 @@
  * C ABI.  Every pointer is marked (host) or (device).  The library owns no device memory:
  * caches, statistics arrays and the workspace are allocated by the caller (for example as
  * torch tensors) and must stay valid until lazyev_destroy.  All calls enqueue work on the
- * stream given at init and return without waiting, except lazyev_stats, which waits for it.
+ * stream given at init and return without waiting, except lazyev_stats and
+ * lazyev_mri_histogram, which wait for it.
  * Calls on one context must come from one thread at a time.
  *
  * A "unit" is one (layer, sequence, KV head).  Each unit has its own cache of N entries
@@ -52,6 +53,9 @@ extern "C" {
  * decode (a budget that covers the whole generation is the full-cache baseline of Sec. 5), but
  * an eviction that becomes due with more candidates returns LAZYEV_ECAPACITY. */
 #define LAZYEV_MAX_CANDIDATES 8192
+
+/* Largest number of bins of lazyev_mri_histogram. */
+#define LAZYEV_MAX_HIST_BINS 8192
 
 typedef struct lazyev_ctx lazyev_ctx;              /* opaque, host memory */
 
@@ -134,6 +138,17 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /
 /* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of
  * *out.  Errors: EINVAL, EHIP. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
+
+/* Distribution of the Maximum Recurrence Interval (Eq. 1) over the cached entries, the
+ * statistic from which the observation window W is chosen offline (Sec. 3, Fig. 2(c); Sec. 4
+ * "Observation Window": W = the MRI below which 80 % of the tokens fall; run it on a context
+ * whose budget covers the whole generation so that no token has been evicted).
+ * hist[m] = number of entries 0..N-1, over all units of `layer` (-1: of every layer), whose MRI
+ * is m, for m < n_bins - 1; hist[n_bins - 1] counts MRI >= n_bins - 1.  hist[0] are the entries
+ * never re-activated since they were appended.
+ * Applies any tracking still pending and waits for the stream.
+ * Errors: EINVAL (2 <= n_bins <= LAZYEV_MAX_HIST_BINS, layer range, null), EHIP. */
+int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t *hist /*host*/);
 
 /* Score of Eq. 3 for n (t - TS, MRI) pairs, on the device, with the same code the eviction
  * uses; result as binary64.  For checking the scoring arithmetic in isolation.

@@ -11,6 +11,8 @@ What follows the paper, and where:
   * Maximum Recurrence Interval MRI ..................... Eq. 1
   * H1 / H2 scores and the MRI-centric importance I ..... Sec. 4 "MRI-Centric Eviction", Eq. 3
   * lagged eviction Top_{B-W}(I) united with the last W . Eq. 6, Algorithm 1
+  * MRI distribution and the window chosen from it ...... Sec. 3 (Fig. 2(c)); Sec. 4
+    "Observation Window"
   * greedy current-attention comparator ................. Appendix C "Baselines" (TOVA sentence)
 
 Readings taken where the paper is silent or inconsistent (each is also listed in the design
@@ -28,7 +30,9 @@ notes of the repository):
   R7  tracking for step t is applied first, then scores use TS_t and MRI_t (Algorithm 1 order).
   R8  H2 is used exactly as printed, 2*sigmoid(-1/(MRI-1)), with H2 = 0 for MRI <= 1 (MRI = 1
       is the IEEE limit of the printed formula, MRI = 0 is stated by the paper).  H1 with
-      MRI = 0 is the IEEE limit: 1 when t == TS, else 0.
+      MRI = 0 is the IEEE limit: 1 when t == TS, else 0.  The printed H2 grows with MRI although
+      the sentence introducing it and App. D describe a decreasing term; the flag H2_DECREASING
+      selects the reflected term 1 - H2 (1 at MRI = 1, 0 at MRI = 0) as the second reading.
   R9  ties in the top-k go to the more recent entry (larger slot index).
   R10 scores are binary64 and produced by ONE fixed sequence of IEEE operations (see
       `two_sigmoid_neg`), so that another implementation running the same sequence ranks
@@ -43,6 +47,8 @@ tiny inputs, and planted recurring keys surviving where the greedy comparator dr
 Accuracy on the paper's task benchmarks: parity unpinned (needs datasets and model weights).
 """
 from __future__ import annotations
+
+import math
 
 import numpy as np
 
@@ -112,7 +118,7 @@ def mri_centric_score(t: int, ts, mri, score_flags: int = USE_H1 | USE_H2,
     `score_flags` switches the two terms for the ablation of Table 4.  With H2_DECREASING the
     second term is 1 - f(1/(MRI - 1)) for MRI >= 1 (1 at MRI = 1, falling towards 0) and 0 for
     MRI = 0: the printed H2 grows with MRI, while the sentence that introduces it and App. D
-    ask for a term that falls with MRI (R6); the reflection keeps the printed building block.
+    ask for a term that falls with MRI (R8); the reflection keeps the printed building block.
     """
     ts = np.asarray(ts, dtype=np.int64)
     mri = np.asarray(mri, dtype=np.int64)
@@ -134,6 +140,25 @@ def mri_centric_score(t: int, ts, mri, score_flags: int = USE_H1 | USE_H2,
             h2 = np.where(mri >= 1, 1.0 - h2, 0.0)  # one more correctly rounded subtraction
 
     return h1 + h2
+
+
+def mri_histogram(mri_values, n_bins: int) -> np.ndarray:
+    """Number of cached entries per MRI value (Sec. 3, Fig. 2(c)); MRI >= n_bins - 1 share the
+    last bin."""
+    hist = np.zeros(n_bins, dtype=np.int64)
+    for m in np.asarray(mri_values, dtype=np.int64).ravel():
+        hist[min(int(m), n_bins - 1)] += 1
+    return hist
+
+
+def window_from_mri(mri_values, quantile: float = 0.8) -> int:
+    """Sec. 4, "Observation Window": W = the MRI value that `quantile` of the recurring tokens
+    (MRI >= 1) do not exceed, i.e. the ceil(quantile * n)-th smallest of their n MRI values."""
+    v = np.sort(np.asarray(mri_values, dtype=np.int64).ravel())
+    v = v[v >= 1]
+    if len(v) == 0:
+        return 0
+    return int(v[max(int(math.ceil(quantile * len(v))) - 1, 0)])
 
 
 def select_survivors(score: np.ndarray, n_keep: int) -> np.ndarray:

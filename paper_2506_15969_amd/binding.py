@@ -21,6 +21,7 @@ OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16
+MAX_HIST_BINS = 8192
 MAX_CANDIDATES = 8192
 
 
@@ -42,7 +43,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
-           "lazyev_evict", "lazyev_stats", "lazyev_score_pairs", "lazyev_set_chunk",
+           "lazyev_evict", "lazyev_stats", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
            "lazyev_event_overhead",
@@ -61,6 +62,8 @@ lib.lazyev_evict.restype = C.c_int
 lib.lazyev_evict.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_stats.restype = C.c_int
 lib.lazyev_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
+lib.lazyev_mri_histogram.restype = C.c_int
+lib.lazyev_mri_histogram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
 lib.lazyev_score_pairs.restype = C.c_int
 lib.lazyev_score_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_void_p]
@@ -112,6 +115,22 @@ def score_pairs(delta_t: torch.Tensor, mri: torch.Tensor, score_flags: int = SCO
     _check(lib.lazyev_score_pairs(_ptr(delta_t), _ptr(mri), _ptr(out), delta_t.numel(),
                                   score_flags, C.c_void_p(stream)), "lazyev_score_pairs")
     return out.view(delta_t.shape)
+
+
+def window_from_histogram(hist, quantile: float = 0.8) -> int:
+    """Observation window from an MRI histogram (Sec. 4, "Observation Window"): the smallest W
+    such that at least `quantile` of the re-activated entries (MRI >= 1) have MRI <= W.
+    Returns 0 if no entry was ever re-activated; an answer in the overflow bin means the
+    histogram was too short (raise n_bins)."""
+    total = sum(hist[1:])
+    if total == 0:
+        return 0
+    seen = 0
+    for m in range(1, len(hist)):
+        seen += hist[m]
+        if seen >= quantile * total:
+            return m
+    return len(hist) - 1
 
 
 class LazyEviction:
@@ -193,6 +212,13 @@ class LazyEviction:
                                                          else C.c_int64)) for k, v in bufs.items()})
         _check(lib.lazyev_stats(self._ctx, C.byref(st)), "lazyev_stats")
         return {k: list(v) for k, v in bufs.items()}
+
+    def mri_histogram(self, layer: int = -1, n_bins: int = MAX_HIST_BINS):
+        """lazyev_mri_histogram: counts of cached entries by MRI (last bin: MRI >= n_bins - 1)
+        over the units of `layer` (-1: all layers), as a list of ints."""
+        hist = (C.c_int64 * n_bins)()
+        _check(lib.lazyev_mri_histogram(self._ctx, layer, n_bins, hist), "lazyev_mri_histogram")
+        return list(hist)
 
     def set_target_blocks(self, n_blocks: int):
         _check(lib.lazyev_set_target_blocks(self._ctx, n_blocks), "lazyev_set_target_blocks")

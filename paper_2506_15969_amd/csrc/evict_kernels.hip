@@ -65,6 +65,23 @@ __global__ void score_pairs_kernel(const int32_t *dt, const int32_t *mri, double
   if (i < n) score[i] = mri_centric_score(dt[i], mri[i], flags);
 }
 
+// Counts the first n entries of every unit of a layer by MRI value; values >= n_bins - 1 share
+// the last bin.  Most entries have MRI = 0: those are counted per wave, not per lane.
+__global__ void mri_histogram_kernel(const int32_t *mri, int64_t n_units, int32_t capacity,
+                                     int32_t n, int32_t n_bins, unsigned long long *hist) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const bool in = i < n_units * n;
+  int32_t b = -1;
+  if (in) {
+    const int32_t m = mri[(i / n) * capacity + i % n];
+    b = m < n_bins - 1 ? m : n_bins - 1;
+  }
+  const unsigned long long zeros = __builtin_amdgcn_ballot_w64(b == 0);
+  if (zeros != 0 && (threadIdx.x & 63) == 0)
+    atomicAdd(&hist[0], static_cast<unsigned long long>(__builtin_popcountll(zeros)));
+  if (b > 0) atomicAdd(&hist[b], 1ull);
+}
+
 __global__ void init_state_kernel(int32_t *ts, int32_t *mri, int32_t *pos, int64_t total,
                                   int32_t capacity, int32_t prompt_len) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -281,6 +298,16 @@ hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_
   const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
   hipLaunchKernelGGL(init_state_kernel, dim3(blocks), dim3(256), 0, stream, ts, mri, pos, total,
                      capacity, prompt_len);
+  return hipGetLastError();
+}
+
+hipError_t launch_mri_histogram(const int32_t *mri, int64_t n_units, int32_t capacity, int32_t n,
+                                int32_t n_bins, unsigned long long *hist, hipStream_t stream) {
+  if (n_units <= 0 || n <= 0) return hipSuccess;
+  if (n > capacity || n_bins < 2) return hipErrorInvalidValue;
+  const unsigned blocks = static_cast<unsigned>((n_units * n + 255) / 256);
+  hipLaunchKernelGGL(mri_histogram_kernel, dim3(blocks), dim3(256), 0, stream, mri, n_units,
+                     capacity, n, n_bins, hist);
   return hipGetLastError();
 }
 

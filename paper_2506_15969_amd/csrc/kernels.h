@@ -19,6 +19,7 @@ struct Workspace {
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
   unsigned long long *rows_moved;   // [n_layers][units]             entries an eviction moved to a new slot
   int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
+  unsigned long long *hist;         // [LAZYEV_MAX_HIST_BINS]  MRI histogram under construction
 };
 
 // Tracking of one finished decode call (Alg. 1 first loop, Eq. 1) from its stored logits and
@@ -92,6 +93,8 @@ size_t decode_unit_stage_offset(int group, int lds_stride);
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
                              int32_t capacity, int32_t prompt_len, hipStream_t stream);
+hipError_t launch_mri_histogram(const int32_t *mri, int64_t n_units, int32_t capacity, int32_t n,
+                                int32_t n_bins, unsigned long long *hist, hipStream_t stream);
 hipError_t launch_score_pairs(const int32_t *dt, const int32_t *mri, double *score, int64_t n,
                               int32_t flags, hipStream_t stream);
 

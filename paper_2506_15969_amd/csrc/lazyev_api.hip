@@ -67,7 +67,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, hist, total;
   int32_t n_split_max;
 };
 
@@ -90,6 +90,7 @@ Layout layout_of(const lazyev_config *c) {
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
+  l.hist = off; off = align_up(off + LAZYEV_MAX_HIST_BINS * sizeof(unsigned long long));
   l.total = off;
   return l;
 }
@@ -176,6 +177,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
+  ctx->ws.hist = reinterpret_cast<unsigned long long *>(base + l.hist);
   ctx->len.assign(cfg->n_layers, cfg->prompt_len);
   ctx->last_step.assign(cfg->n_layers, 0);
   ctx->n_evict_events.assign(cfg->n_layers, 0);
@@ -393,6 +395,23 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
     if (out->n_evicted) out->n_evicted[i] = ctx->n_evicted[i];
   }
   return LAZYEV_OK;
+}
+
+int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t *hist) {
+  if (!ctx || !hist || n_bins < 2 || n_bins > LAZYEV_MAX_HIST_BINS || layer < -1 ||
+      layer >= ctx->cfg.n_layers)
+    return LAZYEV_EINVAL;
+  hipError_t e = flush_tracking(ctx);
+  if (e == hipSuccess) e = hipMemsetAsync(ctx->ws.hist, 0, n_bins * sizeof(unsigned long long), ctx->stream);
+  const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->cfg.n_layers : layer + 1;
+  for (int l = l0; l < l1 && e == hipSuccess; ++l)
+    e = lazyev::launch_mri_histogram(ctx->cfg.mri + static_cast<size_t>(l) * ctx->units * ctx->capacity,
+                                     ctx->units, ctx->capacity, ctx->len[l], n_bins, ctx->ws.hist,
+                                     ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e == hipSuccess)
+    e = hipMemcpy(hist, ctx->ws.hist, n_bins * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+  return e == hipSuccess ? LAZYEV_OK : fail_hip(ctx, e);
 }
 
 int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score, int64_t n,

@@ -164,6 +164,13 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
     # final full comparison, rows included
     for l in layers:
         _compare_state(eng, l, [u for u in units if u[0] == l], orc, steps, rows=True)
+    # distribution of MRI over everything cached (all units of all layers on the library's side)
+    from oracle.lazyev_oracle import mri_histogram
+    stat["gpu_mri_hist"] = eng.mri_histogram(-1, 48)
+    stat["gpu_mri_hist_layer"] = {l: eng.mri_histogram(l, 48) for l in layers}
+    stat["oracle_mri_hist_layer"] = {
+        l: mri_histogram(np.concatenate([orc[u].MRI for u in units if u[0] == l]), 48).tolist()
+        for l in layers}
     stat["gpu_stats"] = st
     stat["oracle_units"] = orc
     stat["engine"] = eng

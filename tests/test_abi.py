@@ -76,3 +76,19 @@ def test_null_context_calls(lazyev_lib):
     assert b.lib.lazyev_last_hip_error(None) == 0
     for code in (0, -1, -2, -3, -4, -99):
         assert len(b.lib.lazyev_strerror(code)) > 0
+
+
+def test_window_from_histogram_is_the_quantile(lazyev_lib):
+    """Host logic: the window taken from an MRI histogram (Sec. 4, "Observation Window") equals
+    the quantile of the raw values as the oracle and numpy define it."""
+    import numpy as np
+    from oracle.lazyev_oracle import mri_histogram, window_from_mri
+    rng = np.random.default_rng(5)
+    for n in (1, 10, 1000, 5003):
+        mri = np.where(rng.random(n) < 0.5, 0, rng.geometric(0.01, n))
+        hist = mri_histogram(mri, 4096).tolist()
+        for q in (0.5, 0.8, 0.99, 1.0):
+            assert lazyev_lib.window_from_histogram(hist, q) == window_from_mri(mri, q)
+    assert lazyev_lib.window_from_histogram([5, 0, 0, 0]) == 0
+    assert lazyev_lib.window_from_histogram([0, 0, 3, 1], 0.8) == 3
+    assert lazyev_lib.lib.lazyev_mri_histogram(None, 0, 16, None) == lazyev_lib.EINVAL

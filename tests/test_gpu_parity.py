@@ -91,6 +91,32 @@ def test_score_ablation_flags(lazyev_lib, flags):
     assert stat["evictions"] > 0 and stat["near_threshold"] == 0
 
 
+def test_mri_histogram_matches_the_oracle(lazyev_lib):
+    """Every unit in the oracle: the library's MRI histogram of the layer equals the oracle's,
+    bin by bin, overflow bin included; and the window derived from it is the oracle's."""
+    from lockstep import run_lockstep
+    from oracle.lazyev_oracle import window_from_mri
+    cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=64, steps=420, budget=484, window=32)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e")      # full cache: no eviction
+    assert stat["evictions"] == 0
+    got, want = stat["gpu_mri_hist_layer"][0], stat["oracle_mri_hist_layer"][0]
+    assert got == want and got == stat["gpu_mri_hist"]
+    assert sum(got) == cfg.batch * cfg.n_kv_heads * 484 and got[-1] > 0 and sum(got[1:]) > 100
+    eng = stat["engine"]
+    all_mri = np.concatenate([u.MRI for u in stat["oracle_units"].values()])
+    wide = eng.mri_histogram(0, 1024)
+    assert lazyev_lib.window_from_histogram(wide) == window_from_mri(all_mri)
+    assert lazyev_lib.window_from_histogram(wide, 0.5) == window_from_mri(all_mri, 0.5)
+    with pytest.raises(lazyev_lib.LazyevError):
+        eng.mri_histogram(0, 1)
+    with pytest.raises(lazyev_lib.LazyevError):
+        eng.mri_histogram(1, 16)
+    # with eviction: same comparison on what is left in the cache
+    cfg = CONFIGS["cfg1"]
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="e2e")
+    assert stat["gpu_mri_hist_layer"][0] == stat["oracle_mri_hist_layer"][0]
+
+
 def test_empty_prompt_and_window_of_one(lazyev_lib):
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg1"].scaled(prompt_len=0, planted_count_in_prompt=0, steps=90, budget=40,

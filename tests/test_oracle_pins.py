@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle.lazyev_oracle import (H2_DECREASING, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
+                                  mri_histogram, window_from_mri,
                                   mri_centric_score, select_survivors, two_sigmoid_neg,
                                   two_sigmoid_neg_libm)
 from paper_2506_15969_amd.workload import CONFIGS, Workload
@@ -355,3 +356,35 @@ def test_multi_unit_wrapper_matches_single_units():
         assert np.array_equal(out[s, h * G:(h + 1) * G], o1)
     assert np.array_equal(full.state(0, "pos")[s, h], one.pos)
     assert np.array_equal(full.state(0, "MRI")[s, h], one.MRI)
+
+
+# ---------------------------------------------------------------- MRI statistics (Sec. 3 / Sec. 4)
+def test_mri_histogram_and_window_against_library_routines():
+    rng = np.random.default_rng(11)
+    for n in (1, 5, 10, 997, 4000):
+        mri = np.where(rng.random(n) < 0.4, 0, rng.geometric(0.02, n))
+        h = mri_histogram(mri, 64)
+        assert np.array_equal(h[:63], np.bincount(mri, minlength=4096)[:63])
+        assert h[63] == (mri >= 63).sum() and h.sum() == n
+        rec = mri[mri >= 1]
+        for q in (0.5, 0.8, 0.95, 1.0):
+            want = int(np.quantile(rec, q, method="inverted_cdf")) if len(rec) else 0
+            assert window_from_mri(mri, q) == want
+    assert window_from_mri([0, 0, 0]) == 0
+    assert window_from_mri([0, 7]) == 7
+    assert window_from_mri([1, 2, 3, 4, 5, 6, 7, 8, 9, 10]) == 8      # 80 % of ten values
+
+
+def test_window_of_periodic_keys_is_their_period():
+    """Six prompt keys re-attended every 37 steps and nothing else: every one of them has
+    MRI = 37 (Eq. 1; prompt entries start at TS = 0), so the histogram is a single spike and
+    W = 37."""
+    u = _scripted_unit(P=6, B=1000, W=1)
+    for t in range(1, 120):
+        act = np.zeros(len(u) + 1, dtype=bool)
+        if t % 37 == 0:
+            act[:6] = True
+        u.decode_step(t, np.zeros((1, 4)), np.zeros(4), np.zeros(4), act_override=act)
+    h = mri_histogram(u.MRI, 64)
+    assert h[37] == 6 and h[0] == len(u) - 6 and h.sum() == len(u)
+    assert window_from_mri(u.MRI) == 37
