@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="after the timed region, run one plain copy kernel of this many MiB "
                          "(a known traffic to scale hardware byte counters with)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="override the observation window W (1 = an eviction after every step, "
+                         "the schedule of the greedy methods the paper compares against)")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
     args = ap.parse_args()
@@ -141,6 +144,8 @@ def main():
     K = args.steps or cfg.steps
     if args.prompt_len >= 0:
         cfg = cfg.scaled(prompt_len=args.prompt_len, name="%s-prompt%d" % (cfg.name, args.prompt_len))
+    if args.window > 0:
+        cfg = cfg.scaled(window=args.window, name="%s-window%d" % (cfg.name, args.window))
     if args.no_evict:
         cfg = cfg.scaled(budget=cfg.prompt_len + K, name=cfg.name + "-fullkv")
     wl = Workload(cfg)
