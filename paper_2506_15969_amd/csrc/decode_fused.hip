@@ -329,7 +329,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     for (int j = 0; j < 4; ++j) {
       const int row = min(sub * 16 + 4 * j + g, n_old);
       const bf16_t *src = (row == n_old) ? k_new : kc + static_cast<size_t>(row) * D;
-      t.k[j] = *reinterpret_cast<const u32x4_t *>(src + c * 8);
+      t.k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src + c * 8));
     }
   };
   auto load_v = [&](SubTile &t, int it) {
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     for (int i = 0; i < 4; ++i) {
       const int row = min(sub * 16 + 4 * g + i, n_old);
       const bf16_t *src = (row == n_old) ? v_new : vc + static_cast<size_t>(row) * D;
-      t.v[i] = *reinterpret_cast<const u32x4_t *>(src + c * 8);
+      t.v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src + c * 8));
     }
   };
 
