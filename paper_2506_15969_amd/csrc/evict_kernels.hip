@@ -120,6 +120,7 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   __shared__ unsigned hist[256];
   __shared__ unsigned wave_tot[kSelWaves];
   __shared__ unsigned sel_bin, sel_rem, sel_cnt;
+  __shared__ unsigned long long and_k[2], or_k[2];
 
   const int tid = threadIdx.x;
   const int unit = blockIdx.x;
@@ -135,18 +136,39 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
         __double_as_longlong(mri_centric_score(a.t - ts[i], mri[i], a.score_flags)));
   __syncthreads();
 
-  // radix select of the k_keep-th largest key, most significant byte first
-  unsigned long long prefix = 0, mask = 0;
-  unsigned k_rem = static_cast<unsigned>(k_keep);
-  unsigned ties_total = 0;
-  for (int shift = 56; shift >= 0; shift -= 8) {
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
+  // Radix select of the k_keep-th largest key, most significant byte first.  Every pass also
+  // forms the AND and the OR of the keys still in play: when they agree, all those keys are
+  // the same value (the usual case: the threshold falls among the entries that were never
+  // re-activated, which all score exactly 0) and the remaining passes are skipped.
+  if (tid < 256) hist[tid] = 0;
+  if (tid < 2) { and_k[tid] = ~0ull; or_k[tid] = 0ull; }
+  __syncthreads();                                    // also: every key is in LDS
+  unsigned long long prefix = 0, mask = 0, thr = 0;
+  unsigned k_rem = static_cast<unsigned>(k_keep);     // kept among the keys still in play ...
+  unsigned ties_total = static_cast<unsigned>(n_cand);   // ... of which there are this many
+  bool all_equal = false;
+  for (int shift = 56, pass = 0; shift >= 0; shift -= 8, ++pass) {
+    const int pb = pass & 1;
+    unsigned long long and_acc = ~0ull, or_acc = 0ull;
     for (int i = tid; i < n_cand; i += kSelBlock) {
       const unsigned long long key = keys[i];
-      if ((key & mask) == prefix) atomicAdd(&hist[static_cast<unsigned>(key >> shift) & 255u], 1u);
+      if ((key & mask) == prefix) {
+        atomicAdd(&hist[static_cast<unsigned>(key >> shift) & 255u], 1u);
+        and_acc &= key;
+        or_acc |= key;
+      }
     }
+    for (int o = 32; o > 0; o >>= 1) {
+      and_acc &= __shfl_xor(and_acc, o);
+      or_acc |= __shfl_xor(or_acc, o);
+    }
+    if ((tid & 63) == 0) { atomicAnd(&and_k[pb], and_acc); atomicOr(&or_k[pb], or_acc); }
     __syncthreads();
+    if (and_k[pb] == or_k[pb]) {                      // the same for every thread of the block
+      thr = and_k[pb];
+      all_equal = true;
+      break;
+    }
     const unsigned bin = 255u - static_cast<unsigned>(tid);      // descending digit order
     const unsigned v = tid < 256 ? hist[bin] : 0u;
     unsigned total;
@@ -156,16 +178,17 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
       sel_rem = k_rem - above;
       sel_cnt = v;
     }
+    if (tid < 256) hist[tid] = 0;                     // for the next pass (the scan's barriers lie
+    if (tid == 0) { and_k[pb ^ 1] = ~0ull; or_k[pb ^ 1] = 0ull; }   // between the reads and this)
     __syncthreads();
     prefix |= static_cast<unsigned long long>(sel_bin) << shift;
     mask |= 255ull << shift;
     k_rem = sel_rem;
     ties_total = sel_cnt;
-    __syncthreads();
   }
-  // prefix is now the threshold key; k_rem of the ties_total entries equal to it are kept,
-  // the most recent ones (largest slots) first.
-  const unsigned long long thr = prefix;
+  if (!all_equal) thr = prefix;
+  // thr is the threshold key; k_rem of the ties_total entries equal to it are kept, the most
+  // recent ones (largest slots) first.
   const unsigned drop_ties = ties_total - k_rem;
 
   unsigned run_def = 0, run_tie = 0, n_moved = 0;
@@ -211,10 +234,10 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
 // Row parts are 256 bytes (16 lanes of 16 bytes; a whole row for bf16 with d = 128) or, for
 // shorter rows, 128 bytes.  A block of 1024 threads owns one part of every row of one unit and
 // walks the rows in tiles of (1024 / LPP) * U; loads and stores are marked non-temporal (every
-// byte is touched once: measured 14 % faster than plain ones); inside a tile every load completes before the
-// first store (a destination row may be another thread's source row), and because sources
-// never lie below their destinations and both grow with j, a tile's stores cannot touch what
-// a later tile still has to read.  The loads of the next tile are requested before this tile
+// byte is touched once: measured 14 % faster than plain ones); inside a tile every load
+// completes before the first store (a destination row may be another thread's source row),
+// and because sources never lie below their destinations and both grow with j, a tile's
+// stores cannot touch what a later tile still has to read.  The loads of the next tile are requested before this tile
 // is stored, so the block always has reads in flight.
 template <int U, int LPP>                      // LPP lanes of 16 bytes per row part
 __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs a, int row_bytes) {
