@@ -182,6 +182,20 @@ def test_threshold_is_inclusive_and_grouped_by_or():
     assert act.tolist() == [True, False, True, True]
 
 
+def test_threshold_on_the_oracles_own_weights():
+    """The same two rules on computed weights.  Head 0 has a zero query: its weights are exactly
+    1/4 over four entries, equal to alpha; head 1 puts everything on entry 0.  Inclusive test
+    and OR over the group: every entry is active (a strict test or an AND leaves only entry 0)."""
+    k = np.zeros((3, 4))
+    k[0, 0] = 3.0
+    u = OracleUnit(k, k, 2, 100, 1, alpha=0.25)
+    q = np.array([[0.0, 0, 0, 0], [40.0, 0, 0, 0]])
+    _, p, act = u.decode_step(1, q, np.zeros(4), np.zeros(4))
+    assert np.all(p[0] == 0.25) and p[1, 0] > 0.999 and np.all(p[1, 1:] < 1e-6)
+    assert act.tolist() == [True, True, True, True]
+    assert u.TS.tolist() == [1, 1, 1, 1] and u.MRI.tolist() == [1, 1, 1, 0]
+
+
 # ---------------------------------------------------------------- Eq. 4 against a library routine
 def test_budget_at_least_sequence_length_is_full_attention():
     rng = np.random.default_rng(3)
