@@ -47,6 +47,13 @@ extern "C" {
  * Sec. 4 item 2 as printed grows with MRI; the sentence introducing it and App. D describe a
  * term that falls with MRI.  Default is the printed formula; this bit selects the other reading. */
 #define LAZYEV_SCORE_H2_DECREASING 16
+/* Rank the candidates by the attention weight they received at the eviction's own step (largest
+ * over the query group) instead of Eq. 3: the rule of the current-attention methods the paper
+ * compares against (Sec. 2 (2); App. C "Baselines").  With window = 1 this is their per-step
+ * greedy eviction, with a larger window the same rule behind an observation window.  Replaces
+ * the H1 / H2 bits.  bf16, head_dim 128 only, and lazyev_evict must directly follow the
+ * lazyev_decode_step of the same layer (the weights of older calls are gone). */
+#define LAZYEV_SCORE_CURRENT_ATTENTION 32
 
 /* Largest number of eviction candidates (cache entries outside the last W) per unit that the
  * selection kernel holds in LDS.  A configuration whose budget or prompt is longer can still

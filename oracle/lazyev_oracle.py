@@ -13,6 +13,7 @@ What follows the paper, and where:
   * lagged eviction Top_{B-W}(I) united with the last W . Eq. 6, Algorithm 1
   * MRI distribution and the window chosen from it ...... Sec. 3 (Fig. 2(c)); Sec. 4
     "Observation Window"
+  * current-attention ranking as an alternative score ... Sec. 2 (2); Appendix C "Baselines"
   * greedy current-attention comparator ................. Appendix C "Baselines" (TOVA sentence)
 
 Readings taken where the paper is silent or inconsistent (each is also listed in the design
@@ -106,6 +107,7 @@ def two_sigmoid_neg_libm(x) -> np.ndarray:
 
 USE_H1 = 1
 USE_H2 = 2
+USE_CURRENT_ATTENTION = 32   # score = the step's own attention weight (the greedy baselines' rule)
 H2_DECREASING = 16      # H2 reflected: 1 - f(1/(MRI-1)), the reading under which Sec. 4 item 2's prose holds
 
 
@@ -201,6 +203,7 @@ class OracleUnit:
         self.t = 0
         self.n_activations = 0
         self.n_evict_events = 0
+        self.last_weight = np.zeros(self.P)          # max over the group of the last step's weights
 
     def __len__(self) -> int:
         return len(self.pos)
@@ -237,12 +240,16 @@ class OracleUnit:
 
         out, p = self.attention(q)
 
+        if p_override is not None:
+            pw = np.asarray(p_override).reshape(self.G, -1)
+            self.last_weight = pw.max(axis=0).astype(np.float64)
+        else:
+            self.last_weight = p.max(axis=0)
         if act_override is not None and not callable(act_override):
             act = np.asarray(act_override, dtype=bool)
         elif p_override is not None:
-            pw = np.asarray(p_override)
             thr = np.float32(self.alpha) if pw.dtype == np.float32 else np.float64(self.alpha)
-            act = (pw.reshape(self.G, -1) >= thr).any(axis=0)                        # R1, R5
+            act = (pw >= thr).any(axis=0)                                            # R1, R5
         else:
             act = (p >= self.alpha).any(axis=0)                                      # R1, R5, R6
         if callable(act_override):
@@ -260,6 +267,11 @@ class OracleUnit:
         return t % self.W == 0 and len(self) > self.B                                # R2
 
     def scores(self, t: int) -> np.ndarray:
+        if self.score_flags & USE_CURRENT_ATTENTION:
+            # the rule of the current-attention baselines (Sec. 2; App. C, TOVA): rank by the
+            # weight the entry received at this very step, largest over the query group
+            assert t == self.t and len(self.last_weight) == len(self)
+            return self.last_weight.copy()
         return mri_centric_score(t, self.TS, self.MRI, self.score_flags)
 
     def evict(self, t: int):

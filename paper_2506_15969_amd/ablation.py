@@ -31,12 +31,16 @@ VARIANTS = [
     ("w/o H1", binding.SCORE_H2),
     ("w/o H1 (H2 reflected)", binding.SCORE_H2 | binding.SCORE_H2_DECREASING),
     ("neither (sliding window)", 0),
+    # the rule of the current-attention baselines (Sec. 2 (2); App. C): rank by the weights of the
+    # eviction's own step; per step (window 1: greedy) and behind the workload's window
+    ("current attention, every step", binding.SCORE_CURRENT_ATTENTION, 1),
+    ("current attention, every W steps", binding.SCORE_CURRENT_ATTENTION),
 ]
 
 
-def _engine(cfg, wl, layer, budget, flags):
+def _engine(cfg, wl, layer, budget, flags, window=None):
     eng = binding.LazyEviction(1, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, budget,
-                               cfg.window, cfg.prompt_len, cfg.alpha, dtype=cfg.torch_dtype,
+                               window or cfg.window, cfg.prompt_len, cfg.alpha, dtype=cfg.torch_dtype,
                                score_flags=flags)
     if cfg.prompt_len:
         k, v = wl.prompt_kv(layer, device="cuda")
@@ -62,8 +66,11 @@ def run(cfg, layer=0, steps=None, gen_block=128, variants=VARIANTS):
     ref_norm = ref.float().norm(dim=-1).clamp_min(1e-30)
 
     rows = []
-    for name, flags in variants:
-        eng = _engine(cfg, wl, layer, cfg.budget, flags)
+    for name, flags, *rest in variants:
+        W = rest[0] if rest else cfg.window
+        if (flags & binding.SCORE_CURRENT_ATTENTION) and (cfg.dtype != "bf16" or d != 128):
+            continue                                 # that ranking exists for the bf16 shape only
+        eng = _engine(cfg, wl, layer, cfg.budget, flags, W)
         out = torch.empty((S, Hq, d), dtype=cfg.torch_dtype, device=dev)
         err_sum = torch.zeros((), dtype=torch.float64, device=dev)
         present = torch.ones((S, Hkv, P + steps), dtype=torch.bool, device=dev)
@@ -89,7 +96,7 @@ def run(cfg, layer=0, steps=None, gen_block=128, variants=VARIANTS):
                     present[:, :, :P + t] = False
                     present.scatter_(2, eng.pos[0, :, :, :n].long(), True)
         st = eng.stats()
-        old = wl.planted[wl.planted < P + steps - W]
+        old = wl.planted[wl.planted < P + steps - cfg.window]
         survive = (float(present[:, :, torch.as_tensor(old, device=dev)].float().mean())
                    if len(old) else float("nan"))
         rows.append(dict(variant=name, score_flags=flags,
@@ -114,9 +121,9 @@ def main():
         print(json.dumps(dict(config=a.config, steps=a.steps or cfg.steps, rows=rows)))
         return
     print(f"{a.config}: layer {a.layer}, {a.steps or cfg.steps} steps, budget {cfg.budget}, window {cfg.window}")
-    print(f"{'variant':28s} {'out_err':>9s} {'err@fire':>9s} {'recall':>8s} {'survive':>8s} {'evictions':>9s}")
+    print(f"{'variant':34s} {'out_err':>9s} {'err@fire':>9s} {'recall':>8s} {'survive':>8s} {'evictions':>9s}")
     for r in rows:
-        print(f"{r['variant']:28s} {r['out_err']:9.5f} {r['err_at_fire']:9.5f} {r['recall']:8.4f} {r['survive']:8.4f} {r['evictions']:9d}")
+        print(f"{r['variant']:34s} {r['out_err']:9.5f} {r['err_at_fire']:9.5f} {r['recall']:8.4f} {r['survive']:8.4f} {r['evictions']:9d}")
 
 
 if __name__ == "__main__":

@@ -21,6 +21,7 @@ OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16
+SCORE_CURRENT_ATTENTION = 32
 MAX_HIST_BINS = 8192
 MAX_CANDIDATES = 8192
 

@@ -131,9 +131,26 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
 
   // scores (non-negative doubles order like their bit patterns)
-  for (int i = tid; i < n_cand; i += kSelBlock)
-    keys[i] = static_cast<unsigned long long>(
-        __double_as_longlong(mri_centric_score(a.t - ts[i], mri[i], a.score_flags)));
+  if (a.score_flags & 32) {
+    // the weight each candidate received at this step, largest over the query group: the same
+    // fp32 expression the tracking uses, widened exactly
+    const float *lg = a.logits + static_cast<size_t>(unit) * a.p_stride * 8;
+    const float *st = a.stat + static_cast<size_t>(unit) * 16;
+    for (int i = tid; i < n_cand; i += kSelBlock) {
+      const float4 sa = *reinterpret_cast<const float4 *>(lg + static_cast<size_t>(i) * 8);
+      const float4 sb = *reinterpret_cast<const float4 *>(lg + static_cast<size_t>(i) * 8 + 4);
+      const float sv[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+      float best = 0.f;
+#pragma unroll
+      for (int h = 0; h < 8; ++h)
+        if (h < a.group) best = fmaxf(best, __expf(sv[h] - st[2 * h]) * st[2 * h + 1]);
+      keys[i] = static_cast<unsigned long long>(__double_as_longlong(static_cast<double>(best)));
+    }
+  } else {
+    for (int i = tid; i < n_cand; i += kSelBlock)
+      keys[i] = static_cast<unsigned long long>(
+          __double_as_longlong(mri_centric_score(a.t - ts[i], mri[i], a.score_flags)));
+  }
   __syncthreads();
 
   // Radix select of the k_keep-th largest key, most significant byte first.  Every pass also
@@ -303,6 +320,8 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int n_cand = a.n - a.window;
   if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
+  if ((a.score_flags & 32) && (!a.logits || !a.stat || a.group < 1 || a.group > 8 || a.p_stride < a.n))
+    return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
   if (ev) (void)hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL(evict_select_kernel, dim3(a.units), dim3(kSelBlock), lds, stream, a);

@@ -75,6 +75,9 @@ struct EvictArgs {
   int32_t *ts, *mri, *pos;
   Workspace ws;
   unsigned long long *rows_moved;   // this layer's [units] counters
+  // score = the last call's attention weights (score_flags bit 32): its logits and statistics
+  const float *logits, *stat;
+  int32_t group, p_stride;
 };
 
 // `ev`, when not null, points at three events recorded before the first kernel, between the two

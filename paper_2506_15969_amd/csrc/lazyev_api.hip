@@ -31,6 +31,11 @@ struct lazyev_ctx {
   // fused kernel: the call whose tracking has not been applied yet, and the buffer pair in turn
   lazyev::TrackArgs pend;
   int cur_buf;
+  // the last decode call, if the fused kernel ran it: its logits and statistics are still in
+  // the workspace (what an eviction that ranks by that step's weights reads)
+  int32_t last_layer;
+  const float *last_logits, *last_stat;
+  int32_t last_p_stride;
   // profiling aid: event triples of the calls that were armed, kind 0 = decode, 1 = evict
   int32_t prof_armed;
   struct Timed { int kind; hipEvent_t ev[3]; };
@@ -54,7 +59,12 @@ bool config_ok(const lazyev_config *c) {
   if (c->head_dim != 64 && c->head_dim != 128) return false;
   if (c->window < 1 || c->budget <= c->window || c->prompt_len < 0) return false;
   if (c->dtype != LAZYEV_DTYPE_FP32 && c->dtype != LAZYEV_DTYPE_BF16) return false;
-  if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2 | LAZYEV_SCORE_H2_DECREASING)) return false;
+  if (c->score_flags & ~(LAZYEV_SCORE_H1 | LAZYEV_SCORE_H2 | LAZYEV_SCORE_H2_DECREASING |
+                         LAZYEV_SCORE_CURRENT_ATTENTION))
+    return false;
+  if ((c->score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) &&
+      (c->dtype != LAZYEV_DTYPE_BF16 || c->head_dim != 128))
+    return false;
   if (!(c->alpha >= 0.0f) || !(c->softmax_scale >= 0.0f)) return false;   // also rejects NaN
   const long long cap = static_cast<long long>(c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
   if (cap > (1ll << 20)) return false;
@@ -173,6 +183,9 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.stat[1] = ctx->ws.stat[0] + static_cast<size_t>(cfg->batch) * cfg->n_kv_heads * 16;
   std::memset(&ctx->pend, 0, sizeof(ctx->pend));
   ctx->cur_buf = 0;
+  ctx->last_layer = -1;
+  ctx->last_logits = ctx->last_stat = nullptr;
+  ctx->last_p_stride = 0;
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
@@ -303,7 +316,9 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   if (e != hipSuccess) return fail_hip(ctx, e);
   ctx->len[layer] = n_old + 1;
   ctx->last_step[layer] = t;
+  ctx->last_layer = kind == 4 ? layer : -1;
   if (kind == 4) {
+    ctx->last_logits = a.logits_out; ctx->last_stat = a.stat_out; ctx->last_p_stride = a.p_stride;
     lazyev::TrackArgs &k = ctx->pend;              // this call's tracking: with the next launch
     std::memset(&k, 0, sizeof(k));
     k.valid = 1;
@@ -347,6 +362,12 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
   a.rows_moved = ctx->ws.rows_moved + static_cast<size_t>(layer) * ctx->units;
+  if (c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) {
+    // the weights of step t: only there if this layer's decode call was the last one
+    if (ctx->last_layer != layer || !ctx->last_logits) return LAZYEV_EINVAL;
+    a.logits = ctx->last_logits; a.stat = ctx->last_stat;
+    a.group = ctx->group; a.p_stride = ctx->last_p_stride;
+  }
   const hipError_t ef = flush_tracking(ctx);       // scores use TS and MRI of step t (Alg. 1 order)
   if (ef != hipSuccess) return fail_hip(ctx, ef);
   const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));
@@ -355,6 +376,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   ctx->n_evict_events[layer] += 1;
   ctx->n_evicted[layer] += n - c.budget;
   ctx->len[layer] = c.budget;
+  ctx->last_layer = -1;                            // the stored logits no longer match the slots
   return LAZYEV_OK;
 }
 

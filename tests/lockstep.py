@@ -40,6 +40,7 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
                       of the threshold (counted; the oracle then takes the library's decision).
     mode "oracle_p":  the oracle's weights, rounded to fp32, are thresholded by both.
     mode "synthetic": seeded random weights are thresholded by both.
+    mode "gpu_p":     the library's exported weights are thresholded (and ranked) by the oracle.
     Returns a dict of counters.  Raises AssertionError on any mismatch.
     """
     wl = Workload(cfg)
@@ -72,7 +73,23 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
                 q, kn, vn = (x[i] for x in gpu_in[l])
                 mine = [u for u in units if u[0] == l]
                 n1 = len(orc[mine[0]]) + 1
-                if mode == "e2e":
+                if mode == "gpu_p":
+                    # the oracle thresholds (and, where the score is the step's own weight,
+                    # ranks by) the library's exported fp32 weights: everything must be exact
+                    eng.decode_step(l, t, q, kn, vn, out, p_out=p_out)
+                    o_gpu = out.float().cpu().numpy().astype(np.float64)
+                    p_gpu = p_out.cpu().numpy()
+                    for u in mine:
+                        _, s, h = u
+                        rows = slice(h * G, (h + 1) * G)
+                        pg = np.ascontiguousarray(p_gpu[s, rows, :n1])
+                        cq, ck, cv = (x[i, 0] for x in cpu_in[u])
+                        o, p, act = orc[u].decode_step(t, cq.double().numpy(), ck[0].double().numpy(),
+                                                       cv[0].double().numpy(), p_override=pg)
+                        _compare_out(o_gpu[s, rows], o, tol, stat, (u, t))
+                        assert np.all(np.abs(pg - p) <= tol * np.maximum(p, 1e-6) + 1e-9), (u, t)
+                        stat["decisions"] += n1
+                elif mode == "e2e":
                     eng.decode_step(l, t, q, kn, vn, out, p_out=p_out)
                     o_gpu = out.float().cpu().numpy().astype(np.float64)
                     p_gpu = p_out.cpu().numpy()

@@ -39,7 +39,7 @@ def test_capacity_and_workspace(lazyev_lib):
 
 
 @pytest.mark.parametrize("field,value", [("n_q_heads", 7), ("head_dim", 96), ("window", 0),
-                                         ("budget", 8), ("dtype", 5), ("score_flags", 8),
+                                         ("budget", 8), ("dtype", 5), ("score_flags", 8), ("score_flags", 64),
                                          ("n_layers", 0), ("alpha", float("nan")),
                                          ("n_q_heads", 32), ("prompt_len", -1),
                                          ("budget", 2_000_000)])
@@ -92,3 +92,14 @@ def test_window_from_histogram_is_the_quantile(lazyev_lib):
     assert lazyev_lib.window_from_histogram([5, 0, 0, 0]) == 0
     assert lazyev_lib.window_from_histogram([0, 0, 3, 1], 0.8) == 3
     assert lazyev_lib.lib.lazyev_mri_histogram(None, 0, 16, None) == lazyev_lib.EINVAL
+
+
+def test_current_attention_ranking_needs_the_bf16_shape(lazyev_lib):
+    b = lazyev_lib
+    cfg = _good(b)
+    cfg.score_flags = b.SCORE_CURRENT_ATTENTION
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 72                   # bf16, head_dim 128: accepted
+    cfg.dtype = b.DTYPE_FP32
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 0
+    cfg.dtype, cfg.head_dim = b.DTYPE_BF16, 64
+    assert b.lib.lazyev_capacity(C.byref(cfg)) == 0

@@ -117,6 +117,40 @@ def test_mri_histogram_matches_the_oracle(lazyev_lib):
     assert stat["gpu_mri_hist_layer"][0] == stat["oracle_mri_hist_layer"][0]
 
 
+@pytest.mark.parametrize("window", [1, 16])
+def test_current_attention_ranking(lazyev_lib, window):
+    """Score = the weight an entry received at the eviction's own step (the greedy baselines'
+    rule): per step with W = 1, behind an observation window with W = 16.  The oracle ranks and
+    thresholds the library's exported fp32 weights, so survivors and statistics are exact."""
+    from lockstep import run_lockstep
+    cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=150, steps=120, budget=128, window=window)
+    stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="gpu_p",
+                        score_flags=lazyev_lib.SCORE_CURRENT_ATTENTION)
+    _report("current attention, W=%d" % window, stat)
+    assert stat["evictions"] == 120 // window            # the prompt is longer than the budget
+
+
+def test_current_attention_ranking_needs_the_call_that_made_the_weights(lazyev_lib):
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=2, batch=1, prompt_len=40, steps=4, budget=32, window=1)
+    wl = Workload(cfg)
+    eng = make_engine(lazyev_lib, cfg, wl, score_flags=lazyev_lib.SCORE_CURRENT_ATTENTION)
+    out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+    ins = [wl.step_inputs(l, 1, 3, device="cuda") for l in range(2)]
+    for l in range(2):
+        eng.decode_step(l, 1, ins[l][0][0], ins[l][1][0], ins[l][2][0], out)
+    with pytest.raises(lazyev_lib.LazyevError):           # layer 0's weights have been overwritten
+        eng.evict(0, 1)
+    assert eng.evict(1, 1) == 9                           # 41 entries -> 32
+    assert eng.evict(1, 1) == 0                           # nothing is due any more
+    eng.set_variant(2)                                    # a kernel that keeps no logits
+    eng.decode_step(1, 2, ins[1][0][1], ins[1][1][1], ins[1][2][1], out)
+    with pytest.raises(lazyev_lib.LazyevError):
+        eng.evict(1, 2)
+    assert eng.stats()["len"] == [41, 33]
+
+
 def test_empty_prompt_and_window_of_one(lazyev_lib):
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg1"].scaled(prompt_len=0, planted_count_in_prompt=0, steps=90, budget=40,

@@ -50,6 +50,8 @@ MUTANTS = [
     ("MRI not moved with its token", 'for name in ("K", "V", "pos", "TS", "MRI"):', 'for name in ("K", "V", "pos", "TS"):'),
     ("score from stale TS", "dt = (t - ts).astype(np.float64)", "dt = (t - 1 - ts).astype(np.float64)"),
     ("reflected H2 not reflected", "h2 = np.where(mri >= 1, 1.0 - h2, 0.0)", "h2 = np.where(mri >= 1, h2, 0.0)"),
+    ("current attention: smallest over the group", "self.last_weight = p.max(axis=0)", "self.last_weight = p.min(axis=0)"),
+    ("current attention: injected weights ignored", "            self.last_weight = pw.max(axis=0).astype(np.float64)\n", "            self.last_weight = p.max(axis=0)\n"),
     ("histogram without overflow bin", "hist[min(int(m), n_bins - 1)] += 1", "hist[int(m) % n_bins] += 1"),
     ("window quantile over all entries", "    v = v[v >= 1]\n", ""),
 ]
@@ -77,7 +79,7 @@ def _load(source, tag):
 
 
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]
-SWAPPED = ["H2_DECREASING", "USE_H1", "USE_H2", "GreedyUnit", "LazyEvictionOracle", "OracleUnit",
+SWAPPED = ["H2_DECREASING", "USE_CURRENT_ATTENTION", "USE_H1", "USE_H2", "GreedyUnit", "LazyEvictionOracle", "OracleUnit",
            "mri_histogram", "window_from_mri", "mri_centric_score", "select_survivors",
            "two_sigmoid_neg", "two_sigmoid_neg_libm"]
 

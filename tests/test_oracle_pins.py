@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle.lazyev_oracle import (H2_DECREASING, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
+from oracle.lazyev_oracle import (H2_DECREASING, USE_CURRENT_ATTENTION, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
                                   mri_histogram, window_from_mri,
                                   mri_centric_score, select_survivors, two_sigmoid_neg,
                                   two_sigmoid_neg_libm)
@@ -402,3 +402,35 @@ def test_window_of_periodic_keys_is_their_period():
     h = mri_histogram(u.MRI, 64)
     assert h[37] == 6 and h[0] == len(u) - 6 and h.sum() == len(u)
     assert window_from_mri(u.MRI) == 37
+
+
+# ---------------------------------------------------------------- current-attention ranking
+def test_current_attention_with_window_one_is_the_greedy_comparator():
+    """Ranking by the step's own weights and evicting after every step (W = 1) is the greedy
+    rule (App. C, TOVA): the general eviction path and the separately written comparator must
+    keep the same entries at every step, also when the prompt is longer than the budget."""
+    rng = np.random.default_rng(3)
+    P, d, G, B = 40, 8, 2, 24
+    k, v = rng.normal(size=(P, d)), rng.normal(size=(P, d))
+    a = OracleUnit(k, v, G, B, 1, alpha=0.05, score_flags=USE_CURRENT_ATTENTION)
+    g = GreedyUnit(k, v, G, B)
+    for t in range(1, 120):
+        q, kn, vn = rng.normal(size=(G, d)) * 3, rng.normal(size=d), rng.normal(size=d)
+        oa, _, _ = a.decode_step(t, q, kn, vn)
+        og = g.decode_step(t, q, kn, vn)
+        a.evict(t)
+        assert np.allclose(oa, og) and a.pos.tolist() == g.pos and len(a) == B
+
+
+def test_current_attention_behind_a_window_by_hand():
+    """Five prompt entries, budget 4, window 2: at t = 2 the candidates are the five prompt
+    entries, the weights of step 2 decide, the two newest entries stay whatever they got."""
+    k = np.zeros((5, 4))
+    u = OracleUnit(k, k, 1, 4, 2, alpha=0.5, score_flags=USE_CURRENT_ATTENTION)
+    w1 = np.array([[0.9, 0.02, 0.02, 0.02, 0.02, 0.02]])
+    w2 = np.array([[0.05, 0.3, 0.01, 0.2, 0.3, 0.04, 0.1]])
+    u.decode_step(1, np.zeros((1, 4)), np.zeros(4), np.zeros(4), p_override=w1)
+    assert u.evict(1) == []                               # t is not a multiple of W
+    u.decode_step(2, np.zeros((1, 4)), np.zeros(4), np.zeros(4), p_override=w2)
+    assert u.evict(2) == [0, 2, 3]                        # keeps 4 (tie with 1: the newer) and 1
+    assert u.pos.tolist() == [1, 4, 5, 6]
