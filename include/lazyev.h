@@ -146,6 +146,31 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /
  * *out.  Errors: EINVAL, EHIP. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
 
+/* Per-sequence timing, for a batch whose sequences do not start together (the paper decodes one
+ * sequence at a time and says nothing about batches; what follows applies Alg. 1 to every
+ * sequence on its own clock).  Until the first of these two calls every sequence has the
+ * configuration's prompt_len and starts at step 1.
+ *
+ * lazyev_admit: batch slot `seq` is taken by a sequence whose prompt_len K/V rows the caller
+ *   has written (or will have written, on the context's stream, before the sequence's first
+ *   step) to entries 0..prompt_len-1 of the slot's units in every layer.  Its first decode step
+ *   is the call with t = t0 + 1; every quantity of Alg. 1 then runs on the sequence's local
+ *   step t - t0: TS, the W-step schedule, pos = prompt_len + local step - 1.  Enqueues the
+ *   state of lazyev_init for the slot in every layer.  A slot that is already taken starts over.
+ *   Needs prompt_len <= capacity - window and t0 >= every layer's last decode step.
+ * lazyev_retire: the slot is empty from now on: its units take no part in later calls (their
+ *   output rows are not written) until it is admitted again.
+ *
+ * With per-sequence timing in use: lazyev_decode_step skips sequences whose first step lies
+ * ahead; lazyev_evict runs for the sequences whose local step is a multiple of W and whose cache
+ * exceeds the budget (n_evicted: the largest number removed from one unit) and must be called
+ * after every step at which that holds for some sequence (the next lazyev_decode_step of the
+ * layer returns ECAPACITY otherwise); lazyev_stats reports the longest cache of each layer.
+ * bf16, head_dim 128 and the default attention kernel only.
+ * Both apply pending tracking first.  Errors: EINVAL, EHIP. */
+int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0);
+int lazyev_retire(lazyev_ctx *ctx, int32_t seq);
+
 /* Distribution of the Maximum Recurrence Interval (Eq. 1) over the cached entries, the
  * statistic from which the observation window W is chosen offline (Sec. 3, Fig. 2(c); Sec. 4
  * "Observation Window": W = the MRI below which 80 % of the tokens fall; run it on a context

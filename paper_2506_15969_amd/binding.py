@@ -44,7 +44,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
-           "lazyev_evict", "lazyev_stats", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
+           "lazyev_evict", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
            "lazyev_event_overhead",
@@ -63,6 +63,10 @@ lib.lazyev_evict.restype = C.c_int
 lib.lazyev_evict.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_stats.restype = C.c_int
 lib.lazyev_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
+lib.lazyev_admit.restype = C.c_int
+lib.lazyev_admit.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+lib.lazyev_retire.restype = C.c_int
+lib.lazyev_retire.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_mri_histogram.restype = C.c_int
 lib.lazyev_mri_histogram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
 lib.lazyev_score_pairs.restype = C.c_int
@@ -213,6 +217,17 @@ class LazyEviction:
                                                          else C.c_int64)) for k, v in bufs.items()})
         _check(lib.lazyev_stats(self._ctx, C.byref(st)), "lazyev_stats")
         return {k: list(v) for k, v in bufs.items()}
+
+    def admit(self, seq: int, prompt_len: int, t0: int, k=None, v=None):
+        """lazyev_admit.  k, v [L,Hkv,prompt_len,d] (optional): the prompt rows, copied into the
+        slot's units of every layer first."""
+        if k is not None:
+            self.k_cache[:, seq, :, :prompt_len].copy_(k)
+            self.v_cache[:, seq, :, :prompt_len].copy_(v)
+        _check(lib.lazyev_admit(self._ctx, seq, prompt_len, t0), "lazyev_admit")
+
+    def retire(self, seq: int):
+        _check(lib.lazyev_retire(self._ctx, seq), "lazyev_retire")
 
     def mri_histogram(self, layer: int = -1, n_bins: int = MAX_HIST_BINS):
         """lazyev_mri_histogram: counts of cached entries by MRI (last bin: MRI >= n_bins - 1)

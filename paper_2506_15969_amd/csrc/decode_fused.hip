@@ -160,6 +160,20 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
   return n_act;
 }
 
+// With per-sequence timing: the call's arguments as they hold for one unit (its own cache length,
+// local step and prompt length).  False: the unit's sequence takes no part in that call.
+__device__ __forceinline__ bool track_for_unit(const TrackArgs &k, int unit, TrackArgs &ku) {
+  ku = k;
+  if (!k.slots.prompt_len) return true;
+  const int seq = unit / k.n_kv_heads;
+  const int32_t P = k.slots.prompt_len[seq], tau = k.t - k.slots.t0[seq];
+  if (P < 0 || tau < 1) return false;
+  ku.n_old = slot_n_old(P, tau, k.slots.budget, k.slots.window);
+  ku.t = tau;
+  ku.prompt_len = P;
+  return true;
+}
+
 __device__ __forceinline__ void track_stats(const TrackArgs &k, int unit, float (&m)[kHeadPad],
                                             float (&invl)[kHeadPad]) {
   const float *st = k.stat + static_cast<size_t>(unit) * (2 * kHeadPad);
@@ -181,9 +195,11 @@ __device__ void track_count(const TrackArgs &k, int unit, int part, unsigned n_a
 }
 
 // Tracking alone (lazyev_evict, lazyev_stats, or a caller that wants the weights at once).
-__global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k, int n_parts) {
+__global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, int n_parts) {
   __shared__ unsigned cnt_lds[kWaves];
   const int unit = blockIdx.x / n_parts, part = blockIdx.x % n_parts;
+  TrackArgs k;
+  if (!track_for_unit(k_all, unit, k)) return;
   float m[kHeadPad], invl[kHeadPad];
   track_stats(k, unit, m, invl);
   unsigned n_act = 0;
@@ -270,9 +286,10 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   if (static_cast<int>(blockIdx.x) >= n_split * a.batch * a.n_kv_heads) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
-    const TrackArgs &k = a.track;
     const int tb = blockIdx.x - n_split * a.batch * a.n_kv_heads;
     const int unit = tb / n_split, part = tb % n_split;
+    TrackArgs k;
+    if (!track_for_unit(a.track, unit, k)) return;
     float m[kHeadPad], invl[kHeadPad];
     track_stats(k, unit, m, invl);
     unsigned n_act = 0;
@@ -291,7 +308,13 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   const int unit = blockIdx.x / n_split, split = blockIdx.x % n_split;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int hc = min(c, G - 1);
-  const int n_old = a.n_old, n1 = a.n_old + 1;
+  int n_old = a.n_old;
+  if (a.slots.prompt_len) {                        // per-sequence timing: this unit's own length
+    const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
+    if (P < 0 || tau < 1) return;                  // the whole unit sits this call out
+    n_old = slot_n_old(P, tau, a.slots.budget, a.slots.window);
+  }
+  const int n1 = n_old + 1;
   const int n_sub = (n1 + 15) >> 4;
   const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
 

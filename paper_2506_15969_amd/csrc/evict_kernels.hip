@@ -82,6 +82,43 @@ __global__ void mri_histogram_kernel(const int32_t *mri, int64_t n_units, int32_
   if (b > 0) atomicAdd(&hist[b], 1ull);
 }
 
+__global__ void mri_histogram_slots_kernel(const int32_t *mri, int64_t n_units, int32_t capacity,
+                                           int32_t n_kv_heads, const int32_t *seq_len, int32_t n_max,
+                                           int32_t n_bins, unsigned long long *hist) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  int32_t b = -1;
+  if (i < n_units * n_max) {
+    const int64_t unit = i / n_max;
+    const int32_t slot = static_cast<int32_t>(i % n_max);
+    if (slot < seq_len[unit / n_kv_heads]) {
+      const int32_t m = mri[unit * capacity + slot];
+      b = m < n_bins - 1 ? m : n_bins - 1;
+    }
+  }
+  const unsigned long long zeros = __builtin_amdgcn_ballot_w64(b == 0);
+  if (zeros != 0 && (threadIdx.x & 63) == 0)
+    atomicAdd(&hist[0], static_cast<unsigned long long>(__builtin_popcountll(zeros)));
+  if (b > 0) atomicAdd(&hist[b], 1ull);
+}
+
+// A sequence starts over in its slot: the state of lazyev_init for its units in every layer,
+// and its timing record.
+__global__ void init_slot_kernel(int32_t *ts, int32_t *mri, int32_t *pos, int32_t n_layers,
+                                 int32_t batch, int32_t n_kv_heads, int32_t capacity, int32_t seq,
+                                 int32_t prompt_len, int32_t *dev_prompt_len, int32_t *dev_t0,
+                                 int32_t t0) {
+  const int64_t per_layer = static_cast<int64_t>(n_kv_heads) * capacity;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i == 0) { dev_prompt_len[seq] = prompt_len; dev_t0[seq] = t0; }
+  if (i >= n_layers * per_layer) return;
+  const int64_t layer = i / per_layer, r = i % per_layer;
+  const int64_t at = ((layer * batch + seq) * n_kv_heads) * capacity + r;
+  const int32_t slot = static_cast<int32_t>(r % capacity);
+  ts[at] = 0;
+  mri[at] = 0;
+  pos[at] = slot < prompt_len ? slot : -1;
+}
+
 __global__ void init_state_kernel(int32_t *ts, int32_t *mri, int32_t *pos, int64_t total,
                                   int32_t capacity, int32_t prompt_len) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -124,7 +161,16 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
 
   const int tid = threadIdx.x;
   const int unit = blockIdx.x;
-  const int n = a.n, n_cand = a.n - a.window, k_keep = a.budget - a.window;
+  int n = a.n, t = a.t;
+  if (a.slots.prompt_len) {                        // per-sequence timing: is this unit's eviction due?
+    const int seq = unit / a.n_kv_heads;
+    const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
+    if (P < 0 || tau < 1 || tau % a.window != 0) return;
+    n = slot_n_old(P, tau, a.budget, a.window) + 1;
+    if (n <= a.budget) return;
+    t = tau;
+  }
+  const int n_cand = n - a.window, k_keep = a.budget - a.window;
   int32_t *ts = a.ts + static_cast<size_t>(unit) * a.capacity;
   int32_t *mri = a.mri + static_cast<size_t>(unit) * a.capacity;
   int32_t *pos = a.pos + static_cast<size_t>(unit) * a.capacity;
@@ -149,7 +195,7 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   } else {
     for (int i = tid; i < n_cand; i += kSelBlock)
       keys[i] = static_cast<unsigned long long>(
-          __double_as_longlong(mri_centric_score(a.t - ts[i], mri[i], a.score_flags)));
+          __double_as_longlong(mri_centric_score(t - ts[i], mri[i], a.score_flags)));
   }
   __syncthreads();
 
@@ -261,6 +307,13 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
   constexpr int ROWS = kMoveBlock / LPP;       // rows per block load
   const int tid = threadIdx.x;
   const int part = blockIdx.x, unit = blockIdx.z;
+  if (a.slots.prompt_len) {                        // only units whose eviction was due have a gather list
+    const int seq = unit / a.n_kv_heads;
+    const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
+    if (P < 0 || tau < 1 || tau % a.window != 0 ||
+        slot_n_old(P, tau, a.budget, a.window) + 1 <= a.budget)
+      return;
+  }
   char *slab = static_cast<char *>(blockIdx.y == 0 ? a.k_cache : a.v_cache) +
                static_cast<size_t>(unit) * a.capacity * row_bytes + part * (LPP * 16) + (tid % LPP) * 16;
   const int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
@@ -320,6 +373,8 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int n_cand = a.n - a.window;
   if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
+  if (a.slots.prompt_len && (!a.slots.t0 || a.n_kv_heads < 1 || a.units % a.n_kv_heads != 0))
+    return hipErrorInvalidValue;
   if ((a.score_flags & 32) && (!a.logits || !a.stat || a.group < 1 || a.group > 8 || a.p_stride < a.n))
     return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
@@ -357,6 +412,31 @@ hipError_t launch_mri_histogram(const int32_t *mri, int64_t n_units, int32_t cap
   const unsigned blocks = static_cast<unsigned>((n_units * n + 255) / 256);
   hipLaunchKernelGGL(mri_histogram_kernel, dim3(blocks), dim3(256), 0, stream, mri, n_units,
                      capacity, n, n_bins, hist);
+  return hipGetLastError();
+}
+
+hipError_t launch_mri_histogram_slots(const int32_t *mri, int64_t n_units, int32_t capacity,
+                                      int32_t n_kv_heads, const int32_t *seq_len, int32_t n_max,
+                                      int32_t n_bins, unsigned long long *hist, hipStream_t stream) {
+  if (n_units <= 0 || n_max <= 0) return hipSuccess;
+  if (n_max > capacity || n_bins < 2 || !seq_len || n_kv_heads < 1) return hipErrorInvalidValue;
+  const unsigned blocks = static_cast<unsigned>((n_units * n_max + 255) / 256);
+  hipLaunchKernelGGL(mri_histogram_slots_kernel, dim3(blocks), dim3(256), 0, stream, mri, n_units,
+                     capacity, n_kv_heads, seq_len, n_max, n_bins, hist);
+  return hipGetLastError();
+}
+
+hipError_t launch_init_slot(int32_t *ts, int32_t *mri, int32_t *pos, int32_t n_layers, int32_t batch,
+                            int32_t n_kv_heads, int32_t capacity, int32_t seq, int32_t prompt_len,
+                            int32_t *dev_prompt_len, int32_t *dev_t0, int32_t t0, hipStream_t stream) {
+  if (seq < 0 || seq >= batch || prompt_len > capacity || !dev_prompt_len || !dev_t0)
+    return hipErrorInvalidValue;
+  // prompt_len < 0 empties the slot: only the timing record changes
+  const int64_t total = prompt_len < 0 ? 1 : static_cast<int64_t>(n_layers) * n_kv_heads * capacity;
+  const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
+  hipLaunchKernelGGL(init_slot_kernel, dim3(blocks), dim3(256), 0, stream, ts, mri, pos,
+                     prompt_len < 0 ? 0 : n_layers, batch, n_kv_heads, capacity, seq, prompt_len,
+                     dev_prompt_len, dev_t0, t0);
   return hipGetLastError();
 }
 

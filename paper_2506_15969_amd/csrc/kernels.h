@@ -22,6 +22,27 @@ struct Workspace {
   unsigned long long *hist;         // [LAZYEV_MAX_HIST_BINS]  MRI histogram under construction
 };
 
+// Per-sequence timing.  Sequence s entered with prompt_len[s] cached rows (prompt_len[s] < 0: the
+// slot is empty) and takes its first decode step at global step t0[s] + 1; its local step is
+// tau = t - t0[s].  Null pointers: every sequence has the call's own n_old / t / prompt_len.
+struct Slots {
+  const int32_t *prompt_len, *t0;
+  int32_t budget, window;
+};
+
+// Entries a sequence holds before the append of its local step tau >= 1, with every due
+// eviction applied (Sec. 4: one is due after local step e when e % W == 0 and more than B
+// entries are cached; it leaves exactly B).
+__host__ __device__ inline int32_t slot_n_old(int32_t prompt_len, int32_t tau, int32_t budget,
+                                              int32_t window) {
+  // first local step after which an eviction fires
+  const int32_t first = prompt_len > budget
+                            ? window
+                            : window * ((budget - prompt_len + 1 + window - 1) / window);
+  const int32_t last = window * ((tau - 1) / window);     // latest multiple of W before step tau
+  return last >= first ? budget + (tau - 1 - last) : prompt_len + tau - 1;
+}
+
 // Tracking of one finished decode call (Alg. 1 first loop, Eq. 1) from its stored logits and
 // softmax statistics; the fused kernel runs it one call late.
 struct TrackArgs {
@@ -35,6 +56,7 @@ struct TrackArgs {
   float *p_out;
   const float *p_override;
   unsigned long long *activation_counter;   // the call's layer
+  Slots slots;                      // with slots: n_old is the largest of the sequences', t global
 };
 
 struct DecodeArgs {
@@ -63,6 +85,7 @@ struct DecodeArgs {
   // fused kernel: where this call's logits and statistics go, and the previous call to track
   float *logits_out, *stat_out;
   TrackArgs track;
+  Slots slots;                              // with slots: n_old is the largest of the sequences', t global
 };
 
 struct EvictArgs {
@@ -78,6 +101,8 @@ struct EvictArgs {
   // score = the last call's attention weights (score_flags bit 32): its logits and statistics
   const float *logits, *stat;
   int32_t group, p_stride;
+  int32_t n_kv_heads;
+  Slots slots;            // with slots: n is the largest of the due sequences', t global
 };
 
 // `ev`, when not null, points at three events recorded before the first kernel, between the two
@@ -96,8 +121,16 @@ size_t decode_unit_stage_offset(int group, int lds_stride);
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
                              int32_t capacity, int32_t prompt_len, hipStream_t stream);
+// One sequence starts over: TS = 0, MRI = 0, pos = i for its first prompt_len entries in every layer.
+hipError_t launch_init_slot(int32_t *ts, int32_t *mri, int32_t *pos, int32_t n_layers, int32_t batch,
+                            int32_t n_kv_heads, int32_t capacity, int32_t seq, int32_t prompt_len,
+                            int32_t *dev_prompt_len, int32_t *dev_t0, int32_t t0, hipStream_t stream);
 hipError_t launch_mri_histogram(const int32_t *mri, int64_t n_units, int32_t capacity, int32_t n,
                                 int32_t n_bins, unsigned long long *hist, hipStream_t stream);
+// seq_len (device, [batch]): entries of each sequence, used instead of n when not null
+hipError_t launch_mri_histogram_slots(const int32_t *mri, int64_t n_units, int32_t capacity,
+                                      int32_t n_kv_heads, const int32_t *seq_len, int32_t n_max,
+                                      int32_t n_bins, unsigned long long *hist, hipStream_t stream);
 hipError_t launch_score_pairs(const int32_t *dt, const int32_t *mri, double *score, int64_t n,
                               int32_t flags, hipStream_t stream);
 

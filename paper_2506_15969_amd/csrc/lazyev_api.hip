@@ -36,6 +36,13 @@ struct lazyev_ctx {
   int32_t last_layer;
   const float *last_logits, *last_stat;
   int32_t last_p_stride;
+  // per-sequence timing (lazyev_admit / lazyev_retire): prompt length (-1: empty slot) and the
+  // global step before each sequence's first one; device copies in the workspace.  Off until
+  // the first admit or retire: until then every sequence has the configuration's prompt, t0 = 0.
+  bool slots_on;
+  std::vector<int32_t> slot_prompt, slot_t0;
+  int32_t *dev_slot_prompt, *dev_slot_t0, *dev_seq_len;
+  std::vector<int32_t> evict_applied;              // per layer: last step whose due eviction ran
   // profiling aid: event triples of the calls that were armed, kind 0 = decode, 1 = evict
   int32_t prof_armed;
   struct Timed { int kind; hipEvent_t ev[3]; };
@@ -77,7 +84,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, hist, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, hist, slots, total;
   int32_t n_split_max;
 };
 
@@ -101,6 +108,7 @@ Layout layout_of(const lazyev_config *c) {
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
   l.hist = off; off = align_up(off + LAZYEV_MAX_HIST_BINS * sizeof(unsigned long long));
+  l.slots = off; off = align_up(off + 3 * static_cast<size_t>(c->batch) * sizeof(int32_t));
   l.total = off;
   return l;
 }
@@ -129,6 +137,44 @@ void drop_events(lazyev_ctx *ctx) {
 int fail_hip(lazyev_ctx *ctx, hipError_t e) {
   ctx->last_hip_error = static_cast<int>(e);
   return LAZYEV_EHIP;
+}
+
+// ---- per-sequence timing
+lazyev::Slots slots_of(const lazyev_ctx *ctx) {
+  lazyev::Slots sl;
+  sl.prompt_len = ctx->slots_on ? ctx->dev_slot_prompt : nullptr;
+  sl.t0 = ctx->slots_on ? ctx->dev_slot_t0 : nullptr;
+  sl.budget = ctx->cfg.budget;
+  sl.window = ctx->cfg.window;
+  return sl;
+}
+
+// Does sequence s take part in global step t, and with how many cached entries before its append?
+bool slot_active(const lazyev_ctx *ctx, int s, int32_t t, int32_t *n_old) {
+  const int32_t P = ctx->slot_prompt[s], tau = t - ctx->slot_t0[s];
+  if (P < 0 || tau < 1) return false;
+  *n_old = lazyev::slot_n_old(P, tau, ctx->cfg.budget, ctx->cfg.window);
+  return true;
+}
+
+// Is an eviction due for sequence s after global step t (Sec. 4), and from how many entries?
+bool slot_due(const lazyev_ctx *ctx, int s, int32_t t, int32_t *n) {
+  int32_t n_old;
+  if (!slot_active(ctx, s, t, &n_old)) return false;
+  *n = n_old + 1;
+  return (t - ctx->slot_t0[s]) % ctx->cfg.window == 0 && *n > ctx->cfg.budget;
+}
+
+// Entries sequence s holds in `layer` now (after the layer's last step and, if it ran, that
+// step's eviction); 0 for an empty or not yet started slot's generated part.
+int32_t slot_len_now(const lazyev_ctx *ctx, int layer, int s) {
+  const int32_t t = ctx->last_step[layer];
+  if (ctx->slot_prompt[s] < 0) return 0;
+  int32_t n_old;
+  if (!slot_active(ctx, s, t, &n_old)) return ctx->slot_prompt[s];
+  int32_t n;
+  if (slot_due(ctx, s, t, &n) && ctx->evict_applied[layer] == t) return ctx->cfg.budget;
+  return n_old + 1;
 }
 
 // Applies the tracking of the last fused decode call if it is still pending.
@@ -191,6 +237,13 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
   ctx->ws.hist = reinterpret_cast<unsigned long long *>(base + l.hist);
+  ctx->dev_slot_prompt = reinterpret_cast<int32_t *>(base + l.slots);
+  ctx->dev_slot_t0 = ctx->dev_slot_prompt + cfg->batch;
+  ctx->dev_seq_len = ctx->dev_slot_t0 + cfg->batch;
+  ctx->slots_on = false;
+  ctx->slot_prompt.assign(cfg->batch, cfg->prompt_len);
+  ctx->slot_t0.assign(cfg->batch, 0);
+  ctx->evict_applied.assign(cfg->n_layers, 0);
   ctx->len.assign(cfg->n_layers, cfg->prompt_len);
   ctx->last_step.assign(cfg->n_layers, 0);
   ctx->n_evict_events.assign(cfg->n_layers, 0);
@@ -241,7 +294,23 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   const lazyev_config &c = ctx->cfg;
   if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
   if (t != ctx->last_step[layer] + 1) return LAZYEV_EINVAL;
-  const int32_t n_old = ctx->len[layer];
+  int32_t n_old = ctx->len[layer];
+  if (ctx->slots_on) {
+    // per-sequence timing: a due eviction of the layer's previous step must have run, and the
+    // launch is sized for the longest cache among the sequences that take this step
+    const int32_t tp = ctx->last_step[layer];
+    int32_t n_tmp;
+    if (tp >= 1 && ctx->evict_applied[layer] != tp)
+      for (int s2 = 0; s2 < c.batch; ++s2)
+        if (slot_due(ctx, s2, tp, &n_tmp)) return LAZYEV_ECAPACITY;
+    n_old = -1;
+    for (int s2 = 0; s2 < c.batch; ++s2)
+      if (slot_active(ctx, s2, t, &n_tmp) && n_tmp > n_old) n_old = n_tmp;
+    if (n_old < 0) {                               // no sequence takes this step
+      ctx->last_step[layer] = t;
+      return LAZYEV_OK;
+    }
+  }
   if (n_old >= ctx->capacity) return LAZYEV_ECAPACITY;
 
   const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
@@ -261,6 +330,8 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     if (ctx->variant == 2) kind = 2;
     if (ctx->variant == 3) kind = unit_fits ? 3 : 2;
   }
+  if (ctx->slots_on && kind != 4) return LAZYEV_EINVAL;   // only the single-launch kernel knows slots
+  a.slots = slots_of(ctx);
   a.lds_stride = lds_stride;
   a.lds_stage_offset = static_cast<int32_t>(lazyev::decode_unit_stage_offset(ctx->group, lds_stride));
   if (kind == 4) {
@@ -330,6 +401,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     k.logits = a.logits_out; k.stat = a.stat_out;
     k.p_out = p_out; k.p_override = p_override;
     k.activation_counter = a.activation_counter;
+    k.slots = a.slots;
     ctx->cur_buf ^= 1;
     if (p_out || p_override) {                     // the caller looks at the weights now
       const hipError_t ef = flush_tracking(ctx);
@@ -345,8 +417,16 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   const lazyev_config &c = ctx->cfg;
   if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
   if (t < 1 || t != ctx->last_step[layer]) return LAZYEV_EINVAL;
-  const int32_t n = ctx->len[layer];
-  if (t % c.window != 0 || n <= c.budget) return LAZYEV_OK;       // not due (Sec. 4)
+  int32_t n = ctx->len[layer];
+  if (ctx->slots_on) {                             // due for any sequence?  sized for the longest of those
+    n = 0;
+    int32_t n_tmp;
+    for (int s2 = 0; s2 < c.batch; ++s2)
+      if (slot_due(ctx, s2, t, &n_tmp) && n_tmp > n) n = n_tmp;
+    if (n == 0 || ctx->evict_applied[layer] == t) return LAZYEV_OK;
+  } else if (t % c.window != 0 || n <= c.budget) {
+    return LAZYEV_OK;                              // not due (Sec. 4)
+  }
   if (n - c.window > LAZYEV_MAX_CANDIDATES) return LAZYEV_ECAPACITY;   // more than the selection holds
 
   const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
@@ -362,6 +442,8 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
   a.rows_moved = ctx->ws.rows_moved + static_cast<size_t>(layer) * ctx->units;
+  a.n_kv_heads = c.n_kv_heads;
+  a.slots = slots_of(ctx);
   if (c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) {
     // the weights of step t: only there if this layer's decode call was the last one
     if (ctx->last_layer != layer || !ctx->last_logits) return LAZYEV_EINVAL;
@@ -375,7 +457,15 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   if (n_evicted) *n_evicted = n - c.budget;
   ctx->n_evict_events[layer] += 1;
   ctx->n_evicted[layer] += n - c.budget;
+  ctx->evict_applied[layer] = t;
   ctx->len[layer] = c.budget;
+  if (ctx->slots_on) {
+    ctx->len[layer] = 0;
+    for (int s2 = 0; s2 < c.batch; ++s2) {
+      const int32_t ls = slot_len_now(ctx, layer, s2);
+      if (ls > ctx->len[layer]) ctx->len[layer] = ls;
+    }
+  }
   ctx->last_layer = -1;                            // the stored logits no longer match the slots
   return LAZYEV_OK;
 }
@@ -426,14 +516,81 @@ int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t
   hipError_t e = flush_tracking(ctx);
   if (e == hipSuccess) e = hipMemsetAsync(ctx->ws.hist, 0, n_bins * sizeof(unsigned long long), ctx->stream);
   const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->cfg.n_layers : layer + 1;
-  for (int l = l0; l < l1 && e == hipSuccess; ++l)
-    e = lazyev::launch_mri_histogram(ctx->cfg.mri + static_cast<size_t>(l) * ctx->units * ctx->capacity,
-                                     ctx->units, ctx->capacity, ctx->len[l], n_bins, ctx->ws.hist,
-                                     ctx->stream);
+  for (int l = l0; l < l1 && e == hipSuccess; ++l) {
+    const int32_t *mri_l = ctx->cfg.mri + static_cast<size_t>(l) * ctx->units * ctx->capacity;
+    if (!ctx->slots_on) {
+      e = lazyev::launch_mri_histogram(mri_l, ctx->units, ctx->capacity, ctx->len[l], n_bins,
+                                       ctx->ws.hist, ctx->stream);
+      continue;
+    }
+    // per-sequence lengths of this layer go to the device first (a rare, synchronous call)
+    std::vector<int32_t> lens(ctx->cfg.batch);
+    int32_t n_max = 0;
+    for (int s2 = 0; s2 < ctx->cfg.batch; ++s2) {
+      lens[s2] = slot_len_now(ctx, l, s2);
+      if (lens[s2] > n_max) n_max = lens[s2];
+    }
+    e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+      e = hipMemcpy(ctx->dev_seq_len, lens.data(), lens.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = lazyev::launch_mri_histogram_slots(mri_l, ctx->units, ctx->capacity, ctx->cfg.n_kv_heads,
+                                             ctx->dev_seq_len, n_max, n_bins, ctx->ws.hist, ctx->stream);
+  }
   if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess)
     e = hipMemcpy(hist, ctx->ws.hist, n_bins * sizeof(unsigned long long), hipMemcpyDeviceToHost);
   return e == hipSuccess ? LAZYEV_OK : fail_hip(ctx, e);
+}
+
+// Common part of lazyev_admit and lazyev_retire.
+static int change_slot(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0) {
+  const lazyev_config &c = ctx->cfg;
+  hipError_t e = flush_tracking(ctx);              // pending tracking still belongs to the old occupant
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (!ctx->slots_on) {                            // first use: the device copies of the timing records
+    e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+      e = hipMemcpy(ctx->dev_slot_prompt, ctx->slot_prompt.data(), c.batch * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = hipMemcpy(ctx->dev_slot_t0, ctx->slot_t0.data(), c.batch * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    ctx->slots_on = true;
+  }
+  e = lazyev::launch_init_slot(c.ts, c.mri, c.pos, c.n_layers, c.batch, c.n_kv_heads, ctx->capacity,
+                               seq, prompt_len, ctx->dev_slot_prompt, ctx->dev_slot_t0, t0, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  ctx->slot_prompt[seq] = prompt_len;
+  ctx->slot_t0[seq] = t0;
+  ctx->last_layer = -1;
+  for (int l = 0; l < c.n_layers; ++l) {           // what lazyev_stats reports as the layer's length
+    ctx->len[l] = 0;
+    for (int s2 = 0; s2 < c.batch; ++s2) {
+      const int32_t ls = slot_len_now(ctx, l, s2);
+      if (ls > ctx->len[l]) ctx->len[l] = ls;
+    }
+  }
+  return LAZYEV_OK;
+}
+
+int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0) {
+  if (!ctx) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (seq < 0 || seq >= c.batch || prompt_len < 0 || prompt_len > ctx->capacity - c.window) return LAZYEV_EINVAL;
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant != 4))
+    return LAZYEV_EINVAL;
+  for (int l = 0; l < c.n_layers; ++l)
+    if (t0 < ctx->last_step[l]) return LAZYEV_EINVAL;   // its first step lies ahead of every layer
+  return change_slot(ctx, seq, prompt_len, t0);
+}
+
+int lazyev_retire(lazyev_ctx *ctx, int32_t seq) {
+  if (!ctx) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (seq < 0 || seq >= c.batch) return LAZYEV_EINVAL;
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant != 4))
+    return LAZYEV_EINVAL;
+  return change_slot(ctx, seq, -1, 0);
 }
 
 int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score, int64_t n,
