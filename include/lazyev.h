@@ -169,6 +169,10 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
  * bf16, head_dim 128 and the default attention kernel only.
  * Both apply pending tracking first.  Errors: EINVAL, EHIP. */
 int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0);
+/* Entries a sequence holds before the append of its local step (>= 1) when every due eviction has
+ * run: the closed form host and kernels share (a due eviction leaves exactly `budget` entries,
+ * Sec. 4 / Eq. 6, so the length depends on nothing else).  Host only.  -1 for bad arguments. */
+int32_t lazyev_cached_before_step(int32_t prompt_len, int32_t local_step, int32_t budget, int32_t window);
 int lazyev_retire(lazyev_ctx *ctx, int32_t seq);
 
 /* Distribution of the Maximum Recurrence Interval (Eq. 1) over the cached entries, the

@@ -44,7 +44,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
-           "lazyev_evict", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
+           "lazyev_evict", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
            "lazyev_event_overhead",
@@ -66,6 +66,8 @@ lib.lazyev_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
 lib.lazyev_admit.restype = C.c_int
 lib.lazyev_admit.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
 lib.lazyev_retire.restype = C.c_int
+lib.lazyev_cached_before_step.restype = C.c_int32
+lib.lazyev_cached_before_step.argtypes = [C.c_int32] * 4
 lib.lazyev_retire.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_mri_histogram.restype = C.c_int
 lib.lazyev_mri_histogram.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]

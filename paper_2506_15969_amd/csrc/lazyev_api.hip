@@ -573,6 +573,11 @@ static int change_slot(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t
   return LAZYEV_OK;
 }
 
+int32_t lazyev_cached_before_step(int32_t prompt_len, int32_t local_step, int32_t budget, int32_t window) {
+  if (prompt_len < 0 || local_step < 1 || window < 1 || budget <= window) return -1;
+  return lazyev::slot_n_old(prompt_len, local_step, budget, window);
+}
+
 int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0) {
   if (!ctx) return LAZYEV_EINVAL;
   const lazyev_config &c = ctx->cfg;

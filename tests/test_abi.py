@@ -103,3 +103,23 @@ def test_current_attention_ranking_needs_the_bf16_shape(lazyev_lib):
     assert b.lib.lazyev_capacity(C.byref(cfg)) == 0
     cfg.dtype, cfg.head_dim = b.DTYPE_BF16, 64
     assert b.lib.lazyev_capacity(C.byref(cfg)) == 0
+
+
+def test_cache_length_formula_against_a_simulation(lazyev_lib):
+    """Host logic shared with the kernels: the closed form for a sequence's cache length must
+    equal stepping the schedule of Sec. 4 (append; after a step that is a multiple of W, cut to
+    B if more than B are cached), for prompts shorter and longer than the budget."""
+    import random
+    rng = random.Random(9)
+    f = lazyev_lib.lib.lazyev_cached_before_step
+    for _ in range(400):
+        B = rng.randint(2, 70)
+        W = rng.randint(1, B - 1)
+        P = rng.randint(0, 120)
+        n = P
+        for tau in range(1, 200):
+            assert f(P, tau, B, W) == n, (P, B, W, tau)
+            n += 1
+            if tau % W == 0 and n > B:
+                n = B
+    assert f(-1, 1, 8, 2) == -1 and f(4, 0, 8, 2) == -1 and f(4, 1, 2, 2) == -1
