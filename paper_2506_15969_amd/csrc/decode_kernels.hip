@@ -24,9 +24,6 @@ constexpr int kSplitMaxLds = 512;  // split partials the combine kernel can weig
 
 typedef unsigned short bf16_t;
 
-__device__ __forceinline__ float bf16_to_float(bf16_t x) {
-  return __uint_as_float(static_cast<unsigned>(x) << 16);
-}
 __device__ __forceinline__ bf16_t float_to_bf16(float f) {   // round to nearest even
   unsigned u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
@@ -608,18 +605,18 @@ template <int N_IT>
 hipError_t launch_mfma(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
   dim3 grid_s(a.n_split, units);
-  if (ev) hipEventRecord(ev[0], stream);
+  if (ev) (void)hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL((decode_split_mfma_kernel<N_IT>), grid_s, dim3(kBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (ev) hipEventRecord(ev[1], stream);
+  if (ev) (void)hipEventRecord(ev[1], stream);
   int n_slice = (a.n_old + 1 + kBlock - 1) / kBlock;
   if (n_slice > kSliceMax) n_slice = kSliceMax;
   dim3 grid_c(n_slice, units);
   hipLaunchKernelGGL((decode_combine_kernel<bf16_t, 128>), grid_c, dim3(kBlock),
                      2 * a.n_split * a.group * sizeof(float), stream, a);
   e = hipGetLastError();
-  if (ev) hipEventRecord(ev[2], stream);
+  if (ev) (void)hipEventRecord(ev[2], stream);
   return e;
 }
 
@@ -627,11 +624,11 @@ template <typename T, int D, int G>
 hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
   dim3 grid_s(a.n_split, units);
-  if (ev) hipEventRecord(ev[0], stream);
+  if (ev) (void)hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL((decode_split_kernel<T, D, G>), grid_s, dim3(kBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (ev) hipEventRecord(ev[1], stream);
+  if (ev) (void)hipEventRecord(ev[1], stream);
   const int n1 = a.n_old + 1;
   int n_slice = (n1 + kBlock - 1) / kBlock;
   if (n_slice > kSliceMax) n_slice = kSliceMax;
@@ -639,7 +636,7 @@ hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev)
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), grid_c, dim3(kBlock),
                      2 * a.n_split * a.group * sizeof(float), stream, a);
   e = hipGetLastError();
-  if (ev) hipEventRecord(ev[2], stream);
+  if (ev) (void)hipEventRecord(ev[2], stream);
   return e;
 }
 

@@ -338,10 +338,10 @@ hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_
   if (a.dtype != 1 || a.head_dim != D || lds > 150 * 1024 || a.group * D > kUnitBlock)
     return hipErrorInvalidValue;
   const int units = a.batch * a.n_kv_heads;
-  if (ev) hipEventRecord(ev[0], stream);
+  if (ev) (void)hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL(decode_unit_kernel, dim3(units), dim3(kUnitBlock), lds, stream, a);
   const hipError_t e = hipGetLastError();
-  if (ev) { hipEventRecord(ev[1], stream); hipEventRecord(ev[2], stream); }
+  if (ev) { (void)hipEventRecord(ev[1], stream); (void)hipEventRecord(ev[2], stream); }
   return e;
 }
 

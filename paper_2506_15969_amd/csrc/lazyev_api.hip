@@ -120,7 +120,7 @@ hipEvent_t *arm_events(lazyev_ctx *ctx, int kind) {
   t.kind = kind;
   for (int i = 0; i < 3; ++i)
     if (hipEventCreate(&t.ev[i]) != hipSuccess) {
-      for (int j = 0; j < i; ++j) hipEventDestroy(t.ev[j]);
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(t.ev[j]);
       return nullptr;
     }
   ctx->prof_armed -= 1;
@@ -130,7 +130,7 @@ hipEvent_t *arm_events(lazyev_ctx *ctx, int kind) {
 
 void drop_events(lazyev_ctx *ctx) {
   for (auto &t : ctx->prof)
-    for (int i = 0; i < 3; ++i) hipEventDestroy(t.ev[i]);
+    for (int i = 0; i < 3; ++i) (void)hipEventDestroy(t.ev[i]);
   ctx->prof.clear();
 }
 

@@ -46,19 +46,19 @@ extern "C" int lazyev_event_overhead(int32_t n_pairs, void *stream, double *ms_a
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipEvent_t a, b;
   if (hipEventCreate(&a) != hipSuccess) return LAZYEV_EHIP;
-  if (hipEventCreate(&b) != hipSuccess) { hipEventDestroy(a); return LAZYEV_EHIP; }
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return LAZYEV_EHIP; }
   double total = 0.0;
   int rc = LAZYEV_OK;
   for (int i = 0; i < n_pairs && rc == LAZYEV_OK; ++i) {
     hipLaunchKernelGGL(empty_kernel, dim3(256), dim3(256), 0, s);      // keep the queue busy first
-    hipEventRecord(a, s);
-    hipEventRecord(b, s);
+    (void)hipEventRecord(a, s);
+    (void)hipEventRecord(b, s);
     float ms = 0.f;
     if (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(&ms, a, b) != hipSuccess) rc = LAZYEV_EHIP;
     total += ms;
   }
-  hipEventDestroy(a);
-  hipEventDestroy(b);
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
   *ms_avg = total / n_pairs;
   return rc;
 }
