@@ -167,6 +167,9 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
  * after every step at which that holds for some sequence (the next lazyev_decode_step of the
  * layer returns ECAPACITY otherwise); lazyev_stats reports the longest cache of each layer.
  * bf16, head_dim 128 and the default attention kernel only.
+ * A caller that wants the prompt itself tracked (TS / MRI from the prompt's own attention, and
+ * eviction while a prompt longer than the budget is read) admits the sequence with prompt_len 0
+ * and feeds the prompt tokens as decode steps.
  * Both apply pending tracking first.  Errors: EINVAL, EHIP. */
 int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0);
 /* Entries a sequence holds before the append of its local step (>= 1) when every due eviction has
