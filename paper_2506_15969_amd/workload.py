@@ -111,7 +111,7 @@ class WorkloadConfig:
         return replace(self, **kw)
 
 
-# The five workloads of the build's baseline description.  "cfg1".."cfg5".
+# The five benchmark workloads, "cfg1".."cfg5": shapes of 7B- and 14B-class GQA models, 512 to 32768 generated tokens.
 CONFIGS = {
     "cfg1": WorkloadConfig("cfg1", 1, 1, 4, 4, 64, "fp32", 64, 512, 128, 16, seed=1,
                            planted_count_in_prompt=8, schedule="uniform",

@@ -53,7 +53,7 @@ def test_benchmark_shapes_weights_injected(lazyev_lib):
 
 
 def test_cfg2_full_length_on_sampled_units(lazyev_lib):
-    """Workload 2 as BASELINE describes it: 512-token prompt, 4096 steps, 112 evictions."""
+    """Workload 2 at its full length: 512-token prompt, 4096 steps, 112 evictions."""
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg2"]
     units = _sample(cfg, 2, 2, [0])
