@@ -43,7 +43,25 @@ def build_library(verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print("built", LIB)
+    build_c_example(verbose)
     return LIB
+
+
+def build_c_example(verbose: bool = True) -> str:
+    """csrc/abi_example.c: the C ABI used from plain C99 with gcc (no C++, no Python); the GPU
+    test tests/test_gpu_c_abi.py runs it."""
+    exe = os.path.join(LIBDIR, "abi_example")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c99", "-O1", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__",
+           "-I" + os.path.join(rocm, "include"), "-I" + INCLUDE, os.path.join(CSRC, "abi_example.c"),
+           "-o", exe, "-L" + LIBDIR, "-llazyev", "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("C example failed to build:\n" + r.stderr)
+    if verbose:
+        print("built", exe)
+    return exe
 
 
 if __name__ == "__main__":
