@@ -434,3 +434,47 @@ def test_current_attention_behind_a_window_by_hand():
     u.decode_step(2, np.zeros((1, 4)), np.zeros(4), np.zeros(4), p_override=w2)
     assert u.evict(2) == [0, 2, 3]                        # keeps 4 (tie with 1: the newer) and 1
     assert u.pos.tolist() == [1, 4, 5, 6]
+
+
+# ---------------------------------------------------------------- invariants on random runs
+def test_invariants_over_random_configurations():
+    """What Sec. 4, Eq. 1 and Eq. 6 fix whatever the inputs are, on 60 random (P, B, W, alpha)
+    with random injected weights: the cache never holds more than max(P, B) + W entries and exactly B
+    after a due eviction; an eviction removes nothing younger than W steps and keeps the order;
+    per token MRI never shrinks, TS <= t, MRI <= t - birth, MRI = 0 exactly for tokens never
+    activated after their birth step, TS = birth for those; statistics travel with the token."""
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        B = int(rng.integers(3, 40))
+        W = int(rng.integers(1, B))
+        P = int(rng.integers(0, 60))
+        G = int(rng.integers(1, 4))
+        alpha = float(rng.choice([0.0, 0.02, 0.1, 0.3, 1.5]))
+        u = OracleUnit(np.zeros((P, 2)), np.zeros((P, 2)), G, B, W, alpha,
+                       score_flags=int(rng.choice([3, 1, 2, 0, 3 | 16])))
+        birth = lambda pos: max(0, pos - P + 1)           # noqa: E731  (step that appended it)
+        hist = {}                                          # pos -> (TS, MRI, ever activated later)
+        for t in range(1, 3 * W + 25):
+            n1 = len(u) + 1
+            p = (rng.random((G, n1)) ** 4 * 0.5).astype(np.float32)
+            _, _, act = u.decode_step(t, np.zeros((G, 2)), np.zeros(2), np.zeros(2), p_override=p)
+            assert len(u) <= max(P, B) + W                 # the capacity a caller has to provide
+            for i, pos in enumerate(u.pos.tolist()):
+                ts, mri = int(u.TS[i]), int(u.MRI[i])
+                old = hist.get(pos, (birth(pos), 0, False))
+                later = old[2] or (bool(act[i]) and t > birth(pos))
+                assert mri >= old[1] and ts >= old[0] and ts <= t
+                assert mri <= t - birth(pos)
+                assert (mri == 0) == (not later)
+                if not later:
+                    assert ts == birth(pos)
+                hist[pos] = (ts, mri, later)
+            before = u.pos.copy()
+            due = t % W == 0 and len(u) > B
+            gone = u.evict(t)
+            assert bool(gone) == due
+            if due:
+                assert len(u) == B and all(g < P + t - W for g in gone)
+                assert np.all(np.diff(u.pos) > 0) and set(u.pos.tolist()) | set(gone) == set(before.tolist())
+                for i, pos in enumerate(u.pos.tolist()):   # (TS, MRI) moved with their token
+                    assert (int(u.TS[i]), int(u.MRI[i])) == hist[pos][:2]
