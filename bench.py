@@ -281,13 +281,17 @@ def main():
                    "activations_per_unit_step": sum(st["n_activations"]) / (K * L * S * Hkv)},
         "input_generation_s": t_gen,
     }
+    # which attention kernel the library picks for this shape (see lazyev_set_variant)
+    fused = cfg.dtype == "bf16" and d == 128 and args.variant in (-1, 1, 4)
     if split_n:
         # event intervals minus the fixed cost of the event pair itself
         split_k = split_ms - ov_ms * split_n
         call_k = split_ms + comb_ms - 2 * ov_ms * split_n
         ach = dec_bytes / (split_k * 1e-3) / 1e9
         result["roofline"] = {
-            "kernel": "decode_fused_kernel (the one kernel of lazyev_decode_step)",
+            "kernel": ("decode_fused_kernel (the one kernel of lazyev_decode_step)"
+                       if fused else "first of the two kernels of lazyev_decode_step (split; "
+                                     "decode_call covers split + merge)"),
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
             "avg_us": 1e3 * split_k / split_n, "avg_us_between_events": 1e3 * split_ms / split_n,
