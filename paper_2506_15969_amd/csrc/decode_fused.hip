@@ -73,11 +73,19 @@ struct SubTile {
 
 // What one block writes for another block of the SAME launch to read (the partials) is
 // stored at device ("agent") scope: the stores write through the XCD-local L2, so no whole-cache
-// write-back is needed to publish them.  Publishing is: wait until this wave's stores have
-// completed (the block barrier does), then one relaxed device-scope atomic on the unit's
-// ticket.  The block that takes the last ticket reads the partials with device-scope loads
+// write-back is needed to publish them.  Publishing is: every wave waits until its stores have
+// completed (wait_own_stores), the block barrier, then one relaxed device-scope atomic on the
+// unit's ticket.  The block that takes the last ticket reads the partials with device-scope loads
 // (which do not use possibly stale cached copies); a cache-invalidating acquire fence followed
 // by ordinary loads measured five times slower.
+// Waits until every global store (and load) this wave has issued is complete.  A block barrier
+// alone does not: the compiler only drains the LDS counter before s_barrier.
+__device__ __forceinline__ void wait_own_stores() {
+  __asm__ volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0); expcnt and lgkmcnt untouched
+  __asm__ volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ void store_f32_device(float *p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -511,7 +519,8 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
           reinterpret_cast<const uint4 *>(v_new)[lane - 16];
   }
   // ---- ticket: the last block of the unit finishes it
-  __syncthreads();                                 // also: this wave's stores have completed ...
+  wait_own_stores();                               // every wave's partial stores have completed ...
+  __syncthreads();
   if (tid == 0) {
     const int prev = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);   // ... before its ticket is taken

@@ -272,7 +272,11 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
     const unsigned dst = def_before + kept_ties_before;
     int32_t v_ts = 0, v_mri = 0, v_pos = 0;
     if (keep) { v_ts = ts[slot]; v_mri = mri[slot]; v_pos = pos[slot]; }
-    __syncthreads();                       // every read of this pass precedes its writes
+    // every read of this pass precedes its writes: the loads have returned (the barrier alone
+    // only drains the LDS counter), in every thread
+    __asm__ volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0)
+    __syncthreads();
     if (keep) {
       ts[dst] = v_ts; mri[dst] = v_mri; pos[dst] = v_pos;
       src_index[dst] = slot;
