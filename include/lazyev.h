@@ -202,7 +202,9 @@ int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*d
  *     64..256; default 128).
  *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernels aim for
  *     (default 512 = two per compute unit); each unit gets round(n_blocks / units) blocks,
- *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64 blocks).
+ *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64 blocks;
+ *     until this is called, kernel 4 also uses fewer blocks for short caches: about 16
+ *     sub-tiles of 16 entries per wave, but at least one block per compute unit).
  * Errors: EINVAL. */
 int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
 int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);

@@ -22,6 +22,7 @@ struct lazyev_ctx {
   lazyev_config cfg;
   int32_t capacity, group, units;
   int32_t chunk, n_split_max, variant, target_blocks;
+  bool target_blocks_set;                          // by the caller: then taken literally
   float scale;
   hipStream_t stream;
   Workspace ws;
@@ -215,6 +216,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->chunk = 128;
   ctx->variant = 1;
   ctx->target_blocks = 512;          // two blocks per compute unit
+  ctx->target_blocks_set = false;
   while ((ctx->capacity + ctx->chunk - 1) / ctx->chunk > lazyev::decode_split_max()) ctx->chunk *= 2;
   ctx->scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale
                                          : 1.0f / std::sqrt(static_cast<float>(cfg->head_dim));
@@ -279,6 +281,7 @@ int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk) {
 int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
   if (!ctx || n_blocks < 1) return LAZYEV_EINVAL;
   ctx->target_blocks = n_blocks;
+  ctx->target_blocks_set = true;
   return LAZYEV_OK;
 }
 
@@ -338,6 +341,14 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     // fused kernel: n_split blocks of four waves per unit, every wave a run of 16-entry sub-tiles
     const int n_sub = (n_old + 1 + 15) / 16;
     int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
+    if (!ctx->target_blocks_set) {
+      // about 16 sub-tiles per wave (measured: fewer, longer-running waves finish a short cache
+      // sooner), but no fewer blocks than compute units and no more than two per compute unit
+      const int lo = (256 + ctx->units - 1) / ctx->units;
+      const int by_run = (n_sub + 32) / 64;
+      if (by_run < n_split) n_split = by_run;
+      if (n_split < lo) n_split = lo;
+    }
     if (n_split > (n_sub + 3) / 4) n_split = (n_sub + 3) / 4;
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();
     if (n_split > ctx->n_split_max) n_split = ctx->n_split_max;
