@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
 // --------------------------------------------------------------------- last block of a unit
 // Merges the unit's block partials (in block order, so the result does not depend on which
 // block came last) into the output row and stores the unit's softmax statistics.
+template <int GW>                                  // partials merged per memory round trip
 __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
   const int tid = threadIdx.x;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
@@ -235,16 +236,16 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
   float m_run[EPT], l_run[EPT], o_run[EPT];
 #pragma unroll
   for (int x = 0; x < EPT; ++x) { m_run[x] = -INFINITY; l_run[x] = 0.f; o_run[x] = 0.f; }
-  for (int j0 = 0; j0 < n_split; j0 += 4) {
-    // 4 partials x EPT elements x (max, sum, value): all loads unconditional (indices clamped
+  for (int j0 = 0; j0 < n_split; j0 += GW) {
+    // GW partials x EPT elements x (max, sum, value): all loads unconditional (indices clamped
     // to real partials) and issued together: one memory round trip
-    float mj[EPT][4], lj[EPT][4], oj[EPT][4];
+    float mj[EPT][GW], lj[EPT][GW], oj[EPT][GW];
 #pragma unroll
     for (int x = 0; x < EPT; ++x) {
       const int e = min(tid + x * kBlock, G * D - 1);
       const int h = e / D;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
+      for (int jj = 0; jj < GW; ++jj) {
         const int j = min(j0 + jj, n_split - 1);
         mj[x][jj] = load_f32_device(ml + j * (2 * G) + h);
         lj[x][jj] = load_f32_device(ml + j * (2 * G) + G + h);
@@ -252,7 +253,7 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
       }
     }
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
+    for (int jj = 0; jj < GW; ++jj) {
       if (j0 + jj >= n_split) break;               // uniform
 #pragma unroll
       for (int x = 0; x < EPT; ++x) {
@@ -529,7 +530,9 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   }
   __syncthreads();
   if (!last_flag) return;
-  finish_unit(a, unit, n_split);
+  // (two blocks per unit is the usual split of a short cache: no loads of clamped duplicates)
+  if (n_split <= 2) finish_unit<2>(a, unit, n_split);
+  else finish_unit<4>(a, unit, n_split);
 }
 
 }  // namespace
