@@ -221,9 +221,58 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
 }
 
 // --------------------------------------------------------------------- last block of a unit
+// A block's partial as another block reads it: four consecutive output elements (one head) and
+// that head's (max, sum).  The loads are device-scope (sc1) like load_f32_device, but 16 bytes
+// wide, which the atomic builtins do not offer; one asm statement issues all loads of a group
+// and waits for them, so no register is touched while a load is still in flight.
+template <int GW>
+struct PartialGroup {
+  f32x4_t o[GW];
+  float m[GW], l[GW];
+};
+
+__device__ __forceinline__ void load_partials(PartialGroup<2> &g, const float *const (&po)[2],
+                                              const float *const (&pm)[2], const float *const (&pl)[2]) {
+  __asm__ volatile(
+      "global_load_dwordx4 %0, %6, off sc1\n"
+      "global_load_dwordx4 %1, %7, off sc1\n"
+      "global_load_dword %2, %8, off sc1\n"
+      "global_load_dword %3, %9, off sc1\n"
+      "global_load_dword %4, %10, off sc1\n"
+      "global_load_dword %5, %11, off sc1\n"
+      "s_waitcnt vmcnt(0)\n"
+      : "=&v"(g.o[0]), "=&v"(g.o[1]), "=&v"(g.m[0]), "=&v"(g.m[1]), "=&v"(g.l[0]), "=&v"(g.l[1])
+      : "v"(po[0]), "v"(po[1]), "v"(pm[0]), "v"(pm[1]), "v"(pl[0]), "v"(pl[1])
+      : "memory");
+}
+
+__device__ __forceinline__ void load_partials(PartialGroup<4> &g, const float *const (&po)[4],
+                                              const float *const (&pm)[4], const float *const (&pl)[4]) {
+  __asm__ volatile(
+      "global_load_dwordx4 %0, %12, off sc1\n"
+      "global_load_dwordx4 %1, %13, off sc1\n"
+      "global_load_dwordx4 %2, %14, off sc1\n"
+      "global_load_dwordx4 %3, %15, off sc1\n"
+      "global_load_dword %4, %16, off sc1\n"
+      "global_load_dword %5, %17, off sc1\n"
+      "global_load_dword %6, %18, off sc1\n"
+      "global_load_dword %7, %19, off sc1\n"
+      "global_load_dword %8, %20, off sc1\n"
+      "global_load_dword %9, %21, off sc1\n"
+      "global_load_dword %10, %22, off sc1\n"
+      "global_load_dword %11, %23, off sc1\n"
+      "s_waitcnt vmcnt(0)\n"
+      : "=&v"(g.o[0]), "=&v"(g.o[1]), "=&v"(g.o[2]), "=&v"(g.o[3]), "=&v"(g.m[0]), "=&v"(g.m[1]),
+        "=&v"(g.m[2]), "=&v"(g.m[3]), "=&v"(g.l[0]), "=&v"(g.l[1]), "=&v"(g.l[2]), "=&v"(g.l[3])
+      : "v"(po[0]), "v"(po[1]), "v"(po[2]), "v"(po[3]), "v"(pm[0]), "v"(pm[1]), "v"(pm[2]),
+        "v"(pm[3]), "v"(pl[0]), "v"(pl[1]), "v"(pl[2]), "v"(pl[3])
+      : "memory");
+}
+
 // Merges the unit's block partials (in block order, so the result does not depend on which
-// block came last) into the output row and stores the unit's softmax statistics.
-template <int GW>                                  // partials merged per memory round trip
+// block came last) into the output row and stores the unit's softmax statistics.  Thread t
+// owns output elements 4t .. 4t+3 (all of one head); GW partials per memory round trip.
+template <int GW>
 __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
   const int tid = threadIdx.x;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
@@ -231,53 +280,49 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
   const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
   const float *ml = a.ws.part_ml + static_cast<size_t>(unit) * a.n_split_max * (2 * G);
   const float *pa = a.ws.part_acc + static_cast<size_t>(unit) * a.n_split_max * (G * D);
-  constexpr int EPT = (8 * D) / kBlock;            // output elements per thread (G <= 8)
+  const int e0 = 4 * tid;
+  const int ec = min(e0, G * D - 4);               // threads beyond the group's rows load a valid place
+  const int h = ec / D;
 
-  float m_run[EPT], l_run[EPT], o_run[EPT];
-#pragma unroll
-  for (int x = 0; x < EPT; ++x) { m_run[x] = -INFINITY; l_run[x] = 0.f; o_run[x] = 0.f; }
+  float m_run = -INFINITY, l_run = 0.f;
+  float o_run[4] = {0.f, 0.f, 0.f, 0.f};
   for (int j0 = 0; j0 < n_split; j0 += GW) {
-    // GW partials x EPT elements x (max, sum, value): all loads unconditional (indices clamped
-    // to real partials) and issued together: one memory round trip
-    float mj[EPT][GW], lj[EPT][GW], oj[EPT][GW];
+    // all loads unconditional (indices clamped to real partials) and issued together
+    PartialGroup<GW> g;
+    const float *po[GW], *pm[GW], *pl[GW];
 #pragma unroll
-    for (int x = 0; x < EPT; ++x) {
-      const int e = min(tid + x * kBlock, G * D - 1);
-      const int h = e / D;
-#pragma unroll
-      for (int jj = 0; jj < GW; ++jj) {
-        const int j = min(j0 + jj, n_split - 1);
-        mj[x][jj] = load_f32_device(ml + j * (2 * G) + h);
-        lj[x][jj] = load_f32_device(ml + j * (2 * G) + G + h);
-        oj[x][jj] = load_f32_device(pa + static_cast<size_t>(j) * (G * D) + e);
-      }
+    for (int jj = 0; jj < GW; ++jj) {
+      const int j = min(j0 + jj, n_split - 1);
+      po[jj] = pa + static_cast<size_t>(j) * (G * D) + ec;
+      pm[jj] = ml + j * (2 * G) + h;
+      pl[jj] = ml + j * (2 * G) + G + h;
     }
+    load_partials(g, po, pm, pl);
 #pragma unroll
     for (int jj = 0; jj < GW; ++jj) {
       if (j0 + jj >= n_split) break;               // uniform
+      const float m_new = fmaxf(m_run, g.m[jj]);
+      // a block without entries has max = -inf, sum = 0, values = 0: its factor is 0
+      const float fr = m_run == -INFINITY ? 0.f : __expf(m_run - m_new);
+      const float fj = g.m[jj] == -INFINITY ? 0.f : __expf(g.m[jj] - m_new);
+      l_run = l_run * fr + g.l[jj] * fj;
 #pragma unroll
-      for (int x = 0; x < EPT; ++x) {
-        const float m_new = fmaxf(m_run[x], mj[x][jj]);
-        // a block without entries has max = -inf, sum = 0, values = 0: its factor is 0
-        const float fr = m_run[x] == -INFINITY ? 0.f : __expf(m_run[x] - m_new);
-        const float fj = mj[x][jj] == -INFINITY ? 0.f : __expf(mj[x][jj] - m_new);
-        l_run[x] = l_run[x] * fr + lj[x][jj] * fj;
-        o_run[x] = o_run[x] * fr + oj[x][jj] * fj;
-        m_run[x] = m_new;
-      }
+      for (int i = 0; i < 4; ++i) o_run[i] = o_run[i] * fr + g.o[jj][i] * fj;
+      m_run = m_new;
     }
   }
-#pragma unroll
-  for (int x = 0; x < EPT; ++x) {
-    const int e = tid + x * kBlock;
-    if (e < G * D) {
-      const float invl = 1.0f / l_run[x];
-      static_cast<bf16_t *>(a.out)[head0 * D + e] = float_to_bf16(o_run[x] * invl);
-      if (e % D == 0) {
-        float *st = a.stat_out + static_cast<size_t>(unit) * (2 * kHeadPad) + 2 * (e / D);
-        st[0] = m_run[x];
-        st[1] = invl;
-      }
+  if (e0 < G * D) {
+    const float invl = 1.0f / l_run;
+    u32x2_t w;
+    w[0] = static_cast<unsigned>(float_to_bf16(o_run[0] * invl)) |
+           (static_cast<unsigned>(float_to_bf16(o_run[1] * invl)) << 16);
+    w[1] = static_cast<unsigned>(float_to_bf16(o_run[2] * invl)) |
+           (static_cast<unsigned>(float_to_bf16(o_run[3] * invl)) << 16);
+    *reinterpret_cast<u32x2_t *>(static_cast<bf16_t *>(a.out) + head0 * D + e0) = w;
+    if (e0 % D == 0) {
+      float *st = a.stat_out + static_cast<size_t>(unit) * (2 * kHeadPad) + 2 * h;
+      st[0] = m_run;
+      st[1] = invl;
     }
   }
 }
@@ -482,18 +527,25 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   {
     const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
     float *pacc = a.ws.part_acc + part * (G * D);
-    for (int e = tid; e < G * D; e += kBlock) {
-      const int h = e / D;
+    const int e0 = 4 * tid;                        // elements 4 tid .. 4 tid + 3, all of one head
+    if (e0 < G * D) {
+      const int h = e0 / D;
       float mb = m_lds[0][h];
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) mb = fmaxf(mb, m_lds[w][h]);
-      float v = 0.f;
+      f32x4_t v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
         const float mw = m_lds[w][h];
-        if (mw != -INFINITY) v = fmaf(__expf(mw - mb), acc_lds[w * (8 * D) + e], v);
+        if (mw != -INFINITY) {
+          const float f = __expf(mw - mb);
+          const f32x4_t x = *reinterpret_cast<const f32x4_t *>(acc_lds + w * (8 * D) + e0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = fmaf(f, x[i], v[i]);
+        }
       }
-      store_f32_device(pacc + e, v);
+      // device-scope (write-through) like store_f32_device, 16 bytes wide
+      __asm__ volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pacc + e0), "v"(v) : "memory");
     }
     if (tid < G) {
       float mb = m_lds[0][tid];
