@@ -15,6 +15,9 @@ What follows the paper, and where:
     "Observation Window"
   * current-attention ranking as an alternative score ... Sec. 2 (2); Appendix C "Baselines"
   * greedy current-attention comparator ................. Appendix C "Baselines" (TOVA sentence)
+  * the same tracking run over the prompt (`prefill_tracking`) Algorithm 1, first loop, and Eq. 1
+    applied to the prompt's own causal attention (the paper starts its clock at the first
+    generated token and says nothing of the prompt: reading R18)
 
 Readings taken where the paper is silent or inconsistent (each is also listed in the design
 notes of the repository):
@@ -39,6 +42,10 @@ notes of the repository):
       `two_sigmoid_neg`), so that another implementation running the same sequence ranks
       identically; `two_sigmoid_neg_libm` is the same function through the C library and is
       what the fixed sequence is pinned against.
+
+  R18 optional start state from the prompt: prompt token i (0-based, P tokens) is the query of
+      step i + 1 - P <= 0 over the keys 0..i, tracked exactly like a decode step (R1, R4-R6);
+      decoding then continues at step 1.  Without it prompt entries start as in R3.
 
 Pins (tests/test_oracle_*.py, CPU only): closed forms of Eq. 3 via 50-digit decimals, a hand
 trace of Eq. 1, full attention when B >= P+T against a library attention routine, the
@@ -161,6 +168,44 @@ def window_from_mri(mri_values, quantile: float = 0.8) -> int:
     if len(v) == 0:
         return 0
     return int(v[max(int(math.ceil(quantile * len(v))) - 1, 0)])
+
+
+def prefill_tracking(k_prompt, q_prompt, alpha: float, scale: float | None = None,
+                     p_override=None):
+    """TS and MRI of the P prompt entries of one unit after the first loop of Algorithm 1 and
+    Eq. 1 have run over the prompt's own causal attention (R18).
+
+    k_prompt [P,d]; q_prompt [P,G,d]: the G query heads of the unit's group at every prompt
+    position.  Position i is step tau_i = i + 1 - P: its entry is born with TS = tau_i, MRI = 0,
+    and its query sees the keys 0..i (Eq. 4 on the prefix).  p_override [G,P,P] (query row,
+    key column; the lower triangle is read): weights to threshold instead of the computed
+    ones, float32 compared in float32 as in `OracleUnit.decode_step`.
+    Returns (TS [P] int64, MRI [P] int64, n_activations).
+    """
+    k = np.asarray(k_prompt, dtype=np.float64)
+    q = np.asarray(q_prompt, dtype=np.float64)
+    P, d = k.shape
+    assert q.ndim == 3 and q.shape[0] == P and q.shape[2] == d
+    scale = float(scale) if scale else 1.0 / np.sqrt(np.float64(d))
+    TS = np.arange(P, dtype=np.int64) + 1 - P
+    MRI = np.zeros(P, dtype=np.int64)
+    n_act = 0
+    for i in range(P):
+        tau = i + 1 - P
+        if p_override is not None:
+            pw = np.asarray(p_override)[:, i, :i + 1]
+            thr = np.float32(alpha) if pw.dtype == np.float32 else np.float64(alpha)
+            act = (pw >= thr).any(axis=0)
+        else:
+            s = (q[i] @ k[:i + 1].T) * scale                     # [G, i+1]
+            e = np.exp(s - s.max(axis=1, keepdims=True))
+            p = e / e.sum(axis=1, keepdims=True)
+            act = (p >= alpha).any(axis=0)
+        idx = np.nonzero(act)[0]
+        MRI[idx] = np.maximum(MRI[idx], tau - TS[idx])           # Eq. 1
+        TS[idx] = tau                                            # Alg. 1
+        n_act += len(idx)
+    return TS, MRI, n_act
 
 
 def select_survivors(score: np.ndarray, n_keep: int) -> np.ndarray:

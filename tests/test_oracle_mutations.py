@@ -54,6 +54,12 @@ MUTANTS = [
     ("current attention: injected weights ignored", "            self.last_weight = pw.max(axis=0).astype(np.float64)\n", "            self.last_weight = p.max(axis=0)\n"),
     ("histogram without overflow bin", "hist[min(int(m), n_bins - 1)] += 1", "hist[int(m) % n_bins] += 1"),
     ("window quantile over all entries", "    v = v[v >= 1]\n", ""),
+    ("prompt tracking: query does not see its own key", "s = (q[i] @ k[:i + 1].T) * scale                     # [G, i+1]",
+     "s = (q[i] @ k[:max(i, 1)].T) * scale"),
+    ("prompt tracking: clock ends at P", "        tau = i + 1 - P\n", "        tau = i + 1\n"),
+    ("prompt tracking: MRI = last gap", "MRI[idx] = np.maximum(MRI[idx], tau - TS[idx])           # Eq. 1", "MRI[idx] = tau - TS[idx]"),
+    ("prompt tracking: AND over the group", "            act = (p >= alpha).any(axis=0)\n        idx", "            act = (p >= alpha).all(axis=0)\n        idx"),
+    ("prompt tracking: injected weights ignored", "        if p_override is not None:\n            pw = np.asarray(p_override)[:, i, :i + 1]", "        if False:\n            pw = np.asarray(p_override)[:, i, :i + 1]"),
 ]
 
 
@@ -81,7 +87,7 @@ def _load(source, tag):
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]
 SWAPPED = ["H2_DECREASING", "USE_CURRENT_ATTENTION", "USE_H1", "USE_H2", "GreedyUnit", "LazyEvictionOracle", "OracleUnit",
            "mri_histogram", "window_from_mri", "mri_centric_score", "select_survivors",
-           "two_sigmoid_neg", "two_sigmoid_neg_libm"]
+           "two_sigmoid_neg", "two_sigmoid_neg_libm", "prefill_tracking"]
 
 
 def _run_pins(mod):

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle.lazyev_oracle import (H2_DECREASING, USE_CURRENT_ATTENTION, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
+from oracle.lazyev_oracle import (prefill_tracking, H2_DECREASING, USE_CURRENT_ATTENTION, USE_H1, USE_H2, GreedyUnit, LazyEvictionOracle, OracleUnit,
                                   mri_histogram, window_from_mri,
                                   mri_centric_score, select_survivors, two_sigmoid_neg,
                                   two_sigmoid_neg_libm)
@@ -478,3 +478,64 @@ def test_invariants_over_random_configurations():
                 assert np.all(np.diff(u.pos) > 0) and set(u.pos.tolist()) | set(gone) == set(before.tolist())
                 for i, pos in enumerate(u.pos.tolist()):   # (TS, MRI) moved with their token
                     assert (int(u.TS[i]), int(u.MRI[i])) == hist[pos][:2]
+
+
+# ---------------------------------------------------------------- tracking over the prompt
+def test_prefill_tracking_by_hand():
+    """Zero queries give uniform weights 1/(i+1) at prompt position i.  With alpha = 0.4 the
+    positions 0 and 1 activate everything they see and position 2 (weights 1/3) nothing:
+    key 0 is hit at steps -2 (its birth) and -1, key 1 at -1 (birth), key 2 at 0 (birth)."""
+    k = np.arange(6, dtype=np.float64).reshape(3, 2)
+    q = np.zeros((3, 1, 2))
+    ts, mri, n_act = prefill_tracking(k, q, 0.4)
+    assert ts.tolist() == [-1, -1, 0] and mri.tolist() == [1, 0, 0] and n_act == 3
+    # alpha = 0: every query activates every key it sees: all TS end at 0, every gap is 1
+    ts, mri, n_act = prefill_tracking(np.ones((5, 2)), np.zeros((5, 2, 2)), 0.0)
+    assert ts.tolist() == [0] * 5 and mri.tolist() == [1, 1, 1, 1, 0] and n_act == 15
+    # alpha > 1: nothing is ever active
+    ts, mri, n_act = prefill_tracking(np.ones((5, 2)), np.zeros((5, 2, 2)), 1.5)
+    assert ts.tolist() == [-4, -3, -2, -1, 0] and mri.tolist() == [0] * 5 and n_act == 0
+
+
+def test_prefill_tracking_is_the_decode_tracking_fed_with_the_prompt():
+    """The same tokens fed one by one as decode steps 1..P to a unit that starts empty and never
+    evicts leave the same MRI, and TS shifted by P (its clock starts at 1, the prompt's ends at 0)."""
+    rng = np.random.default_rng(5)
+    P, G, d = 40, 3, 8
+    k, v = rng.standard_normal((P, d)), rng.standard_normal((P, d))
+    q = 2.0 * rng.standard_normal((P, G, d))
+    alpha = 0.08
+    ts, mri, n_act = prefill_tracking(k, q, alpha)
+    u = OracleUnit(np.zeros((0, d)), np.zeros((0, d)), G, 10 * P, 4, alpha)
+    for t in range(1, P + 1):
+        u.decode_step(t, q[t - 1], k[t - 1], v[t - 1])
+        assert u.evict(t) == []
+    assert np.array_equal(u.TS - P, ts) and np.array_equal(u.MRI, mri) and u.n_activations == n_act
+    assert mri.max() > 1 and (mri == 0).sum() > 0               # the case is not degenerate
+    # handing the computed weights in as float32 decides the same wherever no weight sits within
+    # float32 rounding of alpha (checked), and the override is what is thresholded
+    p_all = np.zeros((G, P, P), dtype=np.float32)
+    for i in range(P):
+        s = (q[i] @ k[:i + 1].T) / np.sqrt(d)
+        e = np.exp(s - s.max(axis=1, keepdims=True))
+        p_all[:, i, :i + 1] = (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
+    assert np.abs(p_all[p_all > 0] - np.float32(alpha)).min() > 1e-6
+    ts2, mri2, n2 = prefill_tracking(k, q, alpha, p_override=p_all)
+    assert np.array_equal(ts2, ts) and np.array_equal(mri2, mri) and n2 == n_act
+    ts3, _, n3 = prefill_tracking(k, q, alpha, p_override=np.zeros_like(p_all))
+    assert n3 == 0 and ts3.tolist() == list(range(1 - P, 1))
+
+
+def test_prefill_tracking_periodic_reader():
+    """A key that is read by every 5th prompt position and by nobody else gets MRI = 5."""
+    P, d = 31, 4
+    k = np.zeros((P, d)); k[:, 1] = 1.0
+    k[3] = [6.0, 0.0, 0.0, 0.0]                                  # the key that gets read
+    q = np.zeros((P, 1, d)); q[:, 0, 1] = 6.0                    # everybody else: uniform over the rest
+    for i in range(8, P, 5):
+        q[i, 0] = [12.0, 0.0, 0.0, 0.0]
+    ts, mri, _ = prefill_tracking(k, q, 0.5, scale=1.0)
+    # (its own query at position 3 spreads e^36 over three older keys: 1/3 < 0.5, so the first
+    # hit comes at position 8, five steps after its birth)
+    assert mri[3] == 5 and ts[3] == 28 + 1 - P
+    assert mri[np.arange(P) != 3].max() <= 1
