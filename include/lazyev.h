@@ -109,6 +109,24 @@ size_t lazyev_workspace_size(const lazyev_config *cfg /*host*/);
  * Errors: EINVAL, EWORKSPACE, EHIP. */
 int lazyev_init(const lazyev_config *cfg /*host*/, lazyev_ctx **out /*host*/);
 
+/* Optional start state from the prompt (the paper starts its clock at the first generated
+ * token and is silent on the prompt): runs the tracking loop of Alg. 1 and Eq. 1 over the
+ * prompt's own causal attention in `layer`.  Prompt position i (0-based, P positions) is the
+ * query of step i + 1 - P <= 0 over the keys 0..i; entry i is born with TS = i + 1 - P, MRI = 0
+ * and is updated by every later position whose probability for it reaches alpha in any head of
+ * its group, exactly as a decode step would.  Decoding continues at step 1; the activations are
+ * added to the layer's count.  Replaces the TS = 0, MRI = 0 that lazyev_init gave the prompt
+ * entries; call it after lazyev_init and before the layer's first decode step.
+ * q_prompt (device): [batch][P][n_q_heads][head_dim], the prompt's queries in the cache's dtype.
+ * p_out / p_override (device, nullable): [batch][n_q_heads][P][P] fp32, row = query position,
+ *   column = key; only the lower triangle (key <= query) is written / read; meaning as in
+ *   lazyev_decode_step.
+ * bf16 with head_dim 128 and at most 8 query heads per KV head; not with lazyev_admit / retire.
+ * Errors: EINVAL (shape, order, null, P = 0), EHIP. */
+int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt /*device*/,
+                         float *p_out /*device, nullable*/,
+                         const float *p_override /*device, nullable*/);
+
 /* One decode step of one layer (Eq. 4; Alg. 1 tracking loop; Eq. 1):
  *   appends (k_new, v_new) as entry N with TS = t, MRI = 0, pos = P + t - 1;
  *   out[h] = softmax(scale * q[h] K^T) V over the N+1 entries of the head's unit;

@@ -20,7 +20,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE,
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the eviction file holds the bit-reproducible binary64 score: no fused multiply-add there
 SOURCES = {"decode_kernels.hip": [], "decode_unit.hip": [], "decode_fused.hip": [], "evict_kernels.hip": ["-ffp-contract=off"],
-           "lazyev_api.hip": [], "probe_kernels.hip": []}
+           "lazyev_api.hip": [], "probe_kernels.hip": [], "prefill_kernels.hip": []}
 
 
 def _compile(item):

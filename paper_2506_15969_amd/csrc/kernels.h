@@ -105,6 +105,23 @@ struct EvictArgs {
   Slots slots;            // with slots: n is the largest of the due sequences', t global
 };
 
+// Tracking over the prompt (Alg. 1 first loop and Eq. 1 on the prompt's causal attention).
+struct PrefillArgs {
+  int32_t batch, n_q_heads, n_kv_heads, group;
+  int32_t capacity, prompt_len;
+  int32_t p16;                      // positions per (unit, head) row of `stat`, >= prompt_len
+  int32_t counter_stride;           // activation counters per unit
+  float   alpha, scale;
+  const void *q_prompt;             // [batch][prompt_len][n_q_heads][128] bf16
+  const void *k_cache;              // the layer's slab
+  int32_t *ts, *mri;                // the layer's slab
+  float2 *stat;                     // [units][group][p16] softmax (max, 1 / sum), workspace
+  float *p_out;                     // [batch][n_q_heads][prompt_len][prompt_len] or null
+  const float *p_override;          // same shape or null
+  unsigned long long *activation_counter;   // the layer's [units][counter_stride] or null
+};
+hipError_t launch_prefill_track(const PrefillArgs &a, hipStream_t stream);
+
 // `ev`, when not null, points at three events recorded before the first kernel, between the two
 // kernels and after the second (per-kernel timing for the profiling aid).
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);

@@ -37,6 +37,7 @@ struct lazyev_ctx {
   int32_t last_layer;
   const float *last_logits, *last_stat;
   int32_t last_p_stride;
+  float2 *prefill_stat;             // workspace of lazyev_prefill_track
   // per-sequence timing (lazyev_admit / lazyev_retire): prompt length (-1: empty slot) and the
   // global step before each sequence's first one; device copies in the workspace.  Off until
   // the first admit or retire: until then every sequence has the configuration's prompt, t0 = 0.
@@ -85,7 +86,7 @@ int32_t capacity_of(const lazyev_config *c) {
 }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, src_index, activations, rows_moved, ticket, hist, slots, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, activations, rows_moved, ticket, hist, slots, total;
   int32_t n_split_max;
 };
 
@@ -104,6 +105,9 @@ Layout layout_of(const lazyev_config *c) {
   l.p_tilde = off;  off = align_up(off + logits_bytes);
   l.logits1 = off;  off = align_up(off + logits_bytes);
   l.stat = off;     off = align_up(off + 2 * units * 16 * sizeof(float));
+  // softmax statistics of every (unit, head, prompt position) for the tracking over the prompt
+  l.prefill_stat = off;
+  off = align_up(off + units * 8 * (static_cast<size_t>(c->prompt_len + 15) / 16 * 16) * 2 * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
@@ -234,6 +238,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->last_layer = -1;
   ctx->last_logits = ctx->last_stat = nullptr;
   ctx->last_p_stride = 0;
+  ctx->prefill_stat = reinterpret_cast<float2 *>(base + l.prefill_stat);
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
@@ -419,6 +424,34 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
       if (ef != hipSuccess) return fail_hip(ctx, ef);
     }
   }
+  return LAZYEV_OK;
+}
+
+int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt, float *p_out,
+                         const float *p_override) {
+  if (!ctx || !q_prompt) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || ctx->group > 8) return LAZYEV_EINVAL;
+  if (ctx->slots_on || c.prompt_len < 1) return LAZYEV_EINVAL;
+  if (ctx->last_step[layer] != 0) return LAZYEV_EINVAL;       // the layer has already decoded
+  const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
+  lazyev::PrefillArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.group = ctx->group;
+  a.capacity = ctx->capacity; a.prompt_len = c.prompt_len;
+  a.p16 = (c.prompt_len + 15) / 16 * 16;
+  a.counter_stride = lazyev::decode_slice_max();
+  a.alpha = c.alpha; a.scale = ctx->scale;
+  a.q_prompt = q_prompt;
+  a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * 2;
+  a.ts = c.ts + static_cast<size_t>(layer) * slab;
+  a.mri = c.mri + static_cast<size_t>(layer) * slab;
+  a.stat = ctx->prefill_stat;
+  a.p_out = p_out; a.p_override = p_override;
+  a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
+  const hipError_t e = lazyev::launch_prefill_track(a, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
   return LAZYEV_OK;
 }
 

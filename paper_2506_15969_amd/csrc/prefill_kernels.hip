@@ -1,0 +1,247 @@
+// Recurrence tracking over the prompt (bf16, head_dim 128): the first loop of Alg. 1 and Eq. 1 of
+// the paper applied to the prompt's own causal attention, so that prompt entries enter the
+// decode phase with a TS / MRI history instead of TS = 0, MRI = 0.  Prompt position i (0-based,
+// P positions) acts as the query of step tau_i = i + 1 - P over the keys 0..i; entry i is born
+// with TS = tau_i, MRI = 0; decoding continues at step 1.
+//
+// Two kernels, both built on S^T = K Q^T tiles of v_mfma_f32_16x16x32_bf16 (16 keys x 16
+// queries of ONE head), operands loaded straight into the MFMA layouts
+//   A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]     (lane l, c = l % 16, g = l / 16):
+//   stats  a wave keeps 64 queries of one head in registers (four B operands), walks the key
+//          tiles 0..its own and keeps the running softmax maximum and sum of every query;
+//          leaves (max, 1 / sum) per (unit, head, position) in the workspace
+//   track  a wave keeps 64 keys in registers (four A operands), walks the query tiles from its
+//          own upwards, for every head recomputes the logits (same operands, same order of
+//          accumulation: bitwise the logits of the first kernel), p = exp(s - max) / sum,
+//          tests p >= alpha over the group, and applies the activations of each key in order
+//          of the query position (one key per lane).
+// Four products per streamed tile: the streamed tiles come from the caches, and one 4 KB tile
+// per 16x16x128 product leaves the matrix cores waiting for them (a 2048-token prompt of the
+// benchmark's third workload: 13.0 ms per layer with one product per tile, 5.4 with four, 5.7
+// with eight, where the registers allow only two waves per SIMD).
+// Neither kernel has a barrier or waits for another wave.
+#include "kernels.h"
+
+namespace lazyev {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / 64;
+constexpr int D = 128;
+constexpr int KC = D / 32;
+constexpr int kHeadMax = 8;
+
+typedef unsigned short bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+
+// 16 rows x 128 columns of bf16 at `rows` (row stride `stride` elements), rows clamped to
+// `last`, as an MFMA A or B operand: lane (c, g) takes row c, columns 32 kk + 8 g .. + 7.
+__device__ __forceinline__ void load_operand(u32x4_t (&x)[KC], const bf16_t *rows, int first, int last,
+                                             size_t stride, int c, int g) {
+  const int r = min(first + c, last);
+  const bf16_t *p = rows + static_cast<size_t>(r) * stride + g * 8;
+#pragma unroll
+  for (int kk = 0; kk < KC; ++kk) x[kk] = *reinterpret_cast<const u32x4_t *>(p + kk * 32);
+}
+
+__device__ __forceinline__ f32x4_t logits_tile(const u32x4_t (&ka)[KC], const u32x4_t (&qb)[KC]) {
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < KC; ++kk)
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[kk]),
+                                                  __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+  return acc;
+}
+
+constexpr int NB = 4;                              // tiles a wave keeps in registers
+constexpr int kSpan = 16 * NB;                     // queries (stats) or keys (track) per wave
+
+// Softmax statistics of every (head, prompt position) of a unit:
+// blocks = units * G * ceil(P / (4 * kSpan)).
+__global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int P = a.prompt_len, G = a.group;
+  const int n_qt = (P + kWaves * kSpan - 1) / (kWaves * kSpan);
+  int b = blockIdx.x;
+  int qt = b % n_qt;  b /= n_qt;
+  // Consecutive blocks go to different XCDs, and late tiles carry more work than early ones:
+  // rotated by the (unit, head) index so that every XCD gets every tile position equally often.
+  qt = (qt + b) % n_qt;
+  const int h = b % G;
+  const int unit = b / G;
+  const int i0 = (qt * kWaves + wave) * kSpan;     // this wave's queries: i0 .. i0 + kSpan - 1
+  if (i0 >= P) return;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
+                    (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G + h) * D;
+  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
+  u32x4_t qb[NB][KC];
+#pragma unroll
+  for (int n = 0; n < NB; ++n)
+    load_operand(qb[n], q, i0 + 16 * n, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+
+  float m[NB], l[NB];                              // of query i0 + 16 n + c (the four lanes of a column agree)
+#pragma unroll
+  for (int n = 0; n < NB; ++n) { m[n] = -INFINITY; l[n] = 0.f; }
+  const int last_tile = min(i0 + kSpan - 1, P - 1) >> 4;
+  u32x4_t ka[KC];
+  load_operand(ka, kc, 0, P - 1, D, c, g);
+  for (int jt = 0; jt <= last_tile; ++jt) {
+    u32x4_t kn[KC];                                // the next key tile travels during the arithmetic
+    load_operand(kn, kc, min(jt + 1, last_tile) * 16, P - 1, D, c, g);
+    // all four products, no branches: keys newer than a query (only in the wave's last three
+    // tiles) and positions beyond the prompt count as -inf
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      const f32x4_t acc = logits_tile(ka, qb[n]);
+      float s[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = jt * 16 + 4 * g + i;
+        s[i] = (key <= i0 + 16 * n + c && key < P) ? acc[i] * a.scale : -INFINITY;
+      }
+      float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m[n], tmax);       // finite from the first tile on: key 0 <= every query
+      float ps = (__expf(s[0] - m_new) + __expf(s[1] - m_new)) + (__expf(s[2] - m_new) + __expf(s[3] - m_new));
+      ps += __shfl_xor(ps, 16);
+      ps += __shfl_xor(ps, 32);
+      l[n] = l[n] * __expf(m[n] - m_new) + ps;     // first tile: l = 0 * exp(-inf) + ps
+      m[n] = m_new;
+    }
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) ka[kk] = kn[kk];
+  }
+  if (g == 0) {
+    float2 *st = a.stat + (static_cast<size_t>(unit) * G + h) * a.p16;
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+      if (i0 + 16 * n + c < P) st[i0 + 16 * n + c] = make_float2(m[n], 1.0f / l[n]);
+  }
+}
+
+// Tracking: blocks = units * ceil(P / (4 * kSpan)); a wave owns the keys j0 .. j0 + kSpan - 1.
+// kIO: the weights are exported and / or replaced (a checker's route); without it the loop
+// has no branches.
+template <bool kIO>
+__global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int P = a.prompt_len, G = a.group;
+  const int n_kt = (P + kWaves * kSpan - 1) / (kWaves * kSpan);
+  const int unit = blockIdx.x / n_kt;
+  const int kt = (blockIdx.x % n_kt + unit) % n_kt;   // rotated like the tiles of the first kernel (early keys carry more work)
+  const int j0 = (kt * kWaves + wave) * kSpan;
+  if (j0 >= P) return;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
+                    (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G) * D;
+  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
+  const float2 *stat = a.stat + static_cast<size_t>(unit) * G * a.p16;
+  u32x4_t ka[NB][KC];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) load_operand(ka[n], kc, j0 + 16 * n, P - 1, D, c, g);
+
+  // lane (c, g) carries the state of key row 4 g + (c & 3) of key tile c >> 2
+  const int my_key = j0 + 16 * (c >> 2) + 4 * g + (c & 3);
+  int32_t ts = my_key + 1 - P, mri = 0;
+  unsigned n_act = 0;
+  // (query tile, head) pairs in order; the operands of the next pair travel during the
+  // arithmetic of the current one
+  int it = j0 >> 4, h = 0;
+  u32x4_t qb[KC];
+  load_operand(qb, q, it * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+  float2 st = stat[min(it * 16 + c, P - 1)];
+  unsigned act = 0;                                // bit 4 n + i: key row 4 g + i of key tile n is active for query qi
+  while (it * 16 < P) {
+    int h2 = h + 1, it2 = it;
+    if (h2 == G) { h2 = 0; ++it2; }
+    const int itn = it2 * 16 < P ? it2 : it, hn = it2 * 16 < P ? h2 : h;   // (the last pair is loaded twice)
+    u32x4_t qn[KC];
+    load_operand(qn, q + static_cast<size_t>(hn) * D, itn * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+    const float2 stn = stat[static_cast<size_t>(hn) * a.p16 + min(itn * 16 + c, P - 1)];
+    const int qi = it * 16 + c;                    // this lane's query column
+    // all four products: keys newer than the query (only in the wave's first three tiles),
+    // and positions beyond the prompt, are masked
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      const f32x4_t acc = logits_tile(ka[n], qb);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = j0 + 16 * n + 4 * g + i;
+        const bool seen = key <= qi && qi < P;     // (key <= qi < P implies key < P)
+        float p = __expf(acc[i] * a.scale - st.x) * st.y;
+        if (kIO) {
+          if (seen) {
+            const size_t at = ((static_cast<size_t>(seq) * a.n_q_heads + kvh * G + h) * P + qi) * P + key;
+            if (a.p_out) a.p_out[at] = p;
+            if (a.p_override) p = a.p_override[at];
+          }
+        }
+        act |= (seen && p >= a.alpha) ? 1u << (4 * n + i) : 0u;
+      }
+    }
+    if (h2 == 0) {                                 // the tile's last head: apply its activations
+      if (__builtin_amdgcn_ballot_w64(act != 0) != 0) {
+        // activations of key row 4 g' + i of key tile n over the tile's 16 queries: bits
+        // 16 g' .. 16 g' + 15 of the ballot of bit 4 n + i; lane (c, g) wants the one with 4 n + i = c
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int bit = 0; bit < 4 * NB; ++bit) {
+          const unsigned long long bal = __builtin_amdgcn_ballot_w64((act >> bit) & 1u);
+          if (c == bit) mine = bal;
+        }
+        unsigned mask = static_cast<unsigned>(mine >> (16 * g)) & 0xFFFFu;
+        n_act += __popc(mask);
+        while (mask) {                             // in order of the query position (Alg. 1, Eq. 1)
+          const int32_t tau = it * 16 + __builtin_ctz(mask) + 1 - P;
+          mask &= mask - 1;
+          const int32_t gap = tau - ts;
+          if (gap > mri) mri = gap;
+          ts = tau;
+        }
+      }
+      act = 0;
+    }
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) qb[kk] = qn[kk];
+    st = stn;
+    it = it2;
+    h = h2;
+  }
+  if (my_key < P) {
+    a.ts[static_cast<size_t>(unit) * a.capacity + my_key] = ts;
+    a.mri[static_cast<size_t>(unit) * a.capacity + my_key] = mri;
+  }
+  if (a.activation_counter) {
+    for (int o = 32; o > 0; o >>= 1) n_act += __shfl_xor(n_act, o);
+    if (lane == 0 && n_act) atomicAdd(a.activation_counter + unit * a.counter_stride, static_cast<unsigned long long>(n_act));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_track(const PrefillArgs &a, hipStream_t stream) {
+  if (a.prompt_len < 1 || a.prompt_len > a.capacity || a.group < 1 || a.group > kHeadMax ||
+      a.n_q_heads != a.n_kv_heads * a.group || a.batch < 1 || a.p16 < (a.prompt_len + 15) / 16 * 16 ||
+      !a.q_prompt || !a.k_cache || !a.ts || !a.mri || !a.stat || a.counter_stride < 1)
+    return hipErrorInvalidValue;
+  const long long units = static_cast<long long>(a.batch) * a.n_kv_heads;
+  const long long n_t = (a.prompt_len + kWaves * kSpan - 1) / (kWaves * kSpan);
+  if (units * a.group * n_t > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(prefill_stats_kernel, dim3(static_cast<unsigned>(units * a.group * n_t)), dim3(kBlock), 0,
+                     stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.p_out || a.p_override)
+    hipLaunchKernelGGL(prefill_track_kernel<true>, dim3(static_cast<unsigned>(units * n_t)), dim3(kBlock), 0, stream, a);
+  else
+    hipLaunchKernelGGL(prefill_track_kernel<false>, dim3(static_cast<unsigned>(units * n_t)), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace lazyev

@@ -35,7 +35,7 @@ _MIX1 = 0xBF58476D1CE4E5B9
 _MIX2 = 0x94D049BB133111EB
 _SECOND = 0xD6E8FEB86659FD93
 
-STREAM_K, STREAM_V, STREAM_Q = 1, 2, 3
+STREAM_K, STREAM_V, STREAM_Q, STREAM_QP = 1, 2, 3, 4
 
 # float32 factor that turns the centred eight-field sum into a unit-variance value
 _UNIT_SCALE = float(np.float32(1.0 / math.sqrt(8.0 * (65536.0 ** 2 - 1.0) / 12.0)))
@@ -135,7 +135,7 @@ class Workload:
 
     def __init__(self, cfg: WorkloadConfig):
         self.cfg = cfg
-        self._base = {s: _mix_py(cfg.seed * _GOLDEN + s * _SECOND) for s in (1, 2, 3)}
+        self._base = {s: _mix_py(cfg.seed * _GOLDEN + s * _SECOND) for s in (1, 2, 3, 4)}
         self._events_t, self._events_j = self._firing_schedule()
 
     # ---- planted recurring keys: host-side schedule (plain numpy, seeded) ---------------
@@ -219,6 +219,31 @@ class Workload:
 
     def prompt_kv(self, layer: int, device="cpu", seq=None, kv_head=None):
         return self.kv_rows(layer, range(self.cfg.prompt_len), device, seq, kv_head)
+
+    def prompt_queries(self, layer: int, device="cpu", seq=None, kv_head=None):
+        """Queries of the prompt positions, [len(seq), P, len(kv_head)*G, d] (for the tracking over
+        the prompt).  Noise, plus for position i >= 32 four times the key of position
+        (5 i) mod 32 on query head i mod G (each of the first 32 keys is read again every 32
+        positions), plus the sink term of the decode queries."""
+        c = self.cfg
+        G, P = c.group, c.prompt_len
+        seq = list(range(c.batch) if seq is None else seq)
+        kv_head = list(range(c.n_kv_heads) if kv_head is None else kv_head)
+        q_heads = [h * G + g for h in kv_head for g in range(G)]
+        q = self._noise(STREAM_QP, layer, range(P), seq, q_heads, c.n_q_heads, device)   # [P,s,hq,d]
+        q = q.view(P, len(seq), len(kv_head), G, c.head_dim)
+        if P > 32:
+            k_hot = self._k_int(layer, range(32), seq, kv_head, device)                # [32,s,h,d]
+            i = torch.arange(32, P, device=q.device)
+            flat = q.permute(0, 3, 1, 2, 4).contiguous().view(P * G, len(seq), len(kv_head), c.head_dim)
+            flat.index_add_(0, i * G + i % G, 4 * k_hot[(5 * i) % 32])
+            q = flat.view(P, G, len(seq), len(kv_head), c.head_dim).permute(0, 2, 3, 1, 4)
+        if c.n_sink:
+            gain = int(round(32.0 * 6.0 / math.sqrt(c.head_dim)))
+            k_sink = self._k_int(layer, range(c.n_sink), seq, kv_head, device).sum(dim=0)
+            q = q + ((k_sink * gain) >> 5).view(1, len(seq), len(kv_head), 1, c.head_dim)
+        q = self._finish(q.reshape(P, len(seq), len(kv_head) * G, c.head_dim).contiguous())
+        return q.permute(1, 0, 2, 3).contiguous()
 
     # ---- per-step inputs -----------------------------------------------------------------
     def step_inputs(self, layer: int, t0: int, t1: int, device="cpu", seq=None, kv_head=None):
