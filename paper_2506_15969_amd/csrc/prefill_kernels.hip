@@ -12,7 +12,7 @@
 //          leaves (max, 1 / sum) per (unit, head, position) in the workspace
 //   track  a wave keeps 64 keys in registers (four A operands), walks the query tiles from its
 //          own upwards, for every head recomputes the logits (same operands, same order of
-//          accumulation: bitwise the logits of the first kernel), p = exp(s - max) / sum,
+//          accumulation: the logits of the first kernel), p = exp(s - max) / sum,
 //          tests p >= alpha over the group, and applies the activations of each key in order
 //          of the query position (one key per lane).
 // Four products per streamed tile: the streamed tiles come from the caches, and one 4 KB tile
@@ -58,6 +58,33 @@ __device__ __forceinline__ f32x4_t logits_tile(const u32x4_t (&ka)[KC], const u3
 constexpr int NB = 4;                              // tiles a wave keeps in registers
 constexpr int kSpan = 16 * NB;                     // queries (stats) or keys (track) per wave
 
+constexpr float kLog2e = 1.4426950408889634f;
+
+// One key tile against one query tile in the statistics kernel.  Logits are kept in units of
+// log 2 (scaled by scale * log2(e)), so an exponential is one v_exp_f32.  kMask: the tile may
+// hold keys newer than a query or positions beyond the prompt.
+template <bool kMask>
+__device__ __forceinline__ void stats_tile(const u32x4_t (&ka)[KC], const u32x4_t (&qb)[KC], float c2, int key0,
+                                           int query, int P, float &m, float &l) {
+  const f32x4_t acc = logits_tile(ka, qb);
+  float s[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    s[i] = acc[i] * c2;
+    if (kMask) s[i] = (key0 + i <= query && key0 + i < P) ? s[i] : -INFINITY;
+  }
+  float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+  const float m_new = fmaxf(m, tmax);              // finite from the first tile on: key 0 <= every query
+  float ps = (__builtin_amdgcn_exp2f(s[0] - m_new) + __builtin_amdgcn_exp2f(s[1] - m_new)) +
+             (__builtin_amdgcn_exp2f(s[2] - m_new) + __builtin_amdgcn_exp2f(s[3] - m_new));
+  ps += __shfl_xor(ps, 16);
+  ps += __shfl_xor(ps, 32);
+  l = l * __builtin_amdgcn_exp2f(m - m_new) + ps;  // first tile: l = 0 * 2^(-inf) + ps
+  m = m_new;
+}
+
 // Softmax statistics of every (head, prompt position) of a unit:
 // blocks = units * G * ceil(P / (4 * kSpan)).
 __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs a) {
@@ -78,6 +105,7 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
                     (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G + h) * D;
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
+  const float c2 = a.scale * kLog2e;
   u32x4_t qb[NB][KC];
 #pragma unroll
   for (int n = 0; n < NB; ++n)
@@ -92,31 +120,19 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   for (int jt = 0; jt <= last_tile; ++jt) {
     u32x4_t kn[KC];                                // the next key tile travels during the arithmetic
     load_operand(kn, kc, min(jt + 1, last_tile) * 16, P - 1, D, c, g);
-    // all four products, no branches: keys newer than a query (only in the wave's last three
-    // tiles) and positions beyond the prompt count as -inf
+    // all four products, no branches inside; only the wave's last four key tiles can hold keys
+    // newer than a query (or positions beyond the prompt)
+    if (jt * 16 + 15 <= i0 && jt * 16 + 15 < P) {
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const f32x4_t acc = logits_tile(ka, qb[n]);
-      float s[4];
+      for (int n = 0; n < NB; ++n) stats_tile<false>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
+    } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = jt * 16 + 4 * g + i;
-        s[i] = (key <= i0 + 16 * n + c && key < P) ? acc[i] * a.scale : -INFINITY;
-      }
-      float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m[n], tmax);       // finite from the first tile on: key 0 <= every query
-      float ps = (__expf(s[0] - m_new) + __expf(s[1] - m_new)) + (__expf(s[2] - m_new) + __expf(s[3] - m_new));
-      ps += __shfl_xor(ps, 16);
-      ps += __shfl_xor(ps, 32);
-      l[n] = l[n] * __expf(m[n] - m_new) + ps;     // first tile: l = 0 * exp(-inf) + ps
-      m[n] = m_new;
+      for (int n = 0; n < NB; ++n) stats_tile<true>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
     }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) ka[kk] = kn[kk];
   }
-  if (g == 0) {
+  if (g == 0) {                                    // (max in units of log 2, 1 / sum)
     float2 *st = a.stat + (static_cast<size_t>(unit) * G + h) * a.p16;
 #pragma unroll
     for (int n = 0; n < NB; ++n)
@@ -125,8 +141,7 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
 }
 
 // Tracking: blocks = units * ceil(P / (4 * kSpan)); a wave owns the keys j0 .. j0 + kSpan - 1.
-// kIO: the weights are exported and / or replaced (a checker's route); without it the loop
-// has no branches.
+// kIO: the weights are exported and / or replaced (a checker's route).
 template <bool kIO>
 __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -142,6 +157,7 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
                     (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G) * D;
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
   const float2 *stat = a.stat + static_cast<size_t>(unit) * G * a.p16;
+  const float c2 = a.scale * kLog2e;
   u32x4_t ka[NB][KC];
 #pragma unroll
   for (int n = 0; n < NB; ++n) load_operand(ka[n], kc, j0 + 16 * n, P - 1, D, c, g);
@@ -156,7 +172,11 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   u32x4_t qb[KC];
   load_operand(qb, q, it * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
   float2 st = stat[min(it * 16 + c, P - 1)];
-  unsigned act = 0;                                // bit 4 n + i: key row 4 g + i of key tile n is active for query qi
+  // bal[4 n + i]: wave mask (bit 16 g + c) of "key row 4 g + i of key tile n is active for
+  // query column c" over the heads of the current query tile: the compare masks themselves
+  unsigned long long bal[4 * NB];
+#pragma unroll
+  for (int x = 0; x < 4 * NB; ++x) bal[x] = 0;
   while (it * 16 < P) {
     int h2 = h + 1, it2 = it;
     if (h2 == G) { h2 = 0; ++it2; }
@@ -165,36 +185,51 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
     load_operand(qn, q + static_cast<size_t>(hn) * D, itn * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
     const float2 stn = stat[static_cast<size_t>(hn) * a.p16 + min(itn * 16 + c, P - 1)];
     const int qi = it * 16 + c;                    // this lane's query column
-    // all four products: keys newer than the query (only in the wave's first three tiles),
-    // and positions beyond the prompt, are masked
+    // every key of the wave exists and is no newer than any query of the tile, and every
+    // query of the tile exists: nothing to mask (all but the wave's first four query tiles,
+    // the prompt's last tile and its last wave)
+    const bool plain = !kIO && j0 + kSpan - 1 <= it * 16 && j0 + kSpan - 1 < P && it * 16 + 15 < P;
+    if (plain) {
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-      const f32x4_t acc = logits_tile(ka[n], qb);
+      for (int n = 0; n < NB; ++n) {
+        const f32x4_t acc = logits_tile(ka[n], qb);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = j0 + 16 * n + 4 * g + i;
-        const bool seen = key <= qi && qi < P;     // (key <= qi < P implies key < P)
-        float p = __expf(acc[i] * a.scale - st.x) * st.y;
-        if (kIO) {
-          if (seen) {
-            const size_t at = ((static_cast<size_t>(seq) * a.n_q_heads + kvh * G + h) * P + qi) * P + key;
-            if (a.p_out) a.p_out[at] = p;
-            if (a.p_override) p = a.p_override[at];
-          }
+        for (int i = 0; i < 4; ++i) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, -st.x)) * st.y;
+          bal[4 * n + i] |= __builtin_amdgcn_ballot_w64(p >= a.alpha);
         }
-        act |= (seen && p >= a.alpha) ? 1u << (4 * n + i) : 0u;
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        const f32x4_t acc = logits_tile(ka[n], qb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = j0 + 16 * n + 4 * g + i;
+          const bool seen = key <= qi && qi < P;   // (key <= qi < P implies key < P)
+          float p = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, -st.x)) * st.y;
+          if (kIO) {
+            if (seen) {
+              const size_t at = ((static_cast<size_t>(seq) * a.n_q_heads + kvh * G + h) * P + qi) * P + key;
+              if (a.p_out) a.p_out[at] = p;
+              if (a.p_override) p = a.p_override[at];
+            }
+          }
+          bal[4 * n + i] |= __builtin_amdgcn_ballot_w64(seen && p >= a.alpha);
+        }
       }
     }
     if (h2 == 0) {                                 // the tile's last head: apply its activations
-      if (__builtin_amdgcn_ballot_w64(act != 0) != 0) {
-        // activations of key row 4 g' + i of key tile n over the tile's 16 queries: bits
-        // 16 g' .. 16 g' + 15 of the ballot of bit 4 n + i; lane (c, g) wants the one with 4 n + i = c
-        unsigned long long mine = 0;
+      // key row 4 g' + i of key tile n over the tile's 16 queries: bits 16 g' .. 16 g' + 15 of
+      // bal[4 n + i]; lane (c, g) wants the one with 4 n + i = c
+      unsigned long long mine = 0, any = 0;
 #pragma unroll
-        for (int bit = 0; bit < 4 * NB; ++bit) {
-          const unsigned long long bal = __builtin_amdgcn_ballot_w64((act >> bit) & 1u);
-          if (c == bit) mine = bal;
-        }
+      for (int x = 0; x < 4 * NB; ++x) {
+        if (c == x) mine = bal[x];
+        any |= bal[x];
+        bal[x] = 0;
+      }
+      if (any != 0) {                              // (wave-uniform)
         unsigned mask = static_cast<unsigned>(mine >> (16 * g)) & 0xFFFFu;
         n_act += __popc(mask);
         while (mask) {                             // in order of the query position (Alg. 1, Eq. 1)
@@ -205,7 +240,6 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
           ts = tau;
         }
       }
-      act = 0;
     }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) qb[kk] = qn[kk];
