@@ -233,7 +233,14 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
  *   3  one MFMA block per unit, no merge kernel and no workspace traffic (bf16, head_dim 128,
  *      group * capacity small enough for the logits of a unit to stay in LDS);
  *   4  one launch: MFMA stream blocks, the block that finishes a unit last merges the partials
- *      into the output; the tracking rides with the next launch (bf16, head_dim 128);
+ *      into the output; the tracking rides with the next launch (bf16, head_dim 128).  Over a
+ *      cache of 1792 entries or more a block leaves only the logits of entries that can still
+ *      reach alpha for the tracking; it leaves all of them over a shorter cache, when the
+ *      caller passes p_out / p_override, with LAZYEV_SCORE_CURRENT_ATTENTION, with 8 query
+ *      heads per KV head, or when a block owns more than 1280 entries;
+ *   5  kernel 4 leaving every logit in all cases, 6 kernel 4 leaving only those of the entries
+ *      that can reach alpha also over short caches (same results bit for bit; for comparison
+ *      and tests);
  *   1  (default) picks 4 when it applies, else 0.
  * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0, 4 -> 0.
  * Errors: EINVAL. */

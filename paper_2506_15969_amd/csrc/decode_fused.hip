@@ -32,6 +32,14 @@
 // entry) while the new call streams; lazyev_evict and lazyev_stats apply what is pending
 // through track_kernel.  Logits and statistics are double-buffered.
 //
+// Candidate lists (kernel instance <true>, groups of at most 7 heads).  A block knows, once its
+// four waves have merged, its own share of every head's softmax denominator, which bounds the
+// true denominator from below: an entry whose weight relative to the BLOCK's denominator
+// stays under alpha in every head cannot reach alpha.  The block then writes only the other
+// entries ("candidates", about a tenth on the benchmark workloads; the appended entry always)
+// as records (7 logits, entry index) into its own region of the logits buffer, and the
+// tracking applies the exact test to the records: the same state bit for bit.
+//
 // MFMA operand layouts (lane l, c = l % 16, g = l / 16):
 //   16x16x32: A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]
 //   16x16x16: A[row c][k = 4g..4g+3]  B[k = 4g..4g+3][col c]  C[row 4g+i][col c]
@@ -127,6 +135,37 @@ __device__ __forceinline__ void track_load(const TrackArgs &k, int unit, int par
   }
 }
 
+// The activation test and the TS / MRI update of entry i (Alg. 1, Eq. 1); true if active.
+__device__ __forceinline__ bool track_one(const TrackArgs &k, int unit, int i, const float (&s)[kHeadPad],
+                                          const float (&m)[kHeadPad], const float (&invl)[kHeadPad]) {
+  const int seq = unit / k.n_kv_heads, kvh = unit % k.n_kv_heads;
+  const int G = k.group;
+  const size_t head0 = static_cast<size_t>(seq) * k.n_q_heads + static_cast<size_t>(kvh) * G;
+  int32_t *ts = k.ts + static_cast<size_t>(unit) * k.capacity;
+  int32_t *mri = k.mri + static_cast<size_t>(unit) * k.capacity;
+  bool act = false;
+#pragma unroll
+  for (int h = 0; h < kHeadPad; ++h) {
+    if (h < G) {
+      float p = __expf(s[h] - m[h]) * invl[h];
+      const size_t at = (head0 + h) * k.capacity + i;
+      if (k.p_out) k.p_out[at] = p;
+      if (k.p_override) p = k.p_override[at];
+      act = act || (p >= k.alpha);
+    }
+  }
+  if (i == k.n_old) {                              // the appended entry starts here (Sec. 4)
+    ts[i] = k.t;
+    mri[i] = 0;
+    k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
+  } else if (act) {                                // few entries are active: TS / MRI are read only here
+    const int32_t gap = k.t - ts[i];
+    if (gap > mri[i]) mri[i] = gap;                // Eq. 1
+    ts[i] = k.t;                                   // Alg. 1
+  }
+  return act;
+}
+
 __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, int part, int n_parts,
                                                 int r0, const TrackBatch &b, const float (&m)[kHeadPad],
                                                 const float (&invl)[kHeadPad]) {
@@ -164,6 +203,31 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
       ts[i] = k.t;                                 // Alg. 1
     }
     n_act += act ? 1u : 0u;
+  }
+  return n_act;
+}
+
+// Slots of a block's region of candidate records in a call with n_parts blocks per unit: one
+// for the count and one for each entry the block can own.
+__host__ __device__ inline int fused_part_cap(int n_old, int n_parts) {
+  const int n_sub = (n_old + 1 + 15) >> 4;
+  return (n_sub + kWaves * n_parts - 1) / (kWaves * n_parts) * (kWaves * 16) + 1;
+}
+
+// Tracking from the candidate records of the call's blocks b = part, part + step, ...
+__device__ __forceinline__ unsigned track_records(const TrackArgs &k, int unit, int part, int step,
+                                                  const float (&m)[kHeadPad], const float (&invl)[kHeadPad]) {
+  const int cap = fused_part_cap(k.n_old, k.n_parts);
+  unsigned n_act = 0;
+  for (int b = part; b < k.n_parts; b += step) {
+    const float *region = k.logits + (static_cast<size_t>(unit) * k.p_stride + static_cast<size_t>(b) * cap) * kHeadPad;
+    const int n = *reinterpret_cast<const int32_t *>(region);
+    for (int r = threadIdx.x; r < n; r += kBlock) {
+      const float4 sa = *reinterpret_cast<const float4 *>(region + static_cast<size_t>(1 + r) * kHeadPad);
+      const float4 sb = *reinterpret_cast<const float4 *>(region + static_cast<size_t>(1 + r) * kHeadPad + 4);
+      const float s[kHeadPad] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, 0.f};
+      n_act += track_one(k, unit, __float_as_int(sb.w), s, m, invl) ? 1u : 0u;
+    }
   }
   return n_act;
 }
@@ -211,11 +275,15 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
   float m[kHeadPad], invl[kHeadPad];
   track_stats(k, unit, m, invl);
   unsigned n_act = 0;
-  const int rounds = (k.n_old + 1 + n_parts * kBlock - 1) / (n_parts * kBlock);
-  for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
-    TrackBatch b;
-    track_load(k, unit, part, n_parts, r0, b);
-    n_act += track_apply(k, unit, part, n_parts, r0, b, m, invl);
+  if (k.compact) {
+    n_act = track_records(k, unit, part, n_parts, m, invl);
+  } else {
+    const int rounds = (k.n_old + 1 + n_parts * kBlock - 1) / (n_parts * kBlock);
+    for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
+      TrackBatch b;
+      track_load(k, unit, part, n_parts, r0, b);
+      n_act += track_apply(k, unit, part, n_parts, r0, b, m, invl);
+    }
   }
   track_count(k, unit, part, n_act, cnt_lds);
 }
@@ -328,6 +396,8 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
 }
 
 // ------------------------------------------------------------------------------- the kernel
+// kCompact: this call leaves candidate lists instead of every logit.
+template <bool kCompact>
 __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArgs a) {
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
   // one 16-row K sub-tile per wave while streaming; afterwards the wave's output accumulator
@@ -335,6 +405,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   extern __shared__ float logit_lds[];             // [kWaves][min(run, kRunMax)][16 entries][8 heads]
   __shared__ unsigned cnt_lds[kWaves];
   __shared__ int last_flag;
+  __shared__ unsigned cand_total;                  // candidate records of this block so far
 
   const int G = a.group, n_split = a.n_split;
   if (static_cast<int>(blockIdx.x) >= n_split * a.batch * a.n_kv_heads) {
@@ -347,17 +418,22 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     float m[kHeadPad], invl[kHeadPad];
     track_stats(k, unit, m, invl);
     unsigned n_act = 0;
-    const int rounds = (k.n_old + 1 + n_split * kBlock - 1) / (n_split * kBlock);
-    for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
-      TrackBatch b;
-      track_load(k, unit, part, n_split, r0, b);
-      n_act += track_apply(k, unit, part, n_split, r0, b, m, invl);
+    if (k.compact) {
+      n_act = track_records(k, unit, part, n_split, m, invl);
+    } else {
+      const int rounds = (k.n_old + 1 + n_split * kBlock - 1) / (n_split * kBlock);
+      for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
+        TrackBatch b;
+        track_load(k, unit, part, n_split, r0, b);
+        n_act += track_apply(k, unit, part, n_split, r0, b, m, invl);
+      }
     }
     track_count(k, unit, part, n_act, cnt_lds);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: scalar branches below
+  if (kCompact && tid == 0) cand_total = 0;        // (the block barrier after the stream orders it)
   const int c = lane & 15, g = lane >> 4;
   const int unit = blockIdx.x / n_split, split = blockIdx.x % n_split;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
@@ -508,7 +584,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
     compute(buf, it);
     if (it + 1 - seg0 == kRunMax && it + 1 < cnt) { flush(seg0, it + 1); seg0 = it + 1; }
   }
-  flush(seg0, cnt);
+  if (!kCompact) flush(seg0, cnt);
   // ---- the four waves of the block -> one partial
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
@@ -562,6 +638,58 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
       store_f32_device(ml + G + tid, l);
     }
   }
+  if (kCompact) {
+    // ---- candidates of the tracking: this wave's entries that can reach alpha in some head.
+    // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
+    // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the
+    // two sides.  Lane h < 8 works out the cut of head h, everybody reads the eight cuts.
+    const int hh = lane & 7;
+    float mbh = m_lds[0][hh];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, m_lds[w][hh]);
+    float lbh = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float mw = m_lds[w][hh];
+      if (mw != -INFINITY) lbh = fmaf(__expf(mw - mbh), lsum_lds[w][hh], lbh);
+    }
+    const float cut_h = (hh < G && lbh > 0.f) ? mbh + __logf(0.98f * a.alpha * lbh) : INFINITY;
+    float cut[kHeadPad];
+#pragma unroll
+    for (int h = 0; h < kHeadPad; ++h)
+      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
+    float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
+    const int e_in = lane & 15;
+    for (int it0 = 0; it0 < cnt; it0 += 4) {       // four sub-tiles per round, one entry per lane
+      const int it = it0 + (lane >> 4);
+      bool cand = false;
+      int entry = 0;
+      f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = sa;
+      if (it < cnt) {
+        const float *src = my_logits + it * (16 * kHeadPad) + e_in * kHeadPad;
+        sa = *reinterpret_cast<const f32x4_t *>(src);
+        sb = *reinterpret_cast<const f32x4_t *>(src + 4);
+        entry = (wv + it * n_wv) * 16 + e_in;
+        cand = sa[0] >= cut[0] || sa[1] >= cut[1] || sa[2] >= cut[2] || sa[3] >= cut[3] ||
+               sb[0] >= cut[4] || sb[1] >= cut[5] || sb[2] >= cut[6];
+        cand = (cand && entry < n1) || entry == n_old;   // the appended entry starts its tracking there
+      }
+      const unsigned long long mask = __builtin_amdgcn_ballot_w64(cand);
+      if (mask != 0) {                             // wave-uniform
+        unsigned base = 0;
+        if (lane == 0) base = atomicAdd(&cand_total, static_cast<unsigned>(__popcll(mask)));
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (cand) {
+          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
+          sb[3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa;
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb;
+        }
+      }
+    }
+  }
   // the appended row goes to slot N (everybody read it from k_new / v_new)
   if (split == 0 && wave == 1) {
     if (lane < 16)
@@ -579,6 +707,10 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
                                             __HIP_MEMORY_SCOPE_AGENT);   // ... before its ticket is taken
     last_flag = (prev == n_split - 1);
     if (prev == n_split - 1) a.ticket[unit] = 0;   // ready for the next launch
+    if (kCompact)
+      *reinterpret_cast<int32_t *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                                   static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad) =
+          static_cast<int32_t>(cand_total);
   }
   __syncthreads();
   if (!last_flag) return;
@@ -592,12 +724,20 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
 int decode_fused_split_max() { return kFusedSplitMax; }
 int decode_fused_head_pad() { return kHeadPad; }
 
+bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group) {
+  if (n_split < 1 || n_split > kFusedSplitMax || group >= kHeadPad) return false;
+  const int cap = fused_part_cap(n_old, n_split);
+  return (cap - 1) / (kWaves * 16) <= kRunMax && static_cast<long long>(cap) * n_split <= p_stride;
+}
+
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
   if (!k.valid || k.units < 1 || k.group > kHeadPad || !k.logits || !k.stat ||
       k.p_stride < (k.n_old + 16) / 16 * 16)
     return hipErrorInvalidValue;
+  if (k.compact && !decode_fused_compact_fits(k.n_old, k.n_parts, k.p_stride, k.group)) return hipErrorInvalidValue;
   int n_parts = (k.n_old + 1 + 2 * kBlock - 1) / (2 * kBlock);   // about two entries per thread
   if (n_parts > 64) n_parts = 64;
+  if (k.compact) n_parts = k.n_parts;              // one block per block of the call
   hipLaunchKernelGGL(track_kernel, dim3(k.units * n_parts), dim3(kBlock), 0, stream, k, n_parts);
   return hipGetLastError();
 }
@@ -608,7 +748,10 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
       a.n_split > kFusedSplitMax || a.n_split > a.n_split_max || !a.ticket || !a.logits_out ||
       !a.stat_out || a.p_stride < (a.n_old + 16) / 16 * 16 ||
       (a.track.valid && (a.track.units != units || !a.track.logits || !a.track.stat ||
-                         a.track.logits == a.logits_out || a.track.stat == a.stat_out)))
+                         a.track.logits == a.logits_out || a.track.stat == a.stat_out)) ||
+      (a.track.valid && a.track.compact &&
+       !decode_fused_compact_fits(a.track.n_old, a.track.n_parts, a.track.p_stride, a.track.group)) ||
+      (a.variant == 6 && (a.p_out || a.p_override || !decode_fused_compact_fits(a.n_old, a.n_split, a.p_stride, a.group))))
     return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
   const int n_sub = (a.n_old + 1 + 15) / 16;
@@ -616,7 +759,10 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   if (run > kRunMax) run = kRunMax;
   const size_t lds_all = static_cast<size_t>(kWaves) * run * 16 * kHeadPad * sizeof(float);
   const int sb = a.n_split * units;
-  hipLaunchKernelGGL(decode_fused_kernel, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);
+  if (a.variant == 6)
+    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);
+  else
+    hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);
   const hipError_t e = hipGetLastError();
   if (ev) { (void)hipEventRecord(ev[1], stream); (void)hipEventRecord(ev[2], stream); }
   return e;

@@ -662,7 +662,7 @@ int decode_split_max() { return kSplitMaxLds; }
 int decode_slice_max() { return kSliceMax; }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
-  if (a.variant == 4) return launch_decode_fused(a, stream, ev);
+  if (a.variant == 4 || a.variant == 6) return launch_decode_fused(a, stream, ev);
   if (a.variant == 3) return launch_decode_unit(a, stream, ev);
   const bool mfma = a.variant == 2 && a.dtype == 1 && a.head_dim == 128;
   if (a.chunk <= 0 || (!mfma && a.chunk > kChunkMax) || a.n_split > kSplitMaxLds ||

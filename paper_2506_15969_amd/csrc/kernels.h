@@ -57,6 +57,12 @@ struct TrackArgs {
   const float *p_override;
   unsigned long long *activation_counter;   // the call's layer
   Slots slots;                      // with slots: n_old is the largest of the sequences', t global
+  // compact != 0 (fused kernel, groups of at most 7 heads): the logits buffer holds, per block
+  // of the call (n_parts per unit), only the entries that can reach alpha ("candidates").
+  // Block b of a unit owns the slots [b * cap, (b + 1) * cap) of the unit's p_stride slots of 8
+  // floats, cap = fused_part_cap(n_old, n_parts): slot 0 holds the number of records (as an
+  // integer), slot 1 + r record r = the entry's 7 logits and, in the 8th place, its index.
+  int32_t compact, n_parts;
 };
 
 struct DecodeArgs {
@@ -70,7 +76,8 @@ struct DecodeArgs {
   int32_t lds_stride;     // unit kernel: row stride of the logits in LDS
   int32_t lds_stage_offset;  // unit kernel: byte offset of the K staging areas in dynamic LDS
   int32_t variant;        // attention kernel actually launched: 0 vector ALU + merge,
-                          // 2 MFMA split + merge, 3 one MFMA block per unit, 4 fused MFMA
+                          // 2 MFMA split + merge, 3 one MFMA block per unit, 4 fused MFMA,
+                          // 6 fused MFMA leaving candidate lists (see TrackArgs)
   float   alpha, scale;
   int32_t dtype;
   const void *q, *k_new, *v_new;
@@ -130,6 +137,9 @@ hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_
 // One launch per call: split blocks, the last block of a unit merges and tracks (bf16, d 128).
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 int decode_fused_split_max();
+// Can a call with these sizes leave candidate lists (they fit the logits buffer, a wave's logits
+// stay in LDS to the end of its run, and the 8th logit place is free for the entry index)?
+bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group);
 int decode_fused_head_pad();
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
 hipError_t decode_unit_prepare();

@@ -85,6 +85,12 @@ int32_t capacity_of(const lazyev_config *c) {
   return (c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
 }
 
+constexpr int32_t kCompactMinEntries = 1792;
+
+// Entries per unit in a logits buffer of the fused kernel: the capacity in whole sub-tiles plus
+// the slack its per-block regions of candidate records need (65 slots for each of up to 64 blocks).
+size_t fused_p_stride(int32_t capacity) { return static_cast<size_t>((capacity + 15) / 16 * 16) + 65 * 64; }
+
 struct Layout {
   size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, activations, rows_moved, ticket, hist, slots, total;
   int32_t n_split_max;
@@ -99,9 +105,9 @@ Layout layout_of(const lazyev_config *c) {
   size_t off = 0;
   l.part_acc = off; off = align_up(off + units * l.n_split_max * g * c->head_dim * sizeof(float));
   l.part_ml = off;  off = align_up(off + units * l.n_split_max * 2 * g * sizeof(float));
-  // two logits buffers of [units][C16][8] floats; the split + merge kernels use the first as
-  // [batch][n_q_heads][C16]
-  const size_t logits_bytes = units * ((cap + 15) / 16 * 16) * 8 * sizeof(float);
+  // two logits buffers of [units][fused_p_stride][8] floats; the split + merge kernels use the
+  // first as [batch][n_q_heads][C16]
+  const size_t logits_bytes = units * fused_p_stride(static_cast<int32_t>(cap)) * 8 * sizeof(float);
   l.p_tilde = off;  off = align_up(off + logits_bytes);
   l.logits1 = off;  off = align_up(off + logits_bytes);
   l.stat = off;     off = align_up(off + 2 * units * 16 * sizeof(float));
@@ -291,7 +297,7 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
 }
 
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant) {
-  if (!ctx || variant < 0 || variant > 4) return LAZYEV_EINVAL;
+  if (!ctx || variant < 0 || variant > 6) return LAZYEV_EINVAL;
   ctx->variant = variant;
   return LAZYEV_OK;
 }
@@ -333,8 +339,9 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   const int lds_stride = (ctx->capacity + 31) / 32 * 32 + 8;
   const bool unit_fits = mfma_shape && lazyev::decode_unit_lds_bytes(ctx->group, lds_stride) <= 150 * 1024;
   int kind = 0;
+  bool compact = false;
   if (mfma_shape && ctx->variant != 0) {
-    kind = 4;
+    kind = 4;                                      // (5 and 6 are 4 with the logits always / never written in full)
     if (ctx->variant == 2) kind = 2;
     if (ctx->variant == 3) kind = unit_fits ? 3 : 2;
   }
@@ -363,6 +370,14 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     a.logits_out = ctx->ws.logits[ctx->cur_buf];
     a.stat_out = ctx->ws.stat[ctx->cur_buf];
     a.track = ctx->pend;                           // the previous call's tracking rides along
+    a.p_stride = static_cast<int32_t>(fused_p_stride(ctx->capacity));
+    // candidate lists instead of every logit, unless somebody reads the logits as such (the
+    // caller through p_out / p_override, or an eviction that ranks by this call's weights) or
+    // the cache is short: building the lists costs a block about 0.6 us at its end and saves
+    // traffic in proportion to the cache length (measured break-even near 1750 entries)
+    compact = ctx->variant != 5 && (ctx->variant == 6 || n_old + 1 >= kCompactMinEntries) && !p_out && !p_override &&
+              !(c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) &&
+              lazyev::decode_fused_compact_fits(n_old, n_split, a.p_stride, ctx->group);
   }
   if (kind == 4) {
     // set up above
@@ -381,8 +396,8 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
   }
   a.n_split_max = ctx->n_split_max;
-  a.p_stride = (ctx->capacity + 15) / 16 * 16;
-  a.variant = kind;
+  if (kind != 4) a.p_stride = (ctx->capacity + 15) / 16 * 16;
+  a.variant = compact ? 6 : kind;
   a.alpha = c.alpha; a.scale = ctx->scale; a.dtype = c.dtype;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
   a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
@@ -415,6 +430,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     k.alpha = c.alpha;
     k.ts = a.ts; k.mri = a.mri; k.pos = a.pos;
     k.logits = a.logits_out; k.stat = a.stat_out;
+    k.compact = compact ? 1 : 0; k.n_parts = a.n_split;
     k.p_out = p_out; k.p_override = p_override;
     k.activation_counter = a.activation_counter;
     k.slots = a.slots;
@@ -626,7 +642,7 @@ int lazyev_admit(lazyev_ctx *ctx, int32_t seq, int32_t prompt_len, int32_t t0) {
   if (!ctx) return LAZYEV_EINVAL;
   const lazyev_config &c = ctx->cfg;
   if (seq < 0 || seq >= c.batch || prompt_len < 0 || prompt_len > ctx->capacity - c.window) return LAZYEV_EINVAL;
-  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant != 4))
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant < 4))
     return LAZYEV_EINVAL;
   for (int l = 0; l < c.n_layers; ++l)
     if (t0 < ctx->last_step[l]) return LAZYEV_EINVAL;   // its first step lies ahead of every layer
@@ -637,7 +653,7 @@ int lazyev_retire(lazyev_ctx *ctx, int32_t seq) {
   if (!ctx) return LAZYEV_EINVAL;
   const lazyev_config &c = ctx->cfg;
   if (seq < 0 || seq >= c.batch) return LAZYEV_EINVAL;
-  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant != 4))
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || (ctx->variant != 1 && ctx->variant < 4))
     return LAZYEV_EINVAL;
   return change_slot(ctx, seq, -1, 0);
 }

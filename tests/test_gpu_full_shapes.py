@@ -67,3 +67,39 @@ def test_cfg2_full_length_on_sampled_units(lazyev_lib):
     early = {int(j) for j, tau in zip(wl.planted, wl.period) if j < cfg.prompt_len and 0 < tau <= 256}
     for u in stat["oracle_units"].values():
         assert len(early & set(u.pos.tolist())) >= 0.75 * len(early)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg5"])
+def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name):
+    """Benchmark shapes in steady state, two layers, 70 steps with an eviction: the default
+    (candidate lists for the deferred tracking at these cache lengths) against the same kernel
+    keeping every logit: outputs, caches, TS / MRI / pos and counters bit for bit."""
+    import torch
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    base = CONFIGS[name]
+    cfg = base.scaled(n_layers=2, prompt_len=base.budget, steps=70)
+    wl = Workload(cfg)
+    runs = []
+    for variant in (4, 5):
+        eng = make_engine(lazyev_lib, cfg, wl, variant=variant)
+        out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+        ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
+        acc = torch.zeros_like(out, dtype=torch.float32)
+        n_ev = 0
+        for t in range(1, cfg.steps + 1):
+            for l in range(cfg.n_layers):
+                q, kn, vn = ins[l]
+                eng.decode_step(l, t, q[t - 1], kn[t - 1], vn[t - 1], out)
+                acc += out.float() * (1 + (t + l) % 7)
+            for l in range(cfg.n_layers):
+                n_ev += 1 if eng.evict(l, t) else 0
+        st = eng.stats()
+        n = st["len"][0]
+        runs.append((acc, eng.k_cache[:, :, :, :n].clone(), eng.ts[:, :, :, :n].clone(),
+                     eng.mri[:, :, :, :n].clone(), eng.pos[:, :, :, :n].clone(), st, n_ev))
+        eng.close()
+    a, b = runs
+    assert a[6] == b[6] == 2 and a[5] == b[5] and sum(a[5]["n_activations"]) > 0
+    for x, y in zip(a[:5], b[:5]):
+        assert torch.equal(x, y)

@@ -2,8 +2,8 @@
 followed by oracle units that threshold those weights (exact comparison).  Engine B gets the
 same inputs but a random mix of what must not change any result: weights exported or not
 (immediate or deferred tracking), lazyev_stats / lazyev_mri_histogram in between, evictions
-asked for when none is due, the block split changed between calls, layers advanced in random
-order.  B's caches, statistics and outputs must equal A's bit for bit."""
+asked for when none is due, the block split and the format the logits are kept in for the
+deferred tracking changed between calls, layers advanced in random order.  B's caches, statistics and outputs must equal A's bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -82,6 +82,8 @@ def test_random_call_sequences(lazyev_lib, seed):
         q, kn, vn = ins[t - 1][l]
         if rng.random() < 0.3:
             Bn.set_target_blocks(int(rng.choice([1, S * HKV, 4 * S * HKV, 40 * S * HKV, 512])))
+        if rng.random() < 0.3:                            # every logit kept for the tracking, or candidate lists
+            Bn.set_variant(int(rng.choice([5, 6])))
         Bn.decode_step(l, t, q, kn, vn, out_b, p_out=p_b if rng.random() < 0.3 else None)
         outs_b[(l, t)] = out_b.clone()
         r = rng.random()

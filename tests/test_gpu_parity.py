@@ -179,7 +179,7 @@ def test_budget_at_least_sequence_is_full_attention(lazyev_lib):
     assert stat["evictions"] == 0 and stat["gpu_stats"]["len"][0] == 340
 
 
-@pytest.mark.parametrize("variant", [2, 3, 4])
+@pytest.mark.parametrize("variant", [2, 3, 4, 6])
 def test_two_runs_are_bitwise_identical(lazyev_lib, variant):
     from lockstep import make_engine
     from paper_2506_15969_amd.workload import Workload
@@ -210,18 +210,21 @@ def test_two_runs_are_bitwise_identical(lazyev_lib, variant):
         assert torch.equal(out_a, out_b)
 
 
-def test_deferred_tracking_equals_immediate(lazyev_lib):
+@pytest.mark.parametrize("blocks", [8, 24, 1000])
+def test_deferred_tracking_equals_immediate(lazyev_lib, blocks):
     """The single-launch kernel applies the tracking of a call with the NEXT launch (or at the
-    next lazyev_evict / lazyev_stats) unless the caller asks for the weights.  Both routes must
+    next lazyev_evict / lazyev_stats) unless the caller asks for the weights.  All routes must
     leave identical state: one engine is driven with p_out (tracked at once, the route the
-    lock-step tests check against the oracle), the other without, two layers interleaved."""
+    lock-step tests check against the oracle), one without and with every logit stored
+    (kernel 5), one without and with candidate lists only (kernel 6); two layers interleaved;
+    one, three and as many blocks per unit as the cache allows."""
     from lockstep import make_engine
     from paper_2506_15969_amd.workload import Workload
     cfg = CONFIGS["cfg2"].scaled(n_layers=2, batch=2, prompt_len=100, steps=140, budget=170, window=32)
     wl = Workload(cfg)
     runs = []
-    for immediate in (True, False):
-        eng = make_engine(lazyev_lib, cfg, wl, variant=4, target_blocks=24)
+    for immediate, variant in ((True, 4), (False, 5), (False, 6)):
+        eng = make_engine(lazyev_lib, cfg, wl, variant=variant, target_blocks=blocks)
         out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
         p_out = torch.zeros((cfg.batch, cfg.n_q_heads, cfg.capacity), dtype=torch.float32, device="cuda")
         ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
@@ -237,11 +240,12 @@ def test_deferred_tracking_equals_immediate(lazyev_lib):
         st = eng.stats()                                  # applies what is still pending
         runs.append((torch.stack(outs), eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(),
                      eng.mri.clone(), eng.pos.clone(), st, n_ev))
-    a, b = runs
-    assert a[7] == b[7] == 2 * len([t for t in range(32, 141, 32) if 100 + t > 170])
-    for x, y in zip(a[:6], b[:6]):
-        assert torch.equal(x, y)
-    assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
+    a = runs[0]
+    for b in runs[1:]:
+        assert a[7] == b[7] == 2 * len([t for t in range(32, 141, 32) if 100 + t > 170])
+        for x, y in zip(a[:6], b[:6]):
+            assert torch.equal(x, y)
+        assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
 
 
 def test_long_runs_per_wave(lazyev_lib):

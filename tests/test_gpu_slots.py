@@ -27,11 +27,13 @@ def _rand(gen, *shape):
     return torch.randn(shape, generator=gen).to(torch.bfloat16)
 
 
-def _drive(binding, with_weights, follow):
+def _drive(binding, with_weights, follow, variant=None):
     """Runs the scenario.  follow: compare with oracle units step by step (needs with_weights)."""
     gen = torch.Generator().manual_seed(77)
     eng = binding.LazyEviction(L, S, HQ, HKV, D, B, W, PMAX, ALPHA, dtype=torch.bfloat16)
     eng.init()
+    if variant is not None:
+        eng.set_variant(variant)
     cap = eng.capacity
     out = torch.empty((S, HQ, D), dtype=torch.bfloat16, device="cuda")
     p_out = torch.zeros((S, HQ, cap), dtype=torch.float32, device="cuda")
@@ -116,11 +118,13 @@ def test_sequences_on_their_own_clocks(lazyev_lib):
     for l in range(L):
         want = mri_histogram(np.concatenate([u.MRI for (l2, s, h), u in orc.items() if l2 == l]), 40)
         assert eng.mri_histogram(l, 40) == want.tolist()
-    # the same scenario without asking for weights (tracking rides with the next launch)
-    _, _, _, st2, state2 = _drive(lazyev_lib, with_weights=False, follow=False)
-    assert st2 == st
-    for x, y in zip(state, state2):
-        assert torch.equal(x, y)
+    # the same scenario without asking for weights (tracking rides with the next launch), with
+    # every logit kept for it and with candidate lists
+    for variant in (5, 6):
+        _, _, _, st2, state2 = _drive(lazyev_lib, with_weights=False, follow=False, variant=variant)
+        assert st2 == st
+        for x, y in zip(state, state2):
+            assert torch.equal(x, y)
 
 
 def test_slot_calls_reject_what_they_cannot_do(lazyev_lib):
