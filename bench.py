@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the attention split kernel at the steady-state cache length, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/; the
 # counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 72180 * 1024 + 9856 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 68540 * 1024 + 2545 * 1024}
 
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
