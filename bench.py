@@ -250,6 +250,21 @@ def main():
                                 torch.cuda.current_stream(dev).cuda_stream)
         torch.cuda.synchronize()
         del src, dst
+    # what a plain streaming read reaches on this machine (1 GiB, non-temporal loads, two blocks per
+    # compute unit): the second denominator beside the published peak
+    probe_bytes = 1 << 30
+    probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
+    probe_sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    stream_ptr = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    lib.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
+    ev0.record()
+    for _ in range(5):
+        lib.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
+    ev1.record()
+    torch.cuda.synchronize()
+    read_probe_gbs = 5 * probe_bytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del probe_src
     prof = eng.profile_read()
     st = eng.stats()
     # what a pair of HIP events adds to the kernel it brackets (empty kernel, same stream)
@@ -294,6 +309,8 @@ def main():
                                      "decode_call covers split + merge)"),
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "plain_read_on_this_box": {"GB/s": read_probe_gbs, "frac_of_it": ach / read_probe_gbs,
+                                       "what": "1 GiB read once with non-temporal loads, grid-stride, 512 blocks of 256 threads (the fastest of 512..65536 blocks: 7.0 TB/s; 1024..16384 blocks reach 5.6-6.2)"},
             "avg_us": 1e3 * split_k / split_n, "avg_us_between_events": 1e3 * split_ms / split_n,
             "event_pair_overhead_us": 1e3 * ov_ms, "launches_timed": split_n,
             "algorithmic_bytes_per_launch": dec_bytes / split_n,

