@@ -72,6 +72,8 @@ def test_null_context_calls(lazyev_lib):
     assert b.lib.lazyev_evict(None, 0, 1, None) == b.EINVAL
     assert b.lib.lazyev_stats(None, None) == b.EINVAL
     assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL
+    assert b.lib.lazyev_prefill_track(None, 0, 1, None, None) == b.EINVAL
+    assert b.lib.lazyev_admit(None, 0, 1, 0) == b.EINVAL and b.lib.lazyev_retire(None, 0) == b.EINVAL
     b.lib.lazyev_destroy(None)
     assert b.lib.lazyev_last_hip_error(None) == 0
     for code in (0, -1, -2, -3, -4, -99):
@@ -123,3 +125,14 @@ def test_cache_length_formula_against_a_simulation(lazyev_lib):
             if tau % W == 0 and n > B:
                 n = B
     assert f(-1, 1, 8, 2) == -1 and f(4, 0, 8, 2) == -1 and f(4, 1, 2, 2) == -1
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """The path has no cross-GPU part: bench.py --gpus 2 says so and exits before touching a GPU."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""

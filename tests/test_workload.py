@@ -20,6 +20,25 @@ def test_slices_equal_the_full_batch():
     assert torch.equal(K[:, :, 0], kf[1]) and torch.equal(V[:, :, 0], vf[1])
 
 
+def test_prompt_queries_slice_and_read_the_first_keys_periodically():
+    cfg = CONFIGS["cfg2"].scaled(batch=3, prompt_len=100, steps=4, budget=200, window=32)
+    w = Workload(cfg)
+    G, d = cfg.group, cfg.head_dim
+    qa = w.prompt_queries(0)                                      # [S, P, Hq, d]
+    assert qa.shape == (3, 100, cfg.n_q_heads, d)
+    q1 = w.prompt_queries(0, seq=[2, 0], kv_head=[3, 1])
+    heads = [3 * G + g for g in range(G)] + [G + g for g in range(G)]
+    assert torch.equal(qa[[2, 0]][:, :, heads], q1)
+    # position i >= 32 reads key (5 i) mod 32 on head i mod G: its logit dominates the row
+    k, _ = w.prompt_kv(0, seq=[1], kv_head=[2])
+    k = k[0, 0].double()
+    for i in (32, 57, 99):
+        s = (qa[1, i, 2 * G + i % G].double() @ k[:i + 1].T) / d ** 0.5
+        assert int(s.argmax()) == (5 * i) % 32 and float(s.max()) > 30.0
+    # the same key again 32 positions later, on another head
+    assert (5 * 57) % 32 == (5 * 89) % 32
+
+
 def test_values_look_standard_normal_and_differ_across_streams():
     w = Workload(CONFIGS["cfg2"])
     K, V = w.prompt_kv(0)
