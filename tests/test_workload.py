@@ -83,3 +83,4 @@ def test_gpu_generation_is_bit_identical_to_cpu():
         ka, va = w.prompt_kv(0)
         kb, vb = w.prompt_kv(0, device="cuda")
         assert torch.equal(ka, kb.cpu()) and torch.equal(va, vb.cpu())
+        assert torch.equal(w.prompt_queries(0), w.prompt_queries(0, device="cuda").cpu())
