@@ -61,7 +61,9 @@ constexpr int kSpan = 16 * NB;                     // queries (stats) or keys (t
 constexpr float kLog2e = 1.4426950408889634f;
 
 // One key tile against one query tile in the statistics kernel.  Logits are kept in units of
-// log 2 (scaled by scale * log2(e)), so an exponential is one v_exp_f32.  kMask: the tile may
+// log 2 (scaled by scale * log2(e)), so an exponential is one v_exp_f32.  Every lane keeps the
+// running maximum and sum of ITS four key rows of every tile (the four lanes of a query column
+// are merged once, at the end): no cross-lane traffic inside the loop.  kMask: the tile may
 // hold keys newer than a query or positions beyond the prompt.
 template <bool kMask>
 __device__ __forceinline__ void stats_tile(const u32x4_t (&ka)[KC], const u32x4_t (&qb)[KC], float c2, int key0,
@@ -73,14 +75,11 @@ __device__ __forceinline__ void stats_tile(const u32x4_t (&ka)[KC], const u32x4_
     s[i] = acc[i] * c2;
     if (kMask) s[i] = (key0 + i <= query && key0 + i < P) ? s[i] : -INFINITY;
   }
-  float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-  const float m_new = fmaxf(m, tmax);              // finite from the first tile on: key 0 <= every query
-  float ps = (__builtin_amdgcn_exp2f(s[0] - m_new) + __builtin_amdgcn_exp2f(s[1] - m_new)) +
-             (__builtin_amdgcn_exp2f(s[2] - m_new) + __builtin_amdgcn_exp2f(s[3] - m_new));
-  ps += __shfl_xor(ps, 16);
-  ps += __shfl_xor(ps, 32);
+  const float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  const float m_new = fmaxf(m, tmax);
+  if (kMask && m_new == -INFINITY) return;         // this lane has seen no key of the query yet
+  const float ps = (__builtin_amdgcn_exp2f(s[0] - m_new) + __builtin_amdgcn_exp2f(s[1] - m_new)) +
+                   (__builtin_amdgcn_exp2f(s[2] - m_new) + __builtin_amdgcn_exp2f(s[3] - m_new));
   l = l * __builtin_amdgcn_exp2f(m - m_new) + ps;  // first tile: l = 0 * 2^(-inf) + ps
   m = m_new;
 }
@@ -111,7 +110,7 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   for (int n = 0; n < NB; ++n)
     load_operand(qb[n], q, i0 + 16 * n, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
 
-  float m[NB], l[NB];                              // of query i0 + 16 n + c (the four lanes of a column agree)
+  float m[NB], l[NB];                              // of query i0 + 16 n + c, over this lane's key rows
 #pragma unroll
   for (int n = 0; n < NB; ++n) { m[n] = -INFINITY; l[n] = 0.f; }
   const int last_tile = min(i0 + kSpan - 1, P - 1) >> 4;
@@ -131,6 +130,20 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
     }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk) ka[kk] = kn[kk];
+  }
+  // the four lanes of a query column (g = 0..3) -> the column's maximum and sum; a lane that
+  // saw no key of the query (possible in the first tiles of a wave) holds (-inf, 0)
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const float mo = __shfl_xor(m[n], o), lo = __shfl_xor(l[n], o);
+      const float mx = fmaxf(m[n], mo);
+      const float fa = m[n] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[n] - mx);
+      const float fb = mo == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mo - mx);
+      l[n] = l[n] * fa + lo * fb;
+      m[n] = mx;
+    }
   }
   if (g == 0) {                                    // (max in units of log 2, 1 / sum)
     float2 *st = a.stat + (static_cast<size_t>(unit) * G + h) * a.p16;
