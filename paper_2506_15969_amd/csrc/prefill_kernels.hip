@@ -91,11 +91,13 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   const int c = lane & 15, g = lane >> 4;
   const int P = a.prompt_len, G = a.group;
   const int n_qt = (P + kWaves * kSpan - 1) / (kWaves * kSpan);
-  int b = blockIdx.x;
-  int qt = b % n_qt;  b /= n_qt;
-  // Consecutive blocks go to different XCDs, and late tiles carry more work than early ones:
-  // rotated by the (unit, head) index so that every XCD gets every tile position equally often.
-  qt = (qt + b) % n_qt;
+  // Blocks start in index order and late query tiles carry more work than early ones: the
+  // heaviest tiles get the lowest block indices (they start first, the light ones fill the
+  // end), and consecutive blocks, which go to different XCDs, hold the same tile position of
+  // different (unit, head) pairs, so every XCD gets every tile position equally often.
+  const int n_uh = static_cast<int>(gridDim.x) / n_qt;            // units * G
+  const int qt = n_qt - 1 - static_cast<int>(blockIdx.x) / n_uh;
+  const int b = static_cast<int>(blockIdx.x) % n_uh;
   const int h = b % G;
   const int unit = b / G;
   const int i0 = (qt * kWaves + wave) * kSpan;     // this wave's queries: i0 .. i0 + kSpan - 1
@@ -161,8 +163,9 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   const int c = lane & 15, g = lane >> 4;
   const int P = a.prompt_len, G = a.group;
   const int n_kt = (P + kWaves * kSpan - 1) / (kWaves * kSpan);
-  const int unit = blockIdx.x / n_kt;
-  const int kt = (blockIdx.x % n_kt + unit) % n_kt;   // rotated like the tiles of the first kernel (early keys carry more work)
+  // early keys carry more work: heaviest first, as in the first kernel
+  const int n_units = static_cast<int>(gridDim.x) / n_kt;
+  const int kt = static_cast<int>(blockIdx.x) / n_units, unit = static_cast<int>(blockIdx.x) % n_units;
   const int j0 = (kt * kWaves + wave) * kSpan;
   if (j0 >= P) return;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
