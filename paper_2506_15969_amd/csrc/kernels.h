@@ -122,7 +122,8 @@ struct PrefillArgs {
   const void *q_prompt;             // [batch][prompt_len][n_q_heads][128] bf16
   const void *k_cache;              // the layer's slab
   int32_t *ts, *mri;                // the layer's slab
-  float2 *stat;                     // [units][group][p16] softmax (max, 1 / sum), workspace
+  float *stat;                      // [units][group][p16]: -(log-sum-exp of the scaled logits) / scale per
+                                    // (head, position), workspace
   float *p_out;                     // [batch][n_q_heads][prompt_len][prompt_len] or null
   const float *p_override;          // same shape or null
   unsigned long long *activation_counter;   // the layer's [units][counter_stride] or null

@@ -37,7 +37,7 @@ struct lazyev_ctx {
   int32_t last_layer;
   const float *last_logits, *last_stat;
   int32_t last_p_stride;
-  float2 *prefill_stat;             // workspace of lazyev_prefill_track
+  float *prefill_stat;              // workspace of lazyev_prefill_track
   // per-sequence timing (lazyev_admit / lazyev_retire): prompt length (-1: empty slot) and the
   // global step before each sequence's first one; device copies in the workspace.  Off until
   // the first admit or retire: until then every sequence has the configuration's prompt, t0 = 0.
@@ -244,7 +244,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->last_layer = -1;
   ctx->last_logits = ctx->last_stat = nullptr;
   ctx->last_p_stride = 0;
-  ctx->prefill_stat = reinterpret_cast<float2 *>(base + l.prefill_stat);
+  ctx->prefill_stat = reinterpret_cast<float *>(base + l.prefill_stat);
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);

@@ -9,16 +9,20 @@
 //   A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]     (lane l, c = l % 16, g = l / 16):
 //   stats  a wave keeps 64 queries of one head in registers (four B operands), walks the key
 //          tiles 0..its own and keeps the running softmax maximum and sum of every query;
-//          leaves (max, 1 / sum) per (unit, head, position) in the workspace
+//          leaves b = -(log-sum-exp of the query's scaled logits) / scale per (unit, head,
+//          position) in the workspace
 //   track  a wave keeps 64 keys in registers (four A operands), walks the query tiles from its
-//          own upwards, for every head recomputes the logits (same operands, same order of
-//          accumulation: the logits of the first kernel), p = exp(s - max) / sum,
-//          tests p >= alpha over the group, and applies the activations of each key in order
-//          of the query position (one key per lane).
+//          own upwards.  The weight of key j for query i in head h is p = exp(scale (q.k + b)),
+//          so the product is started from b instead of 0 (accumulator input of the first
+//          MFMA) and the largest q.k + b over the heads of the group decides (exp and the
+//          scaling are monotone): one maximum per weight and head, one exponential and one
+//          compare with alpha per weight after the group's last head.  The activations of each
+//          key are then applied in order of the query position (one key per lane).
 // Four products per streamed tile: the streamed tiles come from the caches, and one 4 KB tile
 // per 16x16x128 product leaves the matrix cores waiting for them (a 2048-token prompt of the
 // benchmark's third workload: 13.0 ms per layer with one product per tile, 5.4 with four, 5.7
-// with eight, where the registers allow only two waves per SIMD).
+// with eight, where the registers allow only two waves per SIMD).  Blocks start in index
+// order, so the heaviest tiles get the lowest indices.
 // Neither kernel has a barrier or waits for another wave.
 #include "kernels.h"
 
@@ -46,8 +50,8 @@ __device__ __forceinline__ void load_operand(u32x4_t (&x)[KC], const bf16_t *row
   for (int kk = 0; kk < KC; ++kk) x[kk] = *reinterpret_cast<const u32x4_t *>(p + kk * 32);
 }
 
-__device__ __forceinline__ f32x4_t logits_tile(const u32x4_t (&ka)[KC], const u32x4_t (&qb)[KC]) {
-  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ f32x4_t logits_tile(const u32x4_t (&ka)[KC], const u32x4_t (&qb)[KC],
+                                               f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f}) {
 #pragma unroll
   for (int kk = 0; kk < KC; ++kk)
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[kk]),
@@ -59,6 +63,10 @@ constexpr int NB = 4;                              // tiles a wave keeps in regi
 constexpr int kSpan = 16 * NB;                     // queries (stats) or keys (track) per wave
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// max(a, b) of two numbers as ONE instruction (the median of a, b and +inf); fmaxf spends two
+// more on making signalling NaNs quiet, and there are no NaNs here.
+__device__ __forceinline__ float max_f32(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, INFINITY); }
 
 // One key tile against one query tile in the statistics kernel.  Logits are kept in units of
 // log 2 (scaled by scale * log2(e)), so an exponential is one v_exp_f32.  Every lane keeps the
@@ -147,11 +155,11 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
       m[n] = mx;
     }
   }
-  if (g == 0) {                                    // (max in units of log 2, 1 / sum)
-    float2 *st = a.stat + (static_cast<size_t>(unit) * G + h) * a.p16;
+  if (g == 0) {                                    // b = -(m + log2 l) / (scale log2 e): see the tracking kernel
+    float *st = a.stat + (static_cast<size_t>(unit) * G + h) * a.p16;
 #pragma unroll
     for (int n = 0; n < NB; ++n)
-      if (i0 + 16 * n + c < P) st[i0 + 16 * n + c] = make_float2(m[n], 1.0f / l[n]);
+      if (i0 + 16 * n + c < P) st[i0 + 16 * n + c] = -(m[n] + __builtin_amdgcn_logf(l[n])) / c2;
   }
 }
 
@@ -172,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
                     (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G) * D;
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
-  const float2 *stat = a.stat + static_cast<size_t>(unit) * G * a.p16;
+  const float *stat = a.stat + static_cast<size_t>(unit) * G * a.p16;
   const float c2 = a.scale * kLog2e;
   u32x4_t ka[NB][KC];
 #pragma unroll
@@ -182,25 +190,37 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   const int my_key = j0 + 16 * (c >> 2) + 4 * g + (c & 3);
   int32_t ts = my_key + 1 - P, mri = 0;
   unsigned n_act = 0;
-  // (query tile, head) pairs in order; the operands of the next pair travel during the
+  // (query tile, head) pairs in order; the operands of the next two pairs travel during the
   // arithmetic of the current one
   int it = j0 >> 4, h = 0;
-  u32x4_t qb[KC];
+  // (pairs beyond the last one repeat the last one: in bounds, never used)
+  auto step_pair = [&](int &it_x, int &h_x) {
+    int h_y = h_x + 1, it_y = it_x;
+    if (h_y == G) { h_y = 0; ++it_y; }
+    if (it_y * 16 < P) { it_x = it_y; h_x = h_y; }
+  };
+  u32x4_t qb[KC], q1[KC];
   load_operand(qb, q, it * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
-  float2 st = stat[min(it * 16 + c, P - 1)];
-  // bal[4 n + i]: wave mask (bit 16 g + c) of "key row 4 g + i of key tile n is active for
-  // query column c" over the heads of the current query tile: the compare masks themselves
-  unsigned long long bal[4 * NB];
+  float bq = stat[min(it * 16 + c, P - 1)];
+  int it_p = it, h_p = h;                          // the pair whose operands were requested last
+  step_pair(it_p, h_p);
+  load_operand(q1, q + static_cast<size_t>(h_p) * D, it_p * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+  float b1 = stat[static_cast<size_t>(h_p) * a.p16 + min(it_p * 16 + c, P - 1)];
+  // amax[4 n + i]: largest q.k + b over the heads seen so far of the current query tile, for key
+  // row 4 g + i of key tile n and query column c (-inf: the key is newer than the query)
+  float amax[4 * NB];
 #pragma unroll
-  for (int x = 0; x < 4 * NB; ++x) bal[x] = 0;
+  for (int x = 0; x < 4 * NB; ++x) amax[x] = -INFINITY;
+  unsigned over = 0;                               // kIO with injected weights: bit 4 n + i = some head's weight >= alpha
   while (it * 16 < P) {
     int h2 = h + 1, it2 = it;
     if (h2 == G) { h2 = 0; ++it2; }
-    const int itn = it2 * 16 < P ? it2 : it, hn = it2 * 16 < P ? h2 : h;   // (the last pair is loaded twice)
+    step_pair(it_p, h_p);                          // operands two pairs ahead
     u32x4_t qn[KC];
-    load_operand(qn, q + static_cast<size_t>(hn) * D, itn * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
-    const float2 stn = stat[static_cast<size_t>(hn) * a.p16 + min(itn * 16 + c, P - 1)];
+    load_operand(qn, q + static_cast<size_t>(h_p) * D, it_p * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+    const float bn = stat[static_cast<size_t>(h_p) * a.p16 + min(it_p * 16 + c, P - 1)];
     const int qi = it * 16 + c;                    // this lane's query column
+    const f32x4_t b4 = {bq, bq, bq, bq};
     // every key of the wave exists and is no newer than any query of the tile, and every
     // query of the tile exists: nothing to mask (all but the wave's first four query tiles,
     // the prompt's last tile and its last wave)
@@ -208,43 +228,43 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
     if (plain) {
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const f32x4_t acc = logits_tile(ka[n], qb);
+        const f32x4_t acc = logits_tile(ka[n], qb, b4);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, -st.x)) * st.y;
-          bal[4 * n + i] |= __builtin_amdgcn_ballot_w64(p >= a.alpha);
-        }
+        for (int i = 0; i < 4; ++i) amax[4 * n + i] = max_f32(amax[4 * n + i], acc[i]);
       }
     } else {
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const f32x4_t acc = logits_tile(ka[n], qb);
+        const f32x4_t acc = logits_tile(ka[n], qb, b4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int key = j0 + 16 * n + 4 * g + i;
           const bool seen = key <= qi && qi < P;   // (key <= qi < P implies key < P)
-          float p = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, -st.x)) * st.y;
+          if (seen) amax[4 * n + i] = max_f32(amax[4 * n + i], acc[i]);
           if (kIO) {
             if (seen) {
               const size_t at = ((static_cast<size_t>(seq) * a.n_q_heads + kvh * G + h) * P + qi) * P + key;
-              if (a.p_out) a.p_out[at] = p;
-              if (a.p_override) p = a.p_override[at];
+              if (a.p_out) a.p_out[at] = __builtin_amdgcn_exp2f(acc[i] * c2);
+              if (a.p_override && a.p_override[at] >= a.alpha) over |= 1u << (4 * n + i);
             }
           }
-          bal[4 * n + i] |= __builtin_amdgcn_ballot_w64(seen && p >= a.alpha);
         }
       }
     }
     if (h2 == 0) {                                 // the tile's last head: apply its activations
       // key row 4 g' + i of key tile n over the tile's 16 queries: bits 16 g' .. 16 g' + 15 of
-      // bal[4 n + i]; lane (c, g) wants the one with 4 n + i = c
+      // the ballot of entry 4 n + i; lane (c, g) wants the one with 4 n + i = c
       unsigned long long mine = 0, any = 0;
 #pragma unroll
       for (int x = 0; x < 4 * NB; ++x) {
-        if (c == x) mine = bal[x];
-        any |= bal[x];
-        bal[x] = 0;
+        bool on = __builtin_amdgcn_exp2f(amax[x] * c2) >= a.alpha;       // exp2(-inf) = 0
+        if (kIO && a.p_override) on = (over >> x) & 1u;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(on);
+        if (c == x) mine = bal;
+        any |= bal;
+        amax[x] = -INFINITY;
       }
+      over = 0;
       if (any != 0) {                              // (wave-uniform)
         unsigned mask = static_cast<unsigned>(mine >> (16 * g)) & 0xFFFFu;
         n_act += __popc(mask);
@@ -258,8 +278,9 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
       }
     }
 #pragma unroll
-    for (int kk = 0; kk < KC; ++kk) qb[kk] = qn[kk];
-    st = stn;
+    for (int kk = 0; kk < KC; ++kk) { qb[kk] = q1[kk]; q1[kk] = qn[kk]; }
+    bq = b1;
+    b1 = bn;
     it = it2;
     h = h2;
   }
