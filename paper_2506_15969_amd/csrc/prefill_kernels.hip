@@ -59,6 +59,29 @@ __device__ __forceinline__ f32x4_t logits_tile(const u32x4_t (&ka)[KC], const u3
   return acc;
 }
 
+// The streamed tile (16 rows x 256 bytes) is fetched ONCE per block: thread t brings the 16-byte
+// chunk t % 16 of row t / 16 (whole 256-byte rows per 16 lanes), the block keeps it in LDS, and
+// every wave reads its MFMA operand from there.  Chunk x of row r sits at slot x ^ r of the row,
+// so that the row-wise writes and the column-wise operand reads both touch every bank once.
+struct SharedTile {
+  u32x4_t slot[2][16 * 16];                        // double-buffered
+};
+
+__device__ __forceinline__ u32x4_t tile_fetch(const bf16_t *rows, int first, int last, size_t stride) {
+  const int r = min(first + (static_cast<int>(threadIdx.x) >> 4), last);
+  return *reinterpret_cast<const u32x4_t *>(rows + static_cast<size_t>(r) * stride + (threadIdx.x & 15) * 8);
+}
+
+__device__ __forceinline__ void tile_put(SharedTile &t, int buf, u32x4_t v) {
+  const int r = static_cast<int>(threadIdx.x) >> 4, x = threadIdx.x & 15;
+  t.slot[buf][r * 16 + (x ^ r)] = v;
+}
+
+__device__ __forceinline__ void tile_operand(const SharedTile &t, int buf, u32x4_t (&x)[KC], int c, int g) {
+#pragma unroll
+  for (int kk = 0; kk < KC; ++kk) x[kk] = t.slot[buf][c * 16 + ((4 * kk + g) ^ c)];
+}
+
 constexpr int NB = 4;                              // tiles a wave keeps in registers
 constexpr int kSpan = 16 * NB;                     // queries (stats) or keys (track) per wave
 
@@ -93,8 +116,10 @@ __device__ __forceinline__ void stats_tile(const u32x4_t (&ka)[KC], const u32x4_
 }
 
 // Softmax statistics of every (head, prompt position) of a unit:
-// blocks = units * G * ceil(P / (4 * kSpan)).
+// blocks = units * G * ceil(P / (4 * kSpan)); the four waves of a block hold consecutive query
+// spans of one head and walk the key tiles together.
 __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs a) {
+  __shared__ SharedTile tile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int P = a.prompt_len, G = a.group;
@@ -109,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   const int h = b % G;
   const int unit = b / G;
   const int i0 = (qt * kWaves + wave) * kSpan;     // this wave's queries: i0 .. i0 + kSpan - 1
-  if (i0 >= P) return;
+  const bool have = i0 < P;                        // (a wave without queries still fetches and waits with the block)
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
                     (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G + h) * D;
@@ -123,24 +148,30 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
   float m[NB], l[NB];                              // of query i0 + 16 n + c, over this lane's key rows
 #pragma unroll
   for (int n = 0; n < NB; ++n) { m[n] = -INFINITY; l[n] = 0.f; }
-  const int last_tile = min(i0 + kSpan - 1, P - 1) >> 4;
-  u32x4_t ka[KC];
-  load_operand(ka, kc, 0, P - 1, D, c, g);
-  for (int jt = 0; jt <= last_tile; ++jt) {
-    u32x4_t kn[KC];                                // the next key tile travels during the arithmetic
-    load_operand(kn, kc, min(jt + 1, last_tile) * 16, P - 1, D, c, g);
-    // all four products, no branches inside; only the wave's last four key tiles can hold keys
-    // newer than a query (or positions beyond the prompt)
-    if (jt * 16 + 15 <= i0 && jt * 16 + 15 < P) {
+  const int my_last = have ? min(i0 + kSpan - 1, P - 1) >> 4 : -1;
+  const int block_last = min(qt * kWaves * kSpan + kWaves * kSpan - 1, P - 1) >> 4;
+  tile_put(tile, 0, tile_fetch(kc, 0, P - 1, D));
+  __syncthreads();
+  for (int jt = 0; jt <= block_last; ++jt) {
+    // the next key tile travels during the arithmetic
+    const u32x4_t next = tile_fetch(kc, min(jt + 1, block_last) * 16, P - 1, D);
+    if (jt <= my_last) {
+      u32x4_t ka[KC];
+      tile_operand(tile, jt & 1, ka, c, g);
+      // all four products, no branches inside; only the wave's last four key tiles can hold
+      // keys newer than a query (or positions beyond the prompt)
+      if (jt * 16 + 15 <= i0 && jt * 16 + 15 < P) {
 #pragma unroll
-      for (int n = 0; n < NB; ++n) stats_tile<false>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
-    } else {
+        for (int n = 0; n < NB; ++n) stats_tile<false>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
+      } else {
 #pragma unroll
-      for (int n = 0; n < NB; ++n) stats_tile<true>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
+        for (int n = 0; n < NB; ++n) stats_tile<true>(ka, qb[n], c2, jt * 16 + 4 * g, i0 + 16 * n + c, P, m[n], l[n]);
+      }
     }
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) ka[kk] = kn[kk];
+    tile_put(tile, (jt + 1) & 1, next);
+    __syncthreads();                               // tile jt + 1 is complete, tile jt no longer read
   }
+  if (!have) return;
   // the four lanes of a query column (g = 0..3) -> the column's maximum and sum; a lane that
   // saw no key of the query (possible in the first tiles of a wave) holds (-inf, 0)
 #pragma unroll
