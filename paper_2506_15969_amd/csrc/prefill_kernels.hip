@@ -198,6 +198,7 @@ __global__ __launch_bounds__(kBlock) void prefill_stats_kernel(const PrefillArgs
 // kIO: the weights are exported and / or replaced (a checker's route).
 template <bool kIO>
 __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs a) {
+  __shared__ SharedTile tile;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int P = a.prompt_len, G = a.group;
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   const int n_units = static_cast<int>(gridDim.x) / n_kt;
   const int kt = static_cast<int>(blockIdx.x) / n_units, unit = static_cast<int>(blockIdx.x) % n_units;
   const int j0 = (kt * kWaves + wave) * kSpan;
-  if (j0 >= P) return;
+  const bool have = j0 < P;                        // (a wave without keys still fetches and waits with the block)
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const bf16_t *q = static_cast<const bf16_t *>(a.q_prompt) +
                     (static_cast<size_t>(seq) * P * a.n_q_heads + kvh * G) * D;
@@ -221,22 +222,16 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   const int my_key = j0 + 16 * (c >> 2) + 4 * g + (c & 3);
   int32_t ts = my_key + 1 - P, mri = 0;
   unsigned n_act = 0;
-  // (query tile, head) pairs in order; the operands of the next two pairs travel during the
-  // arithmetic of the current one
-  int it = j0 >> 4, h = 0;
-  // (pairs beyond the last one repeat the last one: in bounds, never used)
-  auto step_pair = [&](int &it_x, int &h_x) {
-    int h_y = h_x + 1, it_y = it_x;
-    if (h_y == G) { h_y = 0; ++it_y; }
-    if (it_y * 16 < P) { it_x = it_y; h_x = h_y; }
-  };
-  u32x4_t qb[KC], q1[KC];
-  load_operand(qb, q, it * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
+  // (query tile, head) pairs in order, the same for the four waves of the block (a wave skips
+  // the query tiles before its own keys); the query tile of a pair is fetched once per block,
+  // the next pair's travels during the arithmetic of the current one
+  const size_t q_stride = static_cast<size_t>(a.n_q_heads) * D;
+  int it = (kt * kWaves * kSpan) >> 4, h = 0;      // the block's oldest key tile
+  const int my_first = j0 >> 4;
+  tile_put(tile, 0, tile_fetch(q, it * 16, P - 1, q_stride));
   float bq = stat[min(it * 16 + c, P - 1)];
-  int it_p = it, h_p = h;                          // the pair whose operands were requested last
-  step_pair(it_p, h_p);
-  load_operand(q1, q + static_cast<size_t>(h_p) * D, it_p * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
-  float b1 = stat[static_cast<size_t>(h_p) * a.p16 + min(it_p * 16 + c, P - 1)];
+  __syncthreads();
+  int buf = 0;
   // amax[4 n + i]: largest q.k + b over the heads seen so far of the current query tile, for key
   // row 4 g + i of key tile n and query column c (-inf: the key is newer than the query)
   float amax[4 * NB];
@@ -246,12 +241,14 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   while (it * 16 < P) {
     int h2 = h + 1, it2 = it;
     if (h2 == G) { h2 = 0; ++it2; }
-    step_pair(it_p, h_p);                          // operands two pairs ahead
-    u32x4_t qn[KC];
-    load_operand(qn, q + static_cast<size_t>(h_p) * D, it_p * 16, P - 1, static_cast<size_t>(a.n_q_heads) * D, c, g);
-    const float bn = stat[static_cast<size_t>(h_p) * a.p16 + min(it_p * 16 + c, P - 1)];
+    const int itn = it2 * 16 < P ? it2 : it, hn = it2 * 16 < P ? h2 : h;   // (the last pair is fetched twice)
+    const u32x4_t next = tile_fetch(q + static_cast<size_t>(hn) * D, itn * 16, P - 1, q_stride);
+    const float bn = stat[static_cast<size_t>(hn) * a.p16 + min(itn * 16 + c, P - 1)];
     const int qi = it * 16 + c;                    // this lane's query column
     const f32x4_t b4 = {bq, bq, bq, bq};
+    if (have && it >= my_first) {
+    u32x4_t qb[KC];
+    tile_operand(tile, buf, qb, c, g);
     // every key of the wave exists and is no newer than any query of the tile, and every
     // query of the tile exists: nothing to mask (all but the wave's first four query tiles,
     // the prompt's last tile and its last wave)
@@ -308,13 +305,15 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
         }
       }
     }
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) { qb[kk] = q1[kk]; q1[kk] = qn[kk]; }
-    bq = b1;
-    b1 = bn;
+    }
+    tile_put(tile, buf ^ 1, next);
+    __syncthreads();                               // the next pair's tile is complete, this pair's no longer read
+    buf ^= 1;
+    bq = bn;
     it = it2;
     h = h2;
   }
+  if (!have) return;
   if (my_key < P) {
     a.ts[static_cast<size_t>(unit) * a.capacity + my_key] = ts;
     a.mri[static_cast<size_t>(unit) * a.capacity + my_key] = mri;
