@@ -106,8 +106,7 @@ __device__ __forceinline__ void stats_tile(const u32x4_t (&ka)[KC], const u32x4_
     s[i] = acc[i] * c2;
     if (kMask) s[i] = (key0 + i <= query && key0 + i < P) ? s[i] : -INFINITY;
   }
-  const float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-  const float m_new = fmaxf(m, tmax);
+  const float m_new = max_f32(max_f32(max_f32(s[0], s[1]), max_f32(s[2], s[3])), m);
   if (kMask && m_new == -INFINITY) return;         // this lane has seen no key of the query yet
   const float ps = (__builtin_amdgcn_exp2f(s[0] - m_new) + __builtin_amdgcn_exp2f(s[1] - m_new)) +
                    (__builtin_amdgcn_exp2f(s[2] - m_new) + __builtin_amdgcn_exp2f(s[3] - m_new));
