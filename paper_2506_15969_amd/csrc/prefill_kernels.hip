@@ -5,25 +5,27 @@
 // with TS = tau_i, MRI = 0; decoding continues at step 1.
 //
 // Two kernels, both built on S^T = K Q^T tiles of v_mfma_f32_16x16x32_bf16 (16 keys x 16
-// queries of ONE head), operands loaded straight into the MFMA layouts
+// queries of ONE head); MFMA layouts
 //   A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]     (lane l, c = l % 16, g = l / 16):
-//   stats  a wave keeps 64 queries of one head in registers (four B operands), walks the key
-//          tiles 0..its own and keeps the running softmax maximum and sum of every query;
-//          leaves b = -(log-sum-exp of the query's scaled logits) / scale per (unit, head,
-//          position) in the workspace
-//   track  a wave keeps 64 keys in registers (four A operands), walks the query tiles from its
-//          own upwards.  The weight of key j for query i in head h is p = exp(scale (q.k + b)),
-//          so the product is started from b instead of 0 (accumulator input of the first
-//          MFMA) and the largest q.k + b over the heads of the group decides (exp and the
-//          scaling are monotone): one maximum per weight and head, one exponential and one
-//          compare with alpha per weight after the group's last head.  The activations of each
-//          key are then applied in order of the query position (one key per lane).
-// Four products per streamed tile: the streamed tiles come from the caches, and one 4 KB tile
-// per 16x16x128 product leaves the matrix cores waiting for them (a 2048-token prompt of the
-// benchmark's third workload: 13.0 ms per layer with one product per tile, 5.4 with four, 5.7
-// with eight, where the registers allow only two waves per SIMD).  Blocks start in index
-// order, so the heaviest tiles get the lowest indices.
-// Neither kernel has a barrier or waits for another wave.
+//   stats  the four waves of a block keep 64 queries each of one head in registers (four B
+//          operands per wave, loaded straight into the layout) and walk the key tiles 0..their
+//          own together, keeping the running softmax maximum and sum of every query; leaves
+//          b = -(log-sum-exp of the query's scaled logits) / scale per (unit, head, position)
+//          in the workspace
+//   track  the four waves of a block keep 64 keys each in registers (four A operands) and walk
+//          the (query tile, head) pairs from the block's own position upwards together.  The
+//          weight of key j for query i in head h is p = exp(scale (q.k + b)), so the product is
+//          started from b instead of 0 (accumulator input of the first MFMA) and the largest
+//          q.k + b over the heads of the group decides (exp and the scaling are monotone): one
+//          maximum per weight and head, one exponential and one compare with alpha per weight
+//          after the group's last head.  The activations of each key are then applied in order
+//          of the query position (one key per lane).
+// The streamed tile (keys in the first kernel, queries in the second) is fetched once per block
+// and shared through LDS, one barrier per tile: fetched per wave, the second kernel read 7 GB
+// per call past the L2 for a 2048-token prompt of the benchmark's third workload.  Four
+// products per streamed tile and wave (one: the matrix cores wait for operands; eight: the
+// registers allow only two waves per SIMD).  Blocks start in index order, so the heaviest tiles
+// get the lowest indices.  No wave waits for another block.
 #include "kernels.h"
 
 namespace lazyev {
