@@ -127,6 +127,17 @@ int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt /*
                          float *p_out /*device, nullable*/,
                          const float *p_override /*device, nullable*/);
 
+/* The same for ONE sequence of a batch with per-sequence timing (lazyev_admit): the prompt of
+ * slot `seq` (its prompt_len positions, rows already in the caches) is tracked on the slot's own
+ * clock, position i as local step i + 1 - prompt_len.  Call it after lazyev_admit and before the
+ * sequence's first decode step in `layer`.
+ * q_prompt (device): [prompt_len][n_q_heads][head_dim]; p_out / p_override: [n_q_heads][P][P].
+ * Errors: EINVAL (no per-sequence timing, empty slot or prompt, the sequence has decoded in the
+ * layer, shape), EHIP. */
+int lazyev_prefill_track_seq(lazyev_ctx *ctx, int32_t layer, int32_t seq, const void *q_prompt /*device*/,
+                             float *p_out /*device, nullable*/,
+                             const float *p_override /*device, nullable*/);
+
 /* One decode step of one layer (Eq. 4; Alg. 1 tracking loop; Eq. 1):
  *   appends (k_new, v_new) as entry N with TS = t, MRI = 0, pos = P + t - 1;
  *   out[h] = softmax(scale * q[h] K^T) V over the N+1 entries of the head's unit;

@@ -43,7 +43,7 @@ class Stats(C.Structure):
                 ("n_rows_moved", C.POINTER(C.c_int64))]
 
 
-EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step", "lazyev_prefill_track",
+EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step", "lazyev_prefill_track", "lazyev_prefill_track_seq",
            "lazyev_evict", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
@@ -58,6 +58,8 @@ lib.lazyev_init.restype = C.c_int
 lib.lazyev_init.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
 lib.lazyev_prefill_track.restype = C.c_int
 lib.lazyev_prefill_track.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.lazyev_prefill_track_seq.restype = C.c_int
+lib.lazyev_prefill_track_seq.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.lazyev_decode_step.restype = C.c_int
 lib.lazyev_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -209,6 +211,13 @@ class LazyEviction:
         code = lib.lazyev_prefill_track(self._ctx, layer, q_prompt.data_ptr(), _ptr(p_out), _ptr(p_override))
         if code != OK:
             raise LazyevError(code, "lazyev_prefill_track")
+
+    def prefill_track_seq(self, layer, seq, q_prompt, p_out=None, p_override=None):
+        """lazyev_prefill_track_seq.  q_prompt [P,Hq,d]; p_out / p_override [Hq,P,P] fp32."""
+        code = lib.lazyev_prefill_track_seq(self._ctx, layer, seq, q_prompt.data_ptr(), _ptr(p_out),
+                                            _ptr(p_override))
+        if code != OK:
+            raise LazyevError(code, "lazyev_prefill_track_seq")
 
     def evict(self, layer, t) -> int:
         n = C.c_int32(0)

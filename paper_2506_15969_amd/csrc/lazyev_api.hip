@@ -112,8 +112,8 @@ Layout layout_of(const lazyev_config *c) {
   l.logits1 = off;  off = align_up(off + logits_bytes);
   l.stat = off;     off = align_up(off + 2 * units * 16 * sizeof(float));
   // softmax statistics of every (unit, head, prompt position) for the tracking over the prompt
-  l.prefill_stat = off;
-  off = align_up(off + units * 8 * (static_cast<size_t>(c->prompt_len + 15) / 16 * 16) * 2 * sizeof(float));
+  l.prefill_stat = off;                            // (the longest prompt a slot can hold: capacity - window)
+  off = align_up(off + units * 8 * ((cap - c->window + 15) / 16 * 16) * sizeof(float));
   l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
@@ -466,6 +466,37 @@ int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt, f
   a.stat = ctx->prefill_stat;
   a.p_out = p_out; a.p_override = p_override;
   a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
+  const hipError_t e = lazyev::launch_prefill_track(a, ctx->stream);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  return LAZYEV_OK;
+}
+
+int lazyev_prefill_track_seq(lazyev_ctx *ctx, int32_t layer, int32_t seq, const void *q_prompt, float *p_out,
+                             const float *p_override) {
+  if (!ctx || !q_prompt) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  if (layer < 0 || layer >= c.n_layers || seq < 0 || seq >= c.batch) return LAZYEV_EINVAL;
+  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || ctx->group > 8) return LAZYEV_EINVAL;
+  if (!ctx->slots_on || ctx->slot_prompt[seq] < 1) return LAZYEV_EINVAL;
+  if (ctx->last_step[layer] > ctx->slot_t0[seq]) return LAZYEV_EINVAL;   // the sequence has already decoded here
+  const int32_t P = ctx->slot_prompt[seq];
+  const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
+  const size_t first = static_cast<size_t>(seq) * c.n_kv_heads;          // the sequence's first unit
+  lazyev::PrefillArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.batch = 1; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.group = ctx->group;
+  a.capacity = ctx->capacity; a.prompt_len = P;
+  a.p16 = (P + 15) / 16 * 16;
+  a.counter_stride = lazyev::decode_slice_max();
+  a.alpha = c.alpha; a.scale = ctx->scale;
+  a.q_prompt = q_prompt;
+  a.k_cache = static_cast<char *>(c.k_cache) + (static_cast<size_t>(layer) * slab + first * ctx->capacity) * c.head_dim * 2;
+  a.ts = c.ts + static_cast<size_t>(layer) * slab + first * ctx->capacity;
+  a.mri = c.mri + static_cast<size_t>(layer) * slab + first * ctx->capacity;
+  a.stat = ctx->prefill_stat;
+  a.p_out = p_out; a.p_override = p_override;
+  a.activation_counter = ctx->ws.activations +
+                         (static_cast<size_t>(layer) * ctx->units + first) * lazyev::decode_slice_max();
   const hipError_t e = lazyev::launch_prefill_track(a, ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
   return LAZYEV_OK;

@@ -73,6 +73,7 @@ def test_null_context_calls(lazyev_lib):
     assert b.lib.lazyev_stats(None, None) == b.EINVAL
     assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL
     assert b.lib.lazyev_prefill_track(None, 0, 1, None, None) == b.EINVAL
+    assert b.lib.lazyev_prefill_track_seq(None, 0, 0, 1, None, None) == b.EINVAL
     assert b.lib.lazyev_admit(None, 0, 1, 0) == b.EINVAL and b.lib.lazyev_retire(None, 0) == b.EINVAL
     b.lib.lazyev_destroy(None)
     assert b.lib.lazyev_last_hip_error(None) == 0

@@ -194,3 +194,59 @@ def test_prompt_tracking_rejects_what_it_cannot_do(lazyev_lib):
     eng0 = _engine(lazyev_lib, empty, Workload(empty))
     with pytest.raises(lazyev_lib.LazyevError):               # no prompt
         eng0.prefill_track(0, torch.zeros((1, 1, empty.n_q_heads, 128), dtype=torch.bfloat16, device="cuda"))
+
+
+def test_prompt_tracking_of_admitted_sequences(lazyev_lib):
+    """Per-sequence timing: two sequences with prompts of 70 and 33 positions are admitted, each
+    prompt is tracked on its own (lazyev_prefill_track_seq), and 40 decode steps follow (one
+    eviction for the longer sequence).  Oracle units that start from the oracle's prompt state
+    follow exactly (they threshold the exported weights)."""
+    L, S, HKV, G, D, B, W, alpha = 1, 3, 2, 7, 128, 96, 16, 0.03
+    HQ = HKV * G
+    eng = lazyev_lib.LazyEviction(L, S, HQ, HKV, D, B, W, 80, alpha, dtype=torch.bfloat16).init()
+    gen = torch.Generator().manual_seed(5)
+    rnd = lambda *shape: (1.5 * torch.randn(shape, generator=gen)).to(torch.bfloat16)   # noqa: E731
+    eng.retire(1)                                             # the middle slot stays empty
+    units = {}
+    for seq, P in ((0, 70), (2, 33)):
+        k, v = rnd(L, HKV, P, D), rnd(L, HKV, P, D)
+        eng.admit(seq, P, 0, k.cuda(), v.cuda())
+        q = rnd(P, HQ, D)
+        p_out = torch.zeros((HQ, P, P), dtype=torch.float32, device="cuda")
+        eng.prefill_track_seq(0, seq, q.cuda(), p_out=p_out)
+        pg = p_out.cpu().numpy()
+        for h in range(HKV):
+            u = OracleUnit(k[0, h].double().numpy(), v[0, h].double().numpy(), G, B, W, alpha)
+            rows = slice(h * G, (h + 1) * G)
+            u.TS, u.MRI, u.n_activations = prefill_tracking(u.K, q[:, rows].double().numpy(), alpha,
+                                                            p_override=pg[rows])
+            units[(seq, h)] = u
+    eng.stats()
+    for (seq, h), u in units.items():
+        assert np.array_equal(eng.ts[0, seq, h, :len(u)].cpu().numpy(), u.TS), (seq, h)
+        assert np.array_equal(eng.mri[0, seq, h, :len(u)].cpu().numpy(), u.MRI), (seq, h)
+        assert u.MRI.max() >= 1
+    with pytest.raises(lazyev_lib.LazyevError):               # an empty slot has no prompt to track
+        eng.prefill_track_seq(0, 1, rnd(4, HQ, D).cuda())
+    out = torch.empty((S, HQ, D), dtype=torch.bfloat16, device="cuda")
+    p_step = torch.zeros((S, HQ, eng.capacity), dtype=torch.float32, device="cuda")
+    for t in range(1, 41):
+        q, kn, vn = rnd(S, HQ, D), rnd(S, HKV, D), rnd(S, HKV, D)
+        eng.decode_step(0, t, q.cuda(), kn.cuda(), vn.cuda(), out, p_out=p_step)
+        pg = p_step.cpu().numpy()
+        for (seq, h), u in units.items():
+            rows = slice(h * G, (h + 1) * G)
+            u.decode_step(t, q[seq, rows].double().numpy(), kn[seq, h].double().numpy(), vn[seq, h].double().numpy(),
+                          p_override=np.ascontiguousarray(pg[seq, rows, :len(u) + 1]))
+        eng.evict(0, t)
+        for u in units.values():
+            u.evict(t)
+    with pytest.raises(lazyev_lib.LazyevError):               # the sequences have decoded by now
+        eng.prefill_track_seq(0, 0, rnd(70, HQ, D).cuda())
+    eng.stats()
+    assert units[(0, 0)].n_evict_events == 1 and units[(2, 0)].n_evict_events == 0
+    for (seq, h), u in units.items():
+        n = len(u)
+        assert np.array_equal(eng.pos[0, seq, h, :n].cpu().numpy(), u.pos), (seq, h)
+        assert np.array_equal(eng.ts[0, seq, h, :n].cpu().numpy(), u.TS), (seq, h)
+        assert np.array_equal(eng.mri[0, seq, h, :n].cpu().numpy(), u.MRI), (seq, h)
