@@ -18,6 +18,7 @@ namespace {
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / 64;
 constexpr int kMoveBlock = 1024;
+constexpr int kSmallSet = 256;                     // radix select: at most this many keys left -> ranked directly
 
 // 2*sigmoid(-x) = 2/(1+e^x) for x >= 0.  e^x = 2^k * e^r with k = round(x/ln 2) and
 // r = x - k ln 2 taken in two pieces (the high piece of ln 2 has 32 significant bits, so
@@ -158,6 +159,9 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   __shared__ unsigned wave_tot[kSelWaves];
   __shared__ unsigned sel_bin, sel_rem, sel_cnt;
   __shared__ unsigned long long and_k[2], or_k[2];
+  __shared__ unsigned long long small_keys[kSmallSet];   // the keys still in play, once they are few
+  __shared__ unsigned small_n;
+  __shared__ unsigned long long small_thr;
 
   const int tid = threadIdx.x;
   const int unit = blockIdx.x;
@@ -199,7 +203,8 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   }
   __syncthreads();
 
-  // Radix select of the k_keep-th largest key, most significant byte first.  Every pass also
+  // Radix select of the k_keep-th largest key, most significant byte first, until at most
+  // kSmallSet keys are left in play, which are then ranked directly.  Every pass also
   // forms the AND and the OR of the keys still in play: when they agree, all those keys are
   // the same value (the usual case: the threshold falls among the entries that were never
   // re-activated, which all score exactly 0) and the remaining passes are skipped.
@@ -248,6 +253,37 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
     mask |= 255ull << shift;
     k_rem = sel_rem;
     ties_total = sel_cnt;
+    if (shift > 0 && ties_total <= static_cast<unsigned>(kSmallSet)) {
+      // Few keys left in play: instead of one pass per remaining byte, list them and let each
+      // count the listed keys above it and equal to it; the k_rem-th largest is the threshold.
+      if (tid == 0) small_n = 0;
+      __syncthreads();
+      for (int i = tid; i < n_cand; i += kSelBlock) {
+        const unsigned long long key = keys[i];
+        if ((key & mask) == prefix) small_keys[atomicAdd(&small_n, 1u)] = key;
+      }
+      __syncthreads();
+      if (static_cast<unsigned>(tid) < small_n) {
+        const unsigned long long key = small_keys[tid];
+        unsigned gt = 0, eq = 0;
+        for (unsigned j = 0; j < small_n; ++j) {
+          const unsigned long long other = small_keys[j];
+          gt += other > key ? 1u : 0u;
+          eq += other == key ? 1u : 0u;
+        }
+        if (gt < k_rem && k_rem <= gt + eq) {         // (every holder of that value writes the same)
+          small_thr = key;
+          sel_rem = k_rem - gt;
+          sel_cnt = eq;
+        }
+      }
+      __syncthreads();
+      thr = small_thr;
+      k_rem = sel_rem;
+      ties_total = sel_cnt;
+      all_equal = true;
+      break;
+    }
   }
   if (!all_equal) thr = prefix;
   // thr is the threshold key; k_rem of the ties_total entries equal to it are kept, the most
