@@ -2,8 +2,9 @@
 """Decode throughput of the LazyEviction hot path on one MI355X.
 
 A "step" is one decode step of the whole model: for every layer one lazyev_decode_step
-(append, attention, recurrence tracking) and, when t is a multiple of W, one lazyev_evict
-(score, select, compact).  The run replays the workload from its prompt: W warm-up steps on a
+(append, attention, recurrence tracking) and, when t is a multiple of W, the eviction of every
+layer (score, select, compact: lazyev_evict_all, or one lazyev_evict per layer with
+--evict-per-layer).  The run replays the workload from its prompt: W warm-up steps on a
 throw-away pass, the state is reset, then exactly K steps are timed between two
 synchronisations.  Inputs (prompt K/V and every step's q, k_new, v_new) are generated on the
 GPU beforehand and are resident in HBM when the clock starts.
@@ -127,6 +128,8 @@ def main():
     ap.add_argument("--window", type=int, default=0,
                     help="override the observation window W (1 = an eviction after every step, "
                          "the schedule of the greedy methods the paper compares against)")
+    ap.add_argument("--evict-per-layer", action="store_true",
+                    help="one lazyev_evict call per layer instead of lazyev_evict_all")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
     args = ap.parse_args()
@@ -224,12 +227,19 @@ def main():
                                               % (l, t, lib.lazyev_last_hip_error(ctx)))
             if t % W == 0:
                 due = n1_at(t) > cfg.budget
-                for l in range(L):
-                    if l == prof_layer and due:
+                if args.evict_per_layer:
+                    for l in range(L):
+                        if l == prof_layer and due:
+                            lib.lazyev_profile_arm(ctx, 1)
+                        rc = evict(ctx, l, t, None)
+                        if rc:
+                            raise binding.LazyevError(rc, "lazyev_evict(layer %d, t %d)" % (l, t))
+                else:                                        # all layers in one launch pair
+                    if prof_layer >= 0 and due:
                         lib.lazyev_profile_arm(ctx, 1)
-                    rc = evict(ctx, l, t, None)
+                    rc = lib.lazyev_evict_all(ctx, t, None)
                     if rc:
-                        raise binding.LazyevError(rc, "lazyev_evict(layer %d, t %d)" % (l, t))
+                        raise binding.LazyevError(rc, "lazyev_evict_all(t %d)" % t)
 
     # ---- warm-up on a throw-away pass, then the timed pass from the prompt
     reset_state()
@@ -320,10 +330,12 @@ def main():
         }
         if mov_n:
             events = sum(st["n_evict_events"])
-            mb = algorithmic_bytes_move(cfg, sum(st["n_rows_moved"]) / max(events, 1))
+            # bytes of one launch of the row-move kernel: one layer's, or all layers' at once
+            mb = algorithmic_bytes_move(cfg, sum(st["n_rows_moved"]) / max(events, 1)) * (1 if args.evict_per_layer else L)
             mov_k = mov_ms - ov_ms * mov_n
             result["roofline"]["compaction"] = {
-                "kernel": "evict_move_kernel", "avg_us": 1e3 * mov_k / mov_n,
+                "kernel": "evict_move_kernel", "layers_per_launch": 1 if args.evict_per_layer else L,
+                "avg_us": 1e3 * mov_k / mov_n,
                 "select_avg_us": 1e3 * (sel_ms - ov_ms * sel_n) / sel_n, "launches_timed": mov_n,
                 "algorithmic_bytes_per_launch": mb,
                 "rows_moved_per_unit_event": sum(st["n_rows_moved"]) / max(events, 1) / (S * Hkv),

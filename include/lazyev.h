@@ -171,6 +171,14 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * Errors: EINVAL, ECAPACITY (more than LAZYEV_MAX_CANDIDATES candidates), EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
+/* The same check for EVERY layer after decode step t (every layer must have taken step t).
+ * Where the layers stand at the same point, which is the normal course of a model, the
+ * selection and the row move of all layers go in one launch each (the units of different
+ * layers are independent); otherwise this is lazyev_evict layer by layer.  Results are those
+ * of the per-layer calls.  n_evicted: entries removed per unit of a layer (the largest, if the
+ * layers differ).  Errors: those of lazyev_evict. */
+int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted /*host*/);
+
 /* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of
  * *out.  Errors: EINVAL, EHIP. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);

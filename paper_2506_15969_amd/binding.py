@@ -44,7 +44,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step", "lazyev_prefill_track", "lazyev_prefill_track_seq",
-           "lazyev_evict", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
+           "lazyev_evict", "lazyev_evict_all", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
            "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
            "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
            "lazyev_event_overhead",
@@ -65,6 +65,8 @@ lib.lazyev_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.lazyev_evict.restype = C.c_int
 lib.lazyev_evict.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+lib.lazyev_evict_all.restype = C.c_int
+lib.lazyev_evict_all.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_stats.restype = C.c_int
 lib.lazyev_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
 lib.lazyev_admit.restype = C.c_int
@@ -224,6 +226,14 @@ class LazyEviction:
         code = lib.lazyev_evict(self._ctx, layer, t, C.byref(n))
         if code != OK:
             raise LazyevError(code, "lazyev_evict")
+        return n.value
+
+    def evict_all(self, t) -> int:
+        """lazyev_evict_all: the eviction check of every layer after step t."""
+        n = C.c_int32(0)
+        code = lib.lazyev_evict_all(self._ctx, t, C.byref(n))
+        if code != OK:
+            raise LazyevError(code, "lazyev_evict_all")
         return n.value
 
     def stats(self) -> dict:

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   const int unit = blockIdx.x;
   int n = a.n, t = a.t;
   if (a.slots.prompt_len) {                        // per-sequence timing: is this unit's eviction due?
-    const int seq = unit / a.n_kv_heads;
+    const int seq = (unit % a.units_per_layer) / a.n_kv_heads;
     const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
     if (P < 0 || tau < 1 || tau % a.window != 0) return;
     n = slot_n_old(P, tau, a.budget, a.window) + 1;
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
   const int tid = threadIdx.x;
   const int part = blockIdx.x, unit = blockIdx.z;
   if (a.slots.prompt_len) {                        // only units whose eviction was due have a gather list
-    const int seq = unit / a.n_kv_heads;
+    const int seq = (unit % a.units_per_layer) / a.n_kv_heads;
     const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
     if (P < 0 || tau < 1 || tau % a.window != 0 ||
         slot_n_old(P, tau, a.budget, a.window) + 1 <= a.budget)
@@ -413,8 +413,10 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int n_cand = a.n - a.window;
   if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
-  if (a.slots.prompt_len && (!a.slots.t0 || a.n_kv_heads < 1 || a.units % a.n_kv_heads != 0))
+  if (a.units_per_layer < 1 || a.units % a.units_per_layer != 0 || a.units > 65535) return hipErrorInvalidValue;
+  if (a.slots.prompt_len && (!a.slots.t0 || a.n_kv_heads < 1 || a.units_per_layer % a.n_kv_heads != 0))
     return hipErrorInvalidValue;
+  if ((a.score_flags & 32) && a.units != a.units_per_layer) return hipErrorInvalidValue;
   if ((a.score_flags & 32) && (!a.logits || !a.stat || a.group < 1 || a.group > 8 || a.p_stride < a.n))
     return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);

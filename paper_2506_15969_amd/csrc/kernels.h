@@ -96,7 +96,9 @@ struct DecodeArgs {
 };
 
 struct EvictArgs {
-  int32_t units;          // batch * n_kv_heads
+  int32_t units;          // units of the launch: batch * n_kv_heads, times the number of layers
+                          // when consecutive layers (whose slabs follow one another) go together
+  int32_t units_per_layer;  // batch * n_kv_heads
   int32_t head_dim, dtype;
   int32_t capacity;       // C
   int32_t n, budget, window, t;

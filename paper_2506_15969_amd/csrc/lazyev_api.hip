@@ -114,7 +114,7 @@ Layout layout_of(const lazyev_config *c) {
   // softmax statistics of every (unit, head, prompt position) for the tracking over the prompt
   l.prefill_stat = off;                            // (the longest prompt a slot can hold: capacity - window)
   off = align_up(off + units * 8 * ((cap - c->window + 15) / 16 * 16) * sizeof(float));
-  l.src_index = off; off = align_up(off + units * cap * sizeof(int32_t));
+  l.src_index = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * cap * sizeof(int32_t));   // (all layers may be evicted in one go)
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
@@ -524,7 +524,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
   lazyev::EvictArgs a;
   std::memset(&a, 0, sizeof(a));
-  a.units = ctx->units; a.head_dim = c.head_dim; a.dtype = c.dtype; a.capacity = ctx->capacity;
+  a.units = ctx->units; a.units_per_layer = ctx->units; a.head_dim = c.head_dim; a.dtype = c.dtype; a.capacity = ctx->capacity;
   a.n = n; a.budget = c.budget; a.window = c.window; a.t = t; a.score_flags = c.score_flags;
   a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
   a.v_cache = static_cast<char *>(c.v_cache) + static_cast<size_t>(layer) * slab * c.head_dim * esz;
@@ -555,6 +555,72 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
     for (int s2 = 0; s2 < c.batch; ++s2) {
       const int32_t ls = slot_len_now(ctx, layer, s2);
       if (ls > ctx->len[layer]) ctx->len[layer] = ls;
+    }
+  }
+  ctx->last_layer = -1;                            // the stored logits no longer match the slots
+  return LAZYEV_OK;
+}
+
+int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted) {
+  if (n_evicted) *n_evicted = 0;
+  if (!ctx) return LAZYEV_EINVAL;
+  const lazyev_config &c = ctx->cfg;
+  const int L = c.n_layers;
+  // One launch pair for all layers when they stand at the same point (same step, same length,
+  // none evicted yet at this step) and the score does not need a layer's own last decode call;
+  // otherwise layer by layer.
+  bool together = L > 1 && !(c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) &&
+                  static_cast<long long>(L) * ctx->units <= 65535;
+  for (int l = 0; l < L && together; ++l)
+    together = ctx->last_step[l] == t && ctx->len[l] == ctx->len[0] && ctx->evict_applied[l] != t;
+  if (!together) {
+    for (int l = 0; l < L; ++l) {
+      int32_t n1 = 0;
+      const int rc = lazyev_evict(ctx, l, t, &n1);
+      if (rc != LAZYEV_OK) return rc;
+      if (n_evicted && n1 > *n_evicted) *n_evicted = n1;
+    }
+    return LAZYEV_OK;
+  }
+  if (t < 1) return LAZYEV_EINVAL;
+  int32_t n = ctx->len[0];
+  if (ctx->slots_on) {                             // due for any sequence?  sized for the longest of those
+    n = 0;
+    int32_t n_tmp;
+    for (int s2 = 0; s2 < c.batch; ++s2)
+      if (slot_due(ctx, s2, t, &n_tmp) && n_tmp > n) n = n_tmp;
+    if (n == 0) return LAZYEV_OK;
+  } else if (t % c.window != 0 || n <= c.budget) {
+    return LAZYEV_OK;                              // not due (Sec. 4)
+  }
+  if (n - c.window > LAZYEV_MAX_CANDIDATES) return LAZYEV_ECAPACITY;
+  lazyev::EvictArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.units = L * ctx->units; a.units_per_layer = ctx->units;
+  a.head_dim = c.head_dim; a.dtype = c.dtype; a.capacity = ctx->capacity;
+  a.n = n; a.budget = c.budget; a.window = c.window; a.t = t; a.score_flags = c.score_flags;
+  a.k_cache = c.k_cache; a.v_cache = c.v_cache;    // layer 0; the other layers' slabs follow
+  a.ts = c.ts; a.mri = c.mri; a.pos = c.pos;
+  a.ws = ctx->ws;
+  a.rows_moved = ctx->ws.rows_moved;
+  a.n_kv_heads = c.n_kv_heads;
+  a.slots = slots_of(ctx);
+  const hipError_t ef = flush_tracking(ctx);       // scores use TS and MRI of step t (Alg. 1 order)
+  if (ef != hipSuccess) return fail_hip(ctx, ef);
+  const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (n_evicted) *n_evicted = n - c.budget;
+  for (int l = 0; l < L; ++l) {
+    ctx->n_evict_events[l] += 1;
+    ctx->n_evicted[l] += n - c.budget;
+    ctx->evict_applied[l] = t;
+    ctx->len[l] = c.budget;
+    if (ctx->slots_on) {
+      ctx->len[l] = 0;
+      for (int s2 = 0; s2 < c.batch; ++s2) {
+        const int32_t ls = slot_len_now(ctx, l, s2);
+        if (ls > ctx->len[l]) ctx->len[l] = ls;
+      }
     }
   }
   ctx->last_layer = -1;                            // the stored logits no longer match the slots

@@ -260,3 +260,52 @@ def test_long_runs_per_wave(lazyev_lib):
     cfg = cfg.scaled(budget=1416, steps=40)
     stat = run_lockstep(lazyev_lib, cfg, _all_units(cfg), mode="oracle_p", variant=4, target_blocks=8)
     assert stat["evictions"] == 1 and stat["near_threshold"] == 0
+
+
+@pytest.mark.parametrize("variant", [4, 2])
+def test_evicting_all_layers_at_once_equals_layer_by_layer(lazyev_lib, variant):
+    """lazyev_evict_all (selection and row move of all layers in one launch each) against one
+    lazyev_evict per layer: three layers, 140 steps, two evictions, everything bit for bit."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=3, batch=2, prompt_len=100, steps=140, budget=170, window=32)
+    wl = Workload(cfg)
+    runs = []
+    for together in (False, True):
+        eng = make_engine(lazyev_lib, cfg, wl, variant=variant)
+        out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+        ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
+        outs, n_ev = [], 0
+        for t in range(1, cfg.steps + 1):
+            for l in range(cfg.n_layers):
+                q, kn, vn = ins[l]
+                eng.decode_step(l, t, q[t - 1], kn[t - 1], vn[t - 1], out)
+                outs.append(out.clone())
+            if together:
+                n = eng.evict_all(t)
+                n_ev += cfg.n_layers if n else 0
+                assert eng.evict_all(t) == 0                  # a second request finds nothing due
+            else:
+                n_ev += sum(1 if eng.evict(l, t) else 0 for l in range(cfg.n_layers))
+        st = eng.stats()
+        runs.append((torch.stack(outs), eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(),
+                     eng.mri.clone(), eng.pos.clone(), st, n_ev))
+    a, b = runs
+    assert a[7] == b[7] == 3 * 2
+    for x, y in zip(a[:6], b[:6]):
+        assert torch.equal(x, y)
+    assert a[6] == b[6] and sum(a[6]["n_rows_moved"]) > 0
+
+
+def test_evict_all_falls_back_when_layers_differ(lazyev_lib):
+    """Layers at different steps: lazyev_evict_all reports the order error of the per-layer call."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=2, batch=1, prompt_len=40, steps=4, budget=60, window=8)
+    wl = Workload(cfg)
+    eng = make_engine(lazyev_lib, cfg, wl)
+    out = torch.empty((1, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+    q, kn, vn = wl.step_inputs(0, 1, 2, device="cuda")
+    eng.decode_step(0, 1, q[0], kn[0], vn[0], out)            # layer 1 has not taken step 1
+    with pytest.raises(lazyev_lib.LazyevError):
+        eng.evict_all(1)

@@ -27,7 +27,7 @@ def _rand(gen, *shape):
     return torch.randn(shape, generator=gen).to(torch.bfloat16)
 
 
-def _drive(binding, with_weights, follow, variant=None):
+def _drive(binding, with_weights, follow, variant=None, evict_together=False):
     """Runs the scenario.  follow: compare with oracle units step by step (needs with_weights)."""
     gen = torch.Generator().manual_seed(77)
     eng = binding.LazyEviction(L, S, HQ, HKV, D, B, W, PMAX, ALPHA, dtype=torch.bfloat16)
@@ -86,6 +86,10 @@ def _drive(binding, with_weights, follow, variant=None):
                         u = orc[(l, s, h)]
                         assert np.array_equal(ts_g[s, h, :len(u)], u.TS), ("TS", t, l, s, h)
                         assert np.array_equal(mri_g[s, h, :len(u)], u.MRI), ("MRI", t, l, s, h)
+            if evict_together:                               # after the last layer, all layers in one call
+                if l == L - 1:
+                    eng.evict_all(t)
+                continue
             n_ev = eng.evict(l, t)
             if follow:
                 gone = {(s, h): orc[(l, s, h)].evict(t - slot[s][1]) for s in active for h in range(HKV)}
@@ -119,9 +123,11 @@ def test_sequences_on_their_own_clocks(lazyev_lib):
         want = mri_histogram(np.concatenate([u.MRI for (l2, s, h), u in orc.items() if l2 == l]), 40)
         assert eng.mri_histogram(l, 40) == want.tolist()
     # the same scenario without asking for weights (tracking rides with the next launch), with
-    # every logit kept for it and with candidate lists
-    for variant in (5, 6):
-        _, _, _, st2, state2 = _drive(lazyev_lib, with_weights=False, follow=False, variant=variant)
+    # every logit kept for it and with candidate lists, and with the evictions of a step asked for
+    # in one call for all layers
+    for variant, together in ((5, False), (6, False), (6, True)):
+        _, _, _, st2, state2 = _drive(lazyev_lib, with_weights=False, follow=False, variant=variant,
+                                      evict_together=together)
         assert st2 == st
         for x, y in zip(state, state2):
             assert torch.equal(x, y)
