@@ -132,6 +132,8 @@ def main():
                     help="one lazyev_evict call per layer instead of lazyev_evict_all")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
+    ap.add_argument("--progress", type=int, default=0,
+                    help="write a line to stderr every this many submitted steps (long runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path has no cross-GPU part "
@@ -240,6 +242,8 @@ def main():
                     rc = lib.lazyev_evict_all(ctx, t, None)
                     if rc:
                         raise binding.LazyevError(rc, "lazyev_evict_all(t %d)" % t)
+            if args.progress and t % args.progress == 0:
+                print("bench.py: step %d of %d submitted" % (t, n_steps), file=sys.stderr, flush=True)
 
     # ---- warm-up on a throw-away pass, then the timed pass from the prompt
     reset_state()
