@@ -132,6 +132,8 @@ def main():
                     help="one lazyev_evict call per layer instead of lazyev_evict_all")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
+    ap.add_argument("--target-blocks", type=int, default=0,
+                    help="blocks per decode launch, taken literally (lazyev_set_target_blocks)")
     ap.add_argument("--progress", type=int, default=0,
                     help="write a line to stderr every this many submitted steps (long runs)")
     args = ap.parse_args()
@@ -175,6 +177,8 @@ def main():
             eng.set_chunk(args.chunk)
         if args.variant >= 0:
             eng.set_variant(args.variant)
+        if args.target_blocks:
+            eng.set_target_blocks(args.target_blocks)
 
     # ---- inputs resident in HBM
     per_step = L * S * (Hq + 2 * Hkv) * d * esz

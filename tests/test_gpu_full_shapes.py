@@ -103,3 +103,21 @@ def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name):
     assert a[6] == b[6] == 2 and a[5] == b[5] and sum(a[5]["n_activations"]) > 0
     for x, y in zip(a[:5], b[:5]):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("prompt_len", [5200, 8000])
+def test_long_prompt_with_the_default_block_split(lazyev_lib, prompt_len):
+    """A cache far longer than the benchmark budgets at cfg3's batch and head counts (full-cache
+    decoding, or a prompt that exceeds the budget): the library then uses more blocks per unit so
+    that a wave's run still fits on chip (6 and 9 per unit here).  24 steps, sampled units
+    against the oracle, then the first eviction of the long prompt."""
+    from lockstep import run_lockstep
+    base = CONFIGS["cfg3"]
+    cfg = base.scaled(n_layers=1, prompt_len=prompt_len, steps=24, budget=4096, window=24,
+                      interval_lo=4, interval_hi=12, schedule="uniform")
+    units = _sample(cfg, 3, prompt_len, [0])
+    stat = run_lockstep(lazyev_lib, cfg, units, mode="e2e")
+    _report("long-prompt-%d" % prompt_len, stat)
+    assert stat["evictions"] == 1 and stat["near_threshold"] <= 2
+    for u in stat["oracle_units"].values():
+        assert len(u) == 4096
