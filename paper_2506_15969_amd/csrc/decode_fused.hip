@@ -397,8 +397,13 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
 
 // ------------------------------------------------------------------------------- the kernel
 // kCompact: this call leaves candidate lists instead of every logit.
+// The leading scalar arguments repeat what a stream wave needs to request its first sub-tile
+// (the same values are in `a`): scalar kernel arguments are handed to a wave in registers at its
+// start (kernel-argument preload, see build.py), a struct has to be fetched from memory first.
 template <bool kCompact>
-__global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
+    const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split, const int capacity,
+    const int units_call, const int slots_on, const DecodeArgs a) {
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
   // one 16-row K sub-tile per wave while streaming; afterwards the wave's output accumulator
   __shared__ u32x4_t stage_lds[kWaves][16 * 16];
@@ -407,11 +412,11 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   __shared__ int last_flag;
   __shared__ unsigned cand_total;                  // candidate records of this block so far
 
-  const int G = a.group, n_split = a.n_split;
-  if (static_cast<int>(blockIdx.x) >= n_split * a.batch * a.n_kv_heads) {
+  const int G = a.group;
+  if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
-    const int tb = blockIdx.x - n_split * a.batch * a.n_kv_heads;
+    const int tb = blockIdx.x - n_split * units_call;
     const int unit = tb / n_split, part = tb % n_split;
     TrackArgs k;
     if (!track_for_unit(a.track, unit, k)) return;
@@ -438,8 +443,8 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   const int unit = blockIdx.x / n_split, split = blockIdx.x % n_split;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int hc = min(c, G - 1);
-  int n_old = a.n_old;
-  if (a.slots.prompt_len) {                        // per-sequence timing: this unit's own length
+  int n_old = n_old_call;
+  if (slots_on) {                                  // per-sequence timing: this unit's own length
     const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
     if (P < 0 || tau < 1) return;                  // the whole unit sits this call out
     n_old = slot_n_old(P, tau, a.slots.budget, a.slots.window);
@@ -452,10 +457,10 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(const DecodeArg
   const int n_wv = kWaves * n_split, wv = split * kWaves + wave;
   const int cnt = (n_sub - wv + n_wv - 1) / n_wv;  // may be <= 0 for a short cache
 
-  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
-  const bf16_t *vc = static_cast<const bf16_t *>(a.v_cache) + static_cast<size_t>(unit) * a.capacity * D;
-  const bf16_t *k_new = static_cast<const bf16_t *>(a.k_new) + static_cast<size_t>(unit) * D;
-  const bf16_t *v_new = static_cast<const bf16_t *>(a.v_new) + static_cast<size_t>(unit) * D;
+  const bf16_t *kc = k_cache + static_cast<size_t>(unit) * capacity * D;
+  const bf16_t *vc = v_cache + static_cast<size_t>(unit) * capacity * D;
+  const bf16_t *k_new = k_new_all + static_cast<size_t>(unit) * D;
+  const bf16_t *v_new = v_new_all + static_cast<size_t>(unit) * D;
   const bf16_t *q_row = static_cast<const bf16_t *>(a.q) + (head0 + hc) * D + g * 8;
   const int run = min((n_sub + kWaves * n_split - 1) / (kWaves * n_split), kRunMax);
   float *my_logits = logit_lds + static_cast<size_t>(wave) * run * (16 * kHeadPad);
@@ -759,10 +764,15 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   if (run > kRunMax) run = kRunMax;
   const size_t lds_all = static_cast<size_t>(kWaves) * run * 16 * kHeadPad * sizeof(float);
   const int sb = a.n_split * units;
+  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache), *vc = static_cast<const bf16_t *>(a.v_cache);
+  const bf16_t *kn = static_cast<const bf16_t *>(a.k_new), *vn = static_cast<const bf16_t *>(a.v_new);
+  const int slots_on = a.slots.prompt_len ? 1 : 0;
   if (a.variant == 6)
-    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);
+    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
+                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
   else
-    hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream, a);
+    hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
+                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
   const hipError_t e = hipGetLastError();
   if (ev) { (void)hipEventRecord(ev[1], stream); (void)hipEventRecord(ev[2], stream); }
   return e;
