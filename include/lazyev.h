@@ -37,6 +37,7 @@ extern "C" {
                                   eviction with more than LAZYEV_MAX_CANDIDATES candidates        */
 #define LAZYEV_EWORKSPACE -3   /* workspace missing or smaller than lazyev_workspace_size        */
 #define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
+#define LAZYEV_ENOMEM     -5   /* host memory for the context or a read-back buffer ran out      */
 
 #define LAZYEV_DTYPE_FP32  0
 #define LAZYEV_DTYPE_BF16  1
@@ -106,7 +107,7 @@ size_t lazyev_workspace_size(const lazyev_config *cfg /*host*/);
  * 0..P-1 of every unit.  Enqueues: TS = 0, MRI = 0, pos = i for those entries (the state a
  * token has "as if last important when prefill ended"; the paper starts MRI at 0, Sec. 4),
  * and clears the counters.  N = P for every layer.
- * Errors: EINVAL, EWORKSPACE, EHIP. */
+ * Errors: EINVAL, EWORKSPACE, EHIP, ENOMEM. */
 int lazyev_init(const lazyev_config *cfg /*host*/, lazyev_ctx **out /*host*/);
 
 /* Optional start state from the prompt (the paper starts its clock at the first generated
@@ -180,7 +181,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /
 int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted /*host*/);
 
 /* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of
- * *out.  Errors: EINVAL, EHIP. */
+ * *out.  Errors: EINVAL, EHIP, ENOMEM. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
 
 /* Per-sequence timing, for a batch whose sequences do not start together (the paper decodes one
@@ -223,7 +224,7 @@ int lazyev_retire(lazyev_ctx *ctx, int32_t seq);
  * is m, for m < n_bins - 1; hist[n_bins - 1] counts MRI >= n_bins - 1.  hist[0] are the entries
  * never re-activated since they were appended.
  * Applies any tracking still pending and waits for the stream.
- * Errors: EINVAL (2 <= n_bins <= LAZYEV_MAX_HIST_BINS, layer range, null), EHIP. */
+ * Errors: EINVAL (2 <= n_bins <= LAZYEV_MAX_HIST_BINS, layer range, null), EHIP, ENOMEM. */
 int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t *hist /*host*/);
 
 /* Score of Eq. 3 for n (t - TS, MRI) pairs, on the device, with the same code the eviction

@@ -17,7 +17,7 @@ if not os.path.exists(_LIB_PATH):
                       "(expected at %s)" % _LIB_PATH)
 lib = C.CDLL(_LIB_PATH)
 
-OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16

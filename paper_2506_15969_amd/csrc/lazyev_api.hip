@@ -134,8 +134,13 @@ hipEvent_t *arm_events(lazyev_ctx *ctx, int kind) {
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(t.ev[j]);
       return nullptr;
     }
+  try {
+    ctx->prof.push_back(t);
+  } catch (const std::bad_alloc &) {               // the call then goes untimed
+    for (int i = 0; i < 3; ++i) (void)hipEventDestroy(t.ev[i]);
+    return nullptr;
+  }
   ctx->prof_armed -= 1;
-  ctx->prof.push_back(t);
   return ctx->prof.back().ev;
 }
 
@@ -217,7 +222,19 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
     return LAZYEV_EWORKSPACE;
 
   lazyev_ctx *ctx = new (std::nothrow) lazyev_ctx();
-  if (!ctx) return LAZYEV_EINVAL;
+  if (!ctx) return LAZYEV_ENOMEM;
+  try {                                            // (the host mirrors are std::vectors)
+    ctx->slot_prompt.assign(cfg->batch, cfg->prompt_len);
+    ctx->slot_t0.assign(cfg->batch, 0);
+    ctx->evict_applied.assign(cfg->n_layers, 0);
+    ctx->len.assign(cfg->n_layers, cfg->prompt_len);
+    ctx->last_step.assign(cfg->n_layers, 0);
+    ctx->n_evict_events.assign(cfg->n_layers, 0);
+    ctx->n_evicted.assign(cfg->n_layers, 0);
+  } catch (const std::bad_alloc &) {
+    delete ctx;
+    return LAZYEV_ENOMEM;
+  }
   ctx->cfg = *cfg;
   ctx->capacity = capacity_of(cfg);
   ctx->group = cfg->n_q_heads / cfg->n_kv_heads;
@@ -254,13 +271,6 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->dev_slot_t0 = ctx->dev_slot_prompt + cfg->batch;
   ctx->dev_seq_len = ctx->dev_slot_t0 + cfg->batch;
   ctx->slots_on = false;
-  ctx->slot_prompt.assign(cfg->batch, cfg->prompt_len);
-  ctx->slot_t0.assign(cfg->batch, 0);
-  ctx->evict_applied.assign(cfg->n_layers, 0);
-  ctx->len.assign(cfg->n_layers, cfg->prompt_len);
-  ctx->last_step.assign(cfg->n_layers, 0);
-  ctx->n_evict_events.assign(cfg->n_layers, 0);
-  ctx->n_evicted.assign(cfg->n_layers, 0);
   ctx->last_hip_error = 0;
   ctx->prof_armed = 0;
   if (cfg->dtype == LAZYEV_DTYPE_BF16 && cfg->head_dim == 128 &&
@@ -639,6 +649,7 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
   if (e != hipSuccess) return fail_hip(ctx, e);
   e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
+  try {
   if (out->n_activations) {
     const size_t per_layer = static_cast<size_t>(ctx->units) * lazyev::decode_slice_max();
     std::vector<unsigned long long> tmp(per_layer * L);
@@ -661,6 +672,9 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
       for (int k = 0; k < ctx->units; ++k) sum += tmp[static_cast<size_t>(i) * ctx->units + k];
       out->n_rows_moved[i] = static_cast<int64_t>(sum);
     }
+  }
+  } catch (const std::bad_alloc &) {
+    return LAZYEV_ENOMEM;
   }
   for (int i = 0; i < L; ++i) {
     if (out->len) out->len[i] = ctx->len[i];
@@ -686,7 +700,12 @@ int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t
       continue;
     }
     // per-sequence lengths of this layer go to the device first (a rare, synchronous call)
-    std::vector<int32_t> lens(ctx->cfg.batch);
+    std::vector<int32_t> lens;
+    try {
+      lens.resize(ctx->cfg.batch);
+    } catch (const std::bad_alloc &) {
+      return LAZYEV_ENOMEM;
+    }
     int32_t n_max = 0;
     for (int s2 = 0; s2 < ctx->cfg.batch; ++s2) {
       lens[s2] = slot_len_now(ctx, l, s2);
@@ -806,6 +825,7 @@ const char *lazyev_strerror(int code) {
     case LAZYEV_ECAPACITY: return "cache full (a due eviction was skipped), or more eviction candidates than the selection kernel holds";
     case LAZYEV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LAZYEV_EHIP: return "HIP runtime error";
+    case LAZYEV_ENOMEM: return "out of host memory";
     default: return "unknown lazyev error code";
   }
 }

@@ -78,7 +78,7 @@ def test_null_context_calls(lazyev_lib):
     assert b.lib.lazyev_admit(None, 0, 1, 0) == b.EINVAL and b.lib.lazyev_retire(None, 0) == b.EINVAL
     b.lib.lazyev_destroy(None)
     assert b.lib.lazyev_last_hip_error(None) == 0
-    for code in (0, -1, -2, -3, -4, -99):
+    for code in (0, -1, -2, -3, -4, -5, -99):
         assert len(b.lib.lazyev_strerror(code)) > 0
 
 
