@@ -33,8 +33,7 @@ extern "C" {
 
 #define LAZYEV_OK          0
 #define LAZYEV_EINVAL     -1   /* bad shape, null pointer, B <= W, step or layer out of order   */
-#define LAZYEV_ECAPACITY  -2   /* decode_step on a full cache (a due eviction was skipped), or an
-                                  eviction with more than LAZYEV_MAX_CANDIDATES candidates        */
+#define LAZYEV_ECAPACITY  -2   /* decode_step on a full cache (a due eviction was skipped)        */
 #define LAZYEV_EWORKSPACE -3   /* workspace missing or smaller than lazyev_workspace_size        */
 #define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
 #define LAZYEV_ENOMEM     -5   /* host memory for the context or a read-back buffer ran out      */
@@ -56,11 +55,10 @@ extern "C" {
  * lazyev_decode_step of the same layer (the weights of older calls are gone). */
 #define LAZYEV_SCORE_CURRENT_ATTENTION 32
 
-/* Largest number of eviction candidates (cache entries outside the last W) per unit that the
- * selection kernel holds in LDS.  A configuration whose budget or prompt is longer can still
- * decode (a budget that covers the whole generation is the full-cache baseline of Sec. 5), but
- * an eviction that becomes due with more candidates returns LAZYEV_ECAPACITY. */
-#define LAZYEV_MAX_CANDIDATES 8192
+/* Number of eviction candidates (cache entries outside the last W) per unit whose score keys
+ * the selection kernel holds in LDS.  An eviction with more candidates (a prompt far beyond the
+ * budget) ranks through the workspace instead: same result, slower selection. */
+#define LAZYEV_LDS_CANDIDATES 8192
 
 /* Largest number of bins of lazyev_mri_histogram. */
 #define LAZYEV_MAX_HIST_BINS 8192
@@ -169,7 +167,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * original order.  N becomes B.
  * n_evicted (host, nullable): entries removed per unit (N - B, or 0).
  * t must equal the layer's last decode step.
- * Errors: EINVAL, ECAPACITY (more than LAZYEV_MAX_CANDIDATES candidates), EHIP. */
+ * Errors: EINVAL, EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
 /* The same check for EVERY layer after decode step t (every layer must have taken step t).

@@ -23,7 +23,7 @@ SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16
 SCORE_CURRENT_ATTENTION = 32
 MAX_HIST_BINS = 8192
-MAX_CANDIDATES = 8192
+LDS_CANDIDATES = 8192
 
 
 class Config(C.Structure):

@@ -2,7 +2,7 @@
 // paper), as two kernels:
 //   select  one block per unit: scores every candidate entry (all but the last W) in binary64,
 //           finds the (B-W)-th largest score with an 8-bit radix select over the score bit
-//           patterns held in LDS, breaks ties in favour of the more recent entry, prefix-scans
+//           patterns held in LDS (beyond 8192 candidates: in the workspace), breaks ties in favour of the more recent entry, prefix-scans
 //           the keep flags into destination slots, compacts TS / MRI / pos in place and leaves
 //           the gather list (source entry of every survivor) in the workspace.
 //   move    blocks per (unit, K|V, 128-byte column part): walk the gather list in order and
@@ -18,6 +18,7 @@ namespace {
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / 64;
 constexpr int kMoveBlock = 1024;
+constexpr int kLdsCandidates = 8192;               // keys of 8 bytes in the 64 KB of dynamic LDS a launch gets
 constexpr int kSmallSet = 256;                     // radix select: at most this many keys left -> ranked directly
 
 // 2*sigmoid(-x) = 2/(1+e^x) for x >= 0.  e^x = 2^k * e^r with k = round(x/ln 2) and
@@ -153,8 +154,11 @@ __device__ unsigned block_exclusive_scan(unsigned v, unsigned *wave_tot, unsigne
   return base + incl - v;
 }
 
+// kKeysInLds: the candidates' keys fit the dynamic LDS of the launch (the usual case); otherwise
+// they go through the unit's part of the workspace (same passes over global memory, slower).
+template <bool kKeysInLds>
 __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs a) {
-  extern __shared__ unsigned long long keys[];          // score bit pattern of each candidate
+  extern __shared__ unsigned long long keys_lds[];      // score bit pattern of each candidate
   __shared__ unsigned hist[256];
   __shared__ unsigned wave_tot[kSelWaves];
   __shared__ unsigned sel_bin, sel_rem, sel_cnt;
@@ -179,6 +183,8 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   int32_t *mri = a.mri + static_cast<size_t>(unit) * a.capacity;
   int32_t *pos = a.pos + static_cast<size_t>(unit) * a.capacity;
   int32_t *src_index = a.ws.src_index + static_cast<size_t>(unit) * a.capacity;
+  unsigned long long *keys = keys_lds;
+  if (!kKeysInLds) keys = a.ws.sel_keys + static_cast<size_t>(unit) * a.capacity;
 
   // scores (non-negative doubles order like their bit patterns)
   if (a.score_flags & 32) {
@@ -410,6 +416,8 @@ __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs 
 
 }  // namespace
 
+int evict_lds_candidates() { return kLdsCandidates; }
+
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int n_cand = a.n - a.window;
   if (n_cand <= a.budget - a.window || a.n > a.capacity) return hipErrorInvalidValue;
@@ -420,8 +428,12 @@ hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) 
   if ((a.score_flags & 32) && (!a.logits || !a.stat || a.group < 1 || a.group > 8 || a.p_stride < a.n))
     return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
+  if (n_cand > kLdsCandidates && !a.ws.sel_keys) return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
-  hipLaunchKernelGGL(evict_select_kernel, dim3(a.units), dim3(kSelBlock), lds, stream, a);
+  if (n_cand <= kLdsCandidates)
+    hipLaunchKernelGGL(evict_select_kernel<true>, dim3(a.units), dim3(kSelBlock), lds, stream, a);
+  else
+    hipLaunchKernelGGL(evict_select_kernel<false>, dim3(a.units), dim3(kSelBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);

@@ -16,6 +16,8 @@ struct Workspace {
   float    *logits[2];    // [units][p_stride][8]        fused kernel: scaled logits, double-buffered
   float    *stat[2];      // [units][8][2]               fused kernel: softmax max and 1 / sum per head
   int32_t  *src_index;    // [units][C]                  eviction: source entry of survivor j
+  unsigned long long *sel_keys;     // [n_layers][units][C] eviction: score keys of a unit with more candidates
+                                    // than LDS holds; null when the capacity rules that out
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
   unsigned long long *rows_moved;   // [n_layers][units]             entries an eviction moved to a new slot
   int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
@@ -149,6 +151,7 @@ hipError_t decode_unit_prepare();
 size_t decode_unit_lds_bytes(int group, int lds_stride);
 size_t decode_unit_stage_offset(int group, int lds_stride);
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
+int evict_lds_candidates();   // candidates per unit whose keys the selection keeps in LDS
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,
                              int32_t capacity, int32_t prompt_len, hipStream_t stream);
 // One sequence starts over: TS = 0, MRI = 0, pos = i for its first prompt_len entries in every layer.

@@ -92,7 +92,7 @@ constexpr int32_t kCompactMinEntries = 1792;
 size_t fused_p_stride(int32_t capacity) { return static_cast<size_t>((capacity + 15) / 16 * 16) + 65 * 64; }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, activations, rows_moved, ticket, hist, slots, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, sel_keys, activations, rows_moved, ticket, hist, slots, total;
   int32_t n_split_max;
 };
 
@@ -115,6 +115,10 @@ Layout layout_of(const lazyev_config *c) {
   l.prefill_stat = off;                            // (the longest prompt a slot can hold: capacity - window)
   off = align_up(off + units * 8 * ((cap - c->window + 15) / 16 * 16) * sizeof(float));
   l.src_index = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * cap * sizeof(int32_t));   // (all layers may be evicted in one go)
+  // score keys of the selection, only if an eviction can have more candidates than LDS holds
+  l.sel_keys = off;
+  if (cap - c->window > static_cast<size_t>(lazyev::evict_lds_candidates()))
+    off = align_up(off + static_cast<size_t>(c->n_layers) * units * cap * sizeof(unsigned long long));
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
@@ -263,6 +267,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->last_p_stride = 0;
   ctx->prefill_stat = reinterpret_cast<float *>(base + l.prefill_stat);
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
+  ctx->ws.sel_keys = l.activations > l.sel_keys ? reinterpret_cast<unsigned long long *>(base + l.sel_keys) : nullptr;
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
@@ -533,7 +538,6 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   } else if (t % c.window != 0 || n <= c.budget) {
     return LAZYEV_OK;                              // not due (Sec. 4)
   }
-  if (n - c.window > LAZYEV_MAX_CANDIDATES) return LAZYEV_ECAPACITY;   // more than the selection holds
 
   const size_t esz = c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2;
   const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
@@ -608,7 +612,6 @@ int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted) {
   } else if (t % c.window != 0 || n <= c.budget) {
     return LAZYEV_OK;                              // not due (Sec. 4)
   }
-  if (n - c.window > LAZYEV_MAX_CANDIDATES) return LAZYEV_ECAPACITY;
   lazyev::EvictArgs a;
   std::memset(&a, 0, sizeof(a));
   a.units = L * ctx->units; a.units_per_layer = ctx->units;
@@ -822,7 +825,7 @@ const char *lazyev_strerror(int code) {
   switch (code) {
     case LAZYEV_OK: return "ok";
     case LAZYEV_EINVAL: return "invalid argument (shape, null pointer, budget <= window, step or layer out of order)";
-    case LAZYEV_ECAPACITY: return "cache full (a due eviction was skipped), or more eviction candidates than the selection kernel holds";
+    case LAZYEV_ECAPACITY: return "cache full (a due eviction was skipped)";
     case LAZYEV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LAZYEV_EHIP: return "HIP runtime error";
     case LAZYEV_ENOMEM: return "out of host memory";

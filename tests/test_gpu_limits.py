@@ -1,6 +1,7 @@
-"""The sizes at the edge of what the library takes: an eviction with exactly
-LAZYEV_MAX_CANDIDATES candidates (and the error one candidate beyond), and a full-cache decode
-over 16.5 k entries with the largest block split, against the oracle through the C ABI."""
+"""The sizes at the edges of the library's paths: an eviction with exactly LAZYEV_LDS_CANDIDATES
+candidates (keys in LDS), one more and a prompt ten times the budget (keys through the
+workspace), and a full-cache decode over 16.5 k entries with the largest block split, against the
+oracle through the C ABI."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +10,7 @@ from paper_2506_15969_amd.workload import CONFIGS, Workload
 
 pytestmark = pytest.mark.gpu
 
-MAX_CANDIDATES = 8192
+LDS_CANDIDATES = 8192
 
 
 def _report(name, stat):
@@ -23,7 +24,7 @@ def test_eviction_with_the_largest_candidate_count(lazyev_lib):
     """Prompt 8192 > budget 8000, W = 64: the first eviction (step 64) ranks 8256 - 64 = 8192
     candidates, the most the selection kernel holds, keeps 7936 of them and the last 64."""
     from lockstep import run_lockstep
-    cfg = CONFIGS["cfg2"].scaled(batch=1, prompt_len=MAX_CANDIDATES, steps=70, budget=8000, window=64,
+    cfg = CONFIGS["cfg2"].scaled(batch=1, prompt_len=LDS_CANDIDATES, steps=70, budget=8000, window=64,
                                  interval_lo=10, interval_hi=60)
     units = [(0, 0, 1), (0, 0, 3)]
     stat = run_lockstep(lazyev_lib, cfg, units, mode="e2e")
@@ -33,22 +34,34 @@ def test_eviction_with_the_largest_candidate_count(lazyev_lib):
         assert len(u) == 8000 + 6
 
 
-def test_one_candidate_too_many_is_refused(lazyev_lib):
-    cfg = CONFIGS["cfg2"].scaled(batch=1, prompt_len=MAX_CANDIDATES + 1, steps=64, budget=8000, window=64)
-    wl = Workload(cfg)
+@pytest.mark.parametrize("prompt_len,budget", [(LDS_CANDIDATES + 1, 8000), (20000, 2048)])
+def test_more_candidates_than_lds_holds(lazyev_lib, prompt_len, budget):
+    """One candidate more than the selection keeps in LDS, and a prompt ten times the budget: the
+    keys then go through the workspace; same survivors as the oracle's."""
+    from lockstep import run_lockstep
+    cfg = CONFIGS["cfg2"].scaled(batch=1, prompt_len=prompt_len, steps=70, budget=budget, window=64,
+                                 interval_lo=10, interval_hi=60)
+    units = [(0, 0, 0), (0, 0, 2)]
+    stat = run_lockstep(lazyev_lib, cfg, units, mode="e2e")
+    _report("candidates-beyond-lds-%d" % prompt_len, stat)
+    assert stat["evictions"] == 1 and stat["near_threshold"] <= 2
+    for u in stat["oracle_units"].values():
+        assert len(u) == budget + 6
+
+
+def test_workspace_grows_only_when_the_capacity_needs_it(lazyev_lib):
+    """The key area of the selection is part of the workspace only if an eviction can have more
+    candidates than LDS holds."""
     from lockstep import make_engine
-    eng = make_engine(lazyev_lib, cfg, wl)
-    q, kn, vn = wl.step_inputs(0, 1, 65, device="cuda")
-    out = torch.empty((1, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
-    for t in range(1, 65):
-        eng.decode_step(0, t, q[t - 1], kn[t - 1], vn[t - 1], out)
-        if t < 64:
-            assert eng.evict(0, t) == 0
-    with pytest.raises(lazyev_lib.LazyevError) as e:
-        eng.evict(0, 64)
-    assert e.value.code == lazyev_lib.ECAPACITY
-    st = eng.stats()                                      # the context is still usable
-    assert st["len"] == [MAX_CANDIDATES + 1 + 64] and st["n_evict_events"] == [0]
+    small = CONFIGS["cfg2"].scaled(batch=1, prompt_len=LDS_CANDIDATES, steps=8, budget=8000, window=64)
+    large = CONFIGS["cfg2"].scaled(batch=1, prompt_len=LDS_CANDIDATES + 1, steps=8, budget=8000, window=64)
+    sizes = []
+    for cfg in (small, large):
+        eng = make_engine(lazyev_lib, cfg, Workload(cfg))
+        sizes.append(eng.workspace.numel())
+        eng.close()
+    units, cap = large.n_kv_heads, large.capacity
+    assert sizes[1] - sizes[0] >= units * cap * 8 and sizes[1] - sizes[0] < units * cap * 8 + (1 << 16)
 
 
 def test_full_cache_of_16k_entries_with_the_largest_split(lazyev_lib):
