@@ -120,7 +120,8 @@ int lazyev_init(const lazyev_config *cfg /*host*/, lazyev_ctx **out /*host*/);
  * p_out / p_override (device, nullable): [batch][n_q_heads][P][P] fp32, row = query position,
  *   column = key; only the lower triangle (key <= query) is written / read; meaning as in
  *   lazyev_decode_step.
- * bf16 with head_dim 128 and at most 8 query heads per KV head; not with lazyev_admit / retire.
+ * bf16 with head_dim 128 runs on the matrix cores; fp32 or head_dim 64 on a plain vector-ALU
+ * path meant for small prompts.  Not with lazyev_admit / retire.
  * Errors: EINVAL (shape, order, null, P = 0), EHIP. */
 int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt /*device*/,
                          float *p_out /*device, nullable*/,

@@ -119,11 +119,12 @@ struct EvictArgs {
 // Tracking over the prompt (Alg. 1 first loop and Eq. 1 on the prompt's causal attention).
 struct PrefillArgs {
   int32_t batch, n_q_heads, n_kv_heads, group;
+  int32_t head_dim, dtype;          // 64 or 128; 0 fp32, 1 bf16
   int32_t capacity, prompt_len;
   int32_t p16;                      // positions per (unit, head) row of `stat`, >= prompt_len
   int32_t counter_stride;           // activation counters per unit
   float   alpha, scale;
-  const void *q_prompt;             // [batch][prompt_len][n_q_heads][128] bf16
+  const void *q_prompt;             // [batch][prompt_len][n_q_heads][head_dim], the cache's type
   const void *k_cache;              // the layer's slab
   int32_t *ts, *mri;                // the layer's slab
   float *stat;                      // [units][group][p16]: -(log-sum-exp of the scaled logits) / scale per

@@ -468,19 +468,20 @@ int lazyev_prefill_track(lazyev_ctx *ctx, int32_t layer, const void *q_prompt, f
   if (!ctx || !q_prompt) return LAZYEV_EINVAL;
   const lazyev_config &c = ctx->cfg;
   if (layer < 0 || layer >= c.n_layers) return LAZYEV_EINVAL;
-  if (c.dtype != LAZYEV_DTYPE_BF16 || c.head_dim != 128 || ctx->group > 8) return LAZYEV_EINVAL;
   if (ctx->slots_on || c.prompt_len < 1) return LAZYEV_EINVAL;
   if (ctx->last_step[layer] != 0) return LAZYEV_EINVAL;       // the layer has already decoded
   const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
   lazyev::PrefillArgs a;
   std::memset(&a, 0, sizeof(a));
   a.batch = c.batch; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.group = ctx->group;
+  a.head_dim = c.head_dim; a.dtype = c.dtype;
   a.capacity = ctx->capacity; a.prompt_len = c.prompt_len;
   a.p16 = (c.prompt_len + 15) / 16 * 16;
   a.counter_stride = lazyev::decode_slice_max();
   a.alpha = c.alpha; a.scale = ctx->scale;
   a.q_prompt = q_prompt;
-  a.k_cache = static_cast<char *>(c.k_cache) + static_cast<size_t>(layer) * slab * c.head_dim * 2;
+  a.k_cache = static_cast<char *>(c.k_cache) +
+              static_cast<size_t>(layer) * slab * c.head_dim * (c.dtype == LAZYEV_DTYPE_FP32 ? 4 : 2);
   a.ts = c.ts + static_cast<size_t>(layer) * slab;
   a.mri = c.mri + static_cast<size_t>(layer) * slab;
   a.stat = ctx->prefill_stat;
@@ -505,6 +506,7 @@ int lazyev_prefill_track_seq(lazyev_ctx *ctx, int32_t layer, int32_t seq, const 
   lazyev::PrefillArgs a;
   std::memset(&a, 0, sizeof(a));
   a.batch = 1; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.group = ctx->group;
+  a.head_dim = c.head_dim; a.dtype = c.dtype;
   a.capacity = ctx->capacity; a.prompt_len = P;
   a.p16 = (P + 15) / 16 * 16;
   a.counter_stride = lazyev::decode_slice_max();

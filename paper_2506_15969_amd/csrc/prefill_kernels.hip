@@ -1,4 +1,5 @@
-// Recurrence tracking over the prompt (bf16, head_dim 128): the first loop of Alg. 1 and Eq. 1 of
+// Recurrence tracking over the prompt (MFMA kernels for bf16 with head_dim 128, plain vector-ALU
+// kernels at the end of the file for fp32 rows or head_dim 64): the first loop of Alg. 1 and Eq. 1 of
 // the paper applied to the prompt's own causal attention, so that prompt entries enter the
 // decode phase with a TS / MRI history instead of TS = 0, MRI = 0.  Prompt position i (0-based,
 // P positions) acts as the query of step tau_i = i + 1 - P over the keys 0..i; entry i is born
@@ -325,6 +326,102 @@ __global__ __launch_bounds__(kBlock) void prefill_track_kernel(const PrefillArgs
   }
 }
 
+// ---- any other shape (fp32 rows, head_dim 64): the same two steps on the vector ALU, one
+// thread per (unit, head, query position) and one per (unit, key).  A dot product adds its
+// terms in index order in both kernels, so both see the same logit.
+template <int DH, typename T>
+__device__ inline void row_to_float(const T *src, float (&dst)[DH]) {
+#pragma unroll
+  for (int e = 0; e < DH; ++e) {
+    if constexpr (sizeof(T) == 4) dst[e] = src[e];
+    else dst[e] = __uint_as_float(static_cast<unsigned>(src[e]) << 16);
+  }
+}
+template <int DH, typename T>
+__device__ inline float dot_row(const float (&reg)[DH], const T *mem, bool reg_is_q) {
+  float s = 0.f;
+#pragma unroll 8
+  for (int e = 0; e < DH; ++e) {
+    float m;
+    if constexpr (sizeof(T) == 4) m = mem[e];
+    else m = __uint_as_float(static_cast<unsigned>(mem[e]) << 16);
+    s = reg_is_q ? fmaf(reg[e], m, s) : fmaf(m, reg[e], s);
+  }
+  return s;
+}
+
+// stat[(unit * G + h) * p16 + i] = log-sum-exp of the scaled logits of query i of head h
+template <int DH, typename T>
+__global__ __launch_bounds__(256) void prefill_stats_simple_kernel(const PrefillArgs a) {
+  const int P = a.prompt_len, G = a.group;
+  const long long idx = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= static_cast<long long>(a.batch) * a.n_kv_heads * G * P) return;
+  const int i = static_cast<int>(idx % P), h = static_cast<int>((idx / P) % G);
+  const int unit = static_cast<int>(idx / (static_cast<long long>(P) * G));
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const T *q = static_cast<const T *>(a.q_prompt) +
+               ((static_cast<size_t>(seq) * P + i) * a.n_q_heads + kvh * G + h) * DH;
+  const T *k = static_cast<const T *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * DH;
+  float qr[DH];
+  row_to_float<DH>(q, qr);
+  float m = -INFINITY, l = 0.f;
+  for (int j = 0; j <= i; ++j) {
+    const float sc = a.scale * dot_row<DH>(qr, k + static_cast<size_t>(j) * DH, true);
+    if (sc > m) { l = l * __expf(m - sc) + 1.f; m = sc; }      // (exp(-inf) = 0 on the first key)
+    else l += __expf(sc - m);
+  }
+  a.stat[(static_cast<size_t>(unit) * G + h) * a.p16 + i] = m + __logf(l);
+}
+
+template <int DH, typename T>
+__global__ __launch_bounds__(256) void prefill_track_simple_kernel(const PrefillArgs a) {
+  const int P = a.prompt_len, G = a.group;
+  const long long idx = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const bool live = idx < static_cast<long long>(a.batch) * a.n_kv_heads * P;
+  const int j = live ? static_cast<int>(idx % P) : 0;
+  const int unit = live ? static_cast<int>(idx / P) : 0;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  unsigned n_act = 0;
+  if (live) {
+    float kr[DH];
+    row_to_float<DH>(static_cast<const T *>(a.k_cache) + (static_cast<size_t>(unit) * a.capacity + j) * DH, kr);
+    int32_t ts = j + 1 - P, mri = 0;                 // born at its own step
+    for (int i = j; i < P; ++i) {                    // in order of the query position (Alg. 1, Eq. 1)
+      bool on = false;
+      for (int h = 0; h < G; ++h) {
+        const int head = kvh * G + h;
+        const size_t at = ((static_cast<size_t>(seq) * a.n_q_heads + head) * P + i) * P + j;
+        const T *q = static_cast<const T *>(a.q_prompt) + ((static_cast<size_t>(seq) * P + i) * a.n_q_heads + head) * DH;
+        float pw = __expf(a.scale * dot_row<DH>(kr, q, false) - a.stat[(static_cast<size_t>(unit) * G + h) * a.p16 + i]);
+        if (a.p_out) a.p_out[at] = pw;
+        if (a.p_override) pw = a.p_override[at];
+        on = on || pw >= a.alpha;
+      }
+      if (on) {
+        const int32_t tau = i + 1 - P, gap = tau - ts;
+        if (gap > mri) mri = gap;
+        ts = tau;
+        n_act += 1;
+      }
+    }
+    a.ts[static_cast<size_t>(unit) * a.capacity + j] = ts;
+    a.mri[static_cast<size_t>(unit) * a.capacity + j] = mri;
+  }
+  if (a.activation_counter && n_act) atomicAdd(a.activation_counter + static_cast<size_t>(unit) * a.counter_stride, static_cast<unsigned long long>(n_act));
+}
+
+template <int DH, typename T>
+hipError_t launch_prefill_simple(const PrefillArgs &a, hipStream_t stream) {
+  const long long units = static_cast<long long>(a.batch) * a.n_kv_heads;
+  const long long n1 = (units * a.group * a.prompt_len + 255) / 256, n2 = (units * a.prompt_len + 255) / 256;
+  if (n1 > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((prefill_stats_simple_kernel<DH, T>), dim3(static_cast<unsigned>(n1)), dim3(256), 0, stream, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((prefill_track_simple_kernel<DH, T>), dim3(static_cast<unsigned>(n2)), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_prefill_track(const PrefillArgs &a, hipStream_t stream) {
@@ -332,6 +429,10 @@ hipError_t launch_prefill_track(const PrefillArgs &a, hipStream_t stream) {
       a.n_q_heads != a.n_kv_heads * a.group || a.batch < 1 || a.p16 < (a.prompt_len + 15) / 16 * 16 ||
       !a.q_prompt || !a.k_cache || !a.ts || !a.mri || !a.stat || a.counter_stride < 1)
     return hipErrorInvalidValue;
+  if (a.dtype == 0 && a.head_dim == 64) return launch_prefill_simple<64, float>(a, stream);
+  if (a.dtype == 0 && a.head_dim == 128) return launch_prefill_simple<128, float>(a, stream);
+  if (a.dtype == 1 && a.head_dim == 64) return launch_prefill_simple<64, bf16_t>(a, stream);
+  if (a.dtype != 1 || a.head_dim != D) return hipErrorInvalidValue;
   const long long units = static_cast<long long>(a.batch) * a.n_kv_heads;
   const long long n_t = (a.prompt_len + kWaves * kSpan - 1) / (kWaves * kSpan);
   if (units * a.group * n_t > 0x7FFFFFFFLL) return hipErrorInvalidValue;

@@ -32,6 +32,22 @@ def test_prompt_tracking_against_the_oracle(lazyev_lib, P):
     a block of 64.  Exact: the oracle thresholds the weights the library exported.  The weights
     themselves are compared with the oracle's fp64 ones."""
     cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=P, steps=8, budget=max(P, 40) + 60, window=32)
+    _check_prompt_tracking(lazyev_lib, cfg, "P=%d" % P)
+
+
+@pytest.mark.parametrize("name,dtype,hq,hkv,d,P", [("cfg1", "fp32", 4, 4, 64, 64),
+                                                   ("g2-fp32-d128", "fp32", 4, 2, 128, 90),
+                                                   ("g8-bf16-d64", "bf16", 8, 1, 64, 130)])
+def test_prompt_tracking_of_the_other_shapes(lazyev_lib, name, dtype, hq, hkv, d, P):
+    """fp32 rows or head_dim 64 (workload 1 is both): the vector-ALU kernels, same checks."""
+    base = CONFIGS["cfg1"] if name == "cfg1" else CONFIGS["cfg2"]
+    cfg = base.scaled(batch=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=dtype, prompt_len=P,
+                      steps=8, budget=P + 60, window=32)
+    _check_prompt_tracking(lazyev_lib, cfg, name)
+
+
+def _check_prompt_tracking(lazyev_lib, cfg, label):
+    P = cfg.prompt_len
     wl = Workload(cfg)
     G, S, HQ = cfg.group, cfg.batch, cfg.n_q_heads
     q = wl.prompt_queries(0, device="cuda")
@@ -65,8 +81,8 @@ def test_prompt_tracking_against_the_oracle(lazyev_lib, P):
             if near == 0:                                     # then the oracle alone decides the same
                 ts_w, mri_w, _ = prefill_tracking(kd, qc[s][:, rows], cfg.alpha)
                 assert np.array_equal(ts_w, ts_o) and np.array_equal(mri_w, mri_o)
-    print("\n[prefill P=%d] activations=%d max weight err=%.3g weights within 1e-4 of alpha=%d"
-          % (P, n_act, max_err, near), flush=True)
+    print("\n[prefill %s] activations=%d max weight err=%.3g weights within 1e-4 of alpha=%d"
+          % (label, n_act, max_err, near), flush=True)
     assert n_act_gpu == n_act > 0
     assert max_err <= 2e-5
     if P >= 64:
@@ -186,10 +202,6 @@ def test_prompt_tracking_rejects_what_it_cannot_do(lazyev_lib):
         eng.prefill_track(0, wl.prompt_queries(0, device="cuda"))
     with pytest.raises(lazyev_lib.LazyevError):
         eng.prefill_track(5, wl.prompt_queries(0, device="cuda"))
-    cfg32 = CONFIGS["cfg1"].scaled(steps=4)
-    eng32 = _engine(lazyev_lib, cfg32, Workload(cfg32))
-    with pytest.raises(lazyev_lib.LazyevError):               # fp32 / head_dim 64: not this kernel
-        eng32.prefill_track(0, torch.zeros((1, cfg32.prompt_len, cfg32.n_q_heads, cfg32.head_dim), device="cuda"))
     empty = CONFIGS["cfg2"].scaled(batch=1, prompt_len=0, steps=4, budget=60, window=8)
     eng0 = _engine(lazyev_lib, empty, Workload(empty))
     with pytest.raises(lazyev_lib.LazyevError):               # no prompt
