@@ -30,7 +30,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the attention split kernel at the steady-state cache length, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/; the
 # counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 68540 * 1024 + 2545 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 68540 * 1024 + 2545 * 1024,      # 137.4 MB algorithmic at N = 2080.5
+                          "cfg4": 2 * 38180 * 1024 + 5776 * 1024,      # 72.4 MB at N = 1088.5 (every logit kept)
+                          "cfg5": 2 * 134900 * 1024 + 4395 * 1024}     # 271.5 MB at N = 4128.5
 
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
