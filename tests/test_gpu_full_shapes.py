@@ -105,19 +105,24 @@ def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name):
         assert torch.equal(x, y)
 
 
-@pytest.mark.parametrize("prompt_len", [5200, 8000])
-def test_long_prompt_with_the_default_block_split(lazyev_lib, prompt_len):
-    """A cache far longer than the benchmark budgets at cfg3's batch and head counts (full-cache
-    decoding, or a prompt that exceeds the budget): the library then uses more blocks per unit so
-    that a wave's run still fits on chip (6 and 9 per unit here).  24 steps, sampled units
-    against the oracle, then the first eviction of the long prompt."""
+@pytest.mark.parametrize("prompt_len,steps,budget", [(5200, 24, 4096), (8000, 24, 4096), (5100, 40, 4096),
+                                                     (1780, 30, 2048)])
+def test_long_prompt_with_the_default_block_split(lazyev_lib, prompt_len, steps, budget):
+    """Caches beyond the benchmark budgets at cfg3's batch and head counts (full-cache decoding, or
+    a prompt that exceeds the budget): the library then uses more blocks per unit so that a
+    wave's run still fits on chip (6 and 9 per unit for 5200 and 8000 entries).  From 5100
+    entries the cache grows across the length where the split changes from 4 to 6 blocks, so the
+    tracking blocks of one call read the candidate lists of a call with another split; from 1780
+    it grows across the length where candidate lists replace the full logits.  Sampled units
+    against the oracle, with the eviction at the last step where one is due."""
     from lockstep import run_lockstep
     base = CONFIGS["cfg3"]
-    cfg = base.scaled(n_layers=1, prompt_len=prompt_len, steps=24, budget=4096, window=24,
+    cfg = base.scaled(n_layers=1, prompt_len=prompt_len, steps=steps, budget=budget, window=steps,
                       interval_lo=4, interval_hi=12, schedule="uniform")
     units = _sample(cfg, 3, prompt_len, [0])
     stat = run_lockstep(lazyev_lib, cfg, units, mode="e2e")
     _report("long-prompt-%d" % prompt_len, stat)
-    assert stat["evictions"] == 1 and stat["near_threshold"] <= 2
+    due = prompt_len + steps > budget
+    assert stat["evictions"] == (1 if due else 0) and stat["near_threshold"] <= 2
     for u in stat["oracle_units"].values():
-        assert len(u) == 4096
+        assert len(u) == (budget if due else prompt_len + steps)
