@@ -156,7 +156,11 @@ def main():
     if args.window > 0:
         cfg = cfg.scaled(window=args.window, name="%s-window%d" % (cfg.name, args.window))
     if args.no_evict:
-        cfg = cfg.scaled(budget=cfg.prompt_len + K, name=cfg.name + "-fullkv")
+        # (alpha stays the workload's: it is defined from the budget, and a budget of the whole
+        # generation would put the threshold below the weight of an average entry)
+        full = cfg.prompt_len + K
+        cfg = cfg.scaled(budget=full, name=cfg.name + "-fullkv",
+                         alpha_numer=cfg.alpha_numer * (full + cfg.window) / (cfg.budget + cfg.window))
     wl = Workload(cfg)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -400,7 +400,11 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
 // The leading scalar arguments repeat what a stream wave needs to request its first sub-tile
 // (the same values are in `a`): scalar kernel arguments are handed to a wave in registers at its
 // start (kernel-argument preload, see build.py), a struct has to be fetched from memory first.
-template <bool kCompact>
+// kLong (with kCompact): a wave's run is longer than the kRunMax sub-tiles whose logits it keeps
+// in LDS; every kRunMax sub-tiles it then writes the candidates among them, found with the cut
+// that the block's four waves' running statistics give at that moment (a lower bound of the
+// final denominator at any time, so the cut only errs towards more candidates).
+template <bool kCompact, bool kLong = false>
 __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split, const int capacity,
     const int units_call, const int slots_on, const DecodeArgs a) {
@@ -411,6 +415,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   __shared__ unsigned cnt_lds[kWaves];
   __shared__ int last_flag;
   __shared__ unsigned cand_total;                  // candidate records of this block so far
+  __shared__ unsigned long long run_ml[kWaves][kHeadPad];   // kLong: each wave's latest (max, sum) per head, one word
 
   const int G = a.group;
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
@@ -439,6 +444,11 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: scalar branches below
   if (kCompact && tid == 0) cand_total = 0;        // (the block barrier after the stream orders it)
+  if constexpr (kLong) {                           // (here the waves add to it while they stream)
+    if (tid < kWaves * kHeadPad)
+      run_ml[tid / kHeadPad][tid % kHeadPad] = static_cast<unsigned long long>(__float_as_uint(-INFINITY));   // max -inf, sum 0
+    __syncthreads();
+  }
   const int c = lane & 15, g = lane >> 4;
   const int unit = blockIdx.x / n_split, split = blockIdx.x % n_split;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
@@ -585,9 +595,84 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   };
+  // candidates among this wave's sub-tiles it_a .. it_b - 1 (their logits are in LDS from slot 0
+  // on) under the cuts of the eight heads -> records in the block's region
+  auto emit_candidates = [&](int it_a, int it_b, const float (&cut)[kHeadPad]) {
+    float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
+    const int e_in = lane & 15;
+    for (int it0 = it_a; it0 < it_b; it0 += 4) {   // four sub-tiles per round, one entry per lane
+      const int it = it0 + (lane >> 4);
+      bool cand = false;
+      int entry = 0;
+      f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = sa;
+      if (it < it_b) {
+        const float *src = my_logits + (it - it_a) * (16 * kHeadPad) + e_in * kHeadPad;
+        sa = *reinterpret_cast<const f32x4_t *>(src);
+        sb = *reinterpret_cast<const f32x4_t *>(src + 4);
+        entry = (wv + it * n_wv) * 16 + e_in;
+        cand = sa[0] >= cut[0] || sa[1] >= cut[1] || sa[2] >= cut[2] || sa[3] >= cut[3] ||
+               sb[0] >= cut[4] || sb[1] >= cut[5] || sb[2] >= cut[6];
+        cand = (cand && entry < n1) || entry == n_old;
+      }
+      const unsigned long long mask = __builtin_amdgcn_ballot_w64(cand);
+      if (mask != 0) {                             // wave-uniform
+        unsigned base = 0;
+        if (lane == 0) base = atomicAdd(&cand_total, static_cast<unsigned>(__popcll(mask)));
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (cand) {
+          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
+          sb[3] = __int_as_float(entry);
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa;
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb;
+        }
+      }
+    }
+  };
+  // kLong: the segment it_a .. it_b - 1 is complete.  The wave publishes its running (max, sum)
+  // of every head and takes the cut from what the four waves have published so far: sums only
+  // grow, so p <= exp(s - m) / l holds with any earlier (m, l) of any subset of the entries.
+  auto segment_candidates = [&](int it_a, int it_b) {
+    float ls = lsum;
+    ls += __shfl_xor(ls, 16);
+    ls += __shfl_xor(ls, 32);
+    if (g == 0 && c < kHeadPad)
+      run_ml[wave][c] = (static_cast<unsigned long long>(__float_as_uint(ls)) << 32) | __float_as_uint(m_ref);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int hh = lane & 7;
+    float mw[kWaves], lw[kWaves];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const unsigned long long v = run_ml[w][hh];  // one 8-byte word: a consistent pair
+      mw[w] = __uint_as_float(static_cast<unsigned>(v));
+      lw[w] = __uint_as_float(static_cast<unsigned>(v >> 32));
+    }
+    float mbh = mw[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, mw[w]);
+    float lbh = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+      if (mw[w] != -INFINITY) lbh = fmaf(__expf(mw[w] - mbh), lw[w], lbh);
+    const float cut_h = (hh < G && lbh > 0.f) ? mbh + __logf(0.98f * a.alpha * lbh) : INFINITY;
+    float cut[kHeadPad];
+#pragma unroll
+    for (int h = 0; h < kHeadPad; ++h)
+      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
+    emit_candidates(it_a, it_b, cut);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the LDS slots are written again next
+    __builtin_amdgcn_wave_barrier();
+  };
   for (int it = 0; it < cnt; ++it) {
     compute(buf, it);
-    if (it + 1 - seg0 == kRunMax && it + 1 < cnt) { flush(seg0, it + 1); seg0 = it + 1; }
+    if (it + 1 - seg0 == kRunMax && it + 1 < cnt) {
+      if constexpr (kLong) segment_candidates(seg0, it + 1);
+      else flush(seg0, it + 1);
+      seg0 = it + 1;
+    }
   }
   if (!kCompact) flush(seg0, cnt);
   // ---- the four waves of the block -> one partial
@@ -666,13 +751,14 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
                                     static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
     const int e_in = lane & 15;
-    for (int it0 = 0; it0 < cnt; it0 += 4) {       // four sub-tiles per round, one entry per lane
+    const int s0 = kLong ? seg0 : 0;               // (kLong: the earlier segments are done)
+    for (int it0 = s0; it0 < cnt; it0 += 4) {      // four sub-tiles per round, one entry per lane
       const int it = it0 + (lane >> 4);
       bool cand = false;
       int entry = 0;
       f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = sa;
       if (it < cnt) {
-        const float *src = my_logits + it * (16 * kHeadPad) + e_in * kHeadPad;
+        const float *src = my_logits + (it - s0) * (16 * kHeadPad) + e_in * kHeadPad;
         sa = *reinterpret_cast<const f32x4_t *>(src);
         sb = *reinterpret_cast<const f32x4_t *>(src + 4);
         entry = (wv + it * n_wv) * 16 + e_in;
@@ -732,7 +818,7 @@ int decode_fused_head_pad() { return kHeadPad; }
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group) {
   if (n_split < 1 || n_split > kFusedSplitMax || group >= kHeadPad) return false;
   const int cap = fused_part_cap(n_old, n_split);
-  return (cap - 1) / (kWaves * 16) <= kRunMax && static_cast<long long>(cap) * n_split <= p_stride;
+  return static_cast<long long>(cap) * n_split <= p_stride;
 }
 
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
@@ -767,7 +853,11 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache), *vc = static_cast<const bf16_t *>(a.v_cache);
   const bf16_t *kn = static_cast<const bf16_t *>(a.k_new), *vn = static_cast<const bf16_t *>(a.v_new);
   const int slots_on = a.slots.prompt_len ? 1 : 0;
-  if (a.variant == 6)
+  const bool long_run = (n_sub + kWaves * a.n_split - 1) / (kWaves * a.n_split) > kRunMax;
+  if (a.variant == 6 && long_run)
+    hipLaunchKernelGGL((decode_fused_kernel<true, true>), dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
+                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
+  else if (a.variant == 6)
     hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
                        kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
   else

@@ -375,11 +375,11 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
       const int by_run = (n_sub + 32) / 64;
       if (by_run < n_split) n_split = by_run;
       if (n_split < lo) n_split = lo;
-      // a long cache: enough blocks that a wave's run (about 15 sub-tiles) still fits the part
-      // of LDS that holds its logits, so that only candidate lists leave the chip (measured on
-      // 5120..24576 entries: 0-8 % faster than two blocks per compute unit)
-      const int by_fit = (n_sub + 59) / 60;
-      if ((n_sub + 4 * n_split - 1) / (4 * n_split) > 20 && by_fit > n_split) n_split = by_fit;
+      // a long cache (a wave's run exceeds the 20 sub-tiles whose logits it keeps in LDS and
+      // leaves its candidate lists segment by segment): one block per compute unit streams
+      // fastest (measured at 8192 / 16384 / 32768 entries, 256 against 512 blocks: 93 / 165 /
+      // 329 us against 95 / 171 / 345)
+      if ((n_sub + 4 * n_split - 1) / (4 * n_split) > 20) n_split = lo;
     }
     if (n_split > (n_sub + 3) / 4) n_split = (n_sub + 3) / 4;
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();

@@ -69,20 +69,28 @@ def test_cfg2_full_length_on_sampled_units(lazyev_lib):
         assert len(early & set(u.pos.tolist())) >= 0.75 * len(early)
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg5"])
-def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name):
-    """Benchmark shapes in steady state, two layers, 70 steps with an eviction: the default
-    (candidate lists for the deferred tracking at these cache lengths) against the same kernel
-    keeping every logit: outputs, caches, TS / MRI / pos and counters bit for bit."""
+@pytest.mark.parametrize("name,prompt_len,budget,target_blocks,n_ev",
+                         [("cfg3", 2048, 2048, None, 2), ("cfg5", 4096, 4096, None, 2),
+                          # runs of 47 sub-tiles per wave: the lists are written segment by segment
+                          ("cfg3", 6000, 6000, 256, 2),
+                          # the cache grows across the change of split (4 -> 6 blocks per unit)
+                          ("cfg3", 5080, 8000, None, 0),
+                          # one block per unit and 100 sub-tiles per wave
+                          ("cfg5", 6400, 8000, 128, 0)])
+def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name, prompt_len, budget,
+                                                            target_blocks, n_ev):
+    """Benchmark shapes, two layers, 70 steps: the default (candidate lists for the deferred
+    tracking at these cache lengths) against the same kernel keeping every logit: outputs,
+    caches, TS / MRI / pos and counters bit for bit."""
     import torch
     from lockstep import make_engine
     from paper_2506_15969_amd.workload import Workload
     base = CONFIGS[name]
-    cfg = base.scaled(n_layers=2, prompt_len=base.budget, steps=70)
+    cfg = base.scaled(n_layers=2, prompt_len=prompt_len, budget=budget, steps=70)
     wl = Workload(cfg)
     runs = []
     for variant in (4, 5):
-        eng = make_engine(lazyev_lib, cfg, wl, variant=variant)
+        eng = make_engine(lazyev_lib, cfg, wl, variant=variant, target_blocks=target_blocks)
         out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
         ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
         acc = torch.zeros_like(out, dtype=torch.float32)
@@ -100,7 +108,7 @@ def test_candidate_lists_leave_the_same_state_as_all_logits(lazyev_lib, name):
                      eng.mri[:, :, :, :n].clone(), eng.pos[:, :, :, :n].clone(), st, n_ev))
         eng.close()
     a, b = runs
-    assert a[6] == b[6] == 2 and a[5] == b[5] and sum(a[5]["n_activations"]) > 0
+    assert a[6] == b[6] == n_ev and a[5] == b[5] and sum(a[5]["n_activations"]) > 0
     for x, y in zip(a[:5], b[:5]):
         assert torch.equal(x, y)
 
