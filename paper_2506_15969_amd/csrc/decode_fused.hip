@@ -415,7 +415,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   __shared__ unsigned cnt_lds[kWaves];
   __shared__ int last_flag;
   __shared__ unsigned cand_total;                  // candidate records of this block so far
-  __shared__ unsigned long long run_ml[kWaves][kHeadPad];   // kLong: each wave's latest (max, sum) per head, one word
+  __shared__ float run_lse[kWaves][kHeadPad];      // kLong: each wave's latest log-sum-exp per head (one word: no torn reads)
 
   const int G = a.group;
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
@@ -445,8 +445,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // wave-uniform: scalar branches below
   if (kCompact && tid == 0) cand_total = 0;        // (the block barrier after the stream orders it)
   if constexpr (kLong) {                           // (here the waves add to it while they stream)
-    if (tid < kWaves * kHeadPad)
-      run_ml[tid / kHeadPad][tid % kHeadPad] = static_cast<unsigned long long>(__float_as_uint(-INFINITY));   // max -inf, sum 0
+    if (tid < kWaves * kHeadPad) run_lse[tid / kHeadPad][tid % kHeadPad] = -INFINITY;   // nothing seen yet
     __syncthreads();
   }
   const int c = lane & 15, g = lane >> 4;
@@ -630,34 +629,30 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       }
     }
   };
-  // kLong: the segment it_a .. it_b - 1 is complete.  The wave publishes its running (max, sum)
-  // of every head and takes the cut from what the four waves have published so far: sums only
-  // grow, so p <= exp(s - m) / l holds with any earlier (m, l) of any subset of the entries.
+  // kLong: the segment it_a .. it_b - 1 is complete.  The wave publishes the log-sum-exp of
+  // every head over what it has seen and takes the cut from what the four waves have published
+  // so far: the sums only grow, so p <= exp(s - lse) holds with the log-sum-exp of any subset of
+  // the entries at any earlier time.
   auto segment_candidates = [&](int it_a, int it_b) {
     float ls = lsum;
     ls += __shfl_xor(ls, 16);
     ls += __shfl_xor(ls, 32);
-    if (g == 0 && c < kHeadPad)
-      run_ml[wave][c] = (static_cast<unsigned long long>(__float_as_uint(ls)) << 32) | __float_as_uint(m_ref);
+    if (g == 0 && c < kHeadPad) run_lse[wave][c] = ls > 0.f ? m_ref + __logf(ls) : -INFINITY;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int hh = lane & 7;
-    float mw[kWaves], lw[kWaves];
+    float lw[kWaves];
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const unsigned long long v = run_ml[w][hh];  // one 8-byte word: a consistent pair
-      mw[w] = __uint_as_float(static_cast<unsigned>(v));
-      lw[w] = __uint_as_float(static_cast<unsigned>(v >> 32));
-    }
-    float mbh = mw[0];
+    for (int w = 0; w < kWaves; ++w) lw[w] = run_lse[w][hh];
+    float lmax = lw[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, mw[w]);
-    float lbh = 0.f;
+    for (int w = 1; w < kWaves; ++w) lmax = fmaxf(lmax, lw[w]);
+    float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w)
-      if (mw[w] != -INFINITY) lbh = fmaf(__expf(mw[w] - mbh), lw[w], lbh);
-    const float cut_h = (hh < G && lbh > 0.f) ? mbh + __logf(0.98f * a.alpha * lbh) : INFINITY;
+      if (lw[w] != -INFINITY) sum += __expf(lw[w] - lmax);
+    const float cut_h = (hh < G && sum > 0.f) ? lmax + __logf(0.98f * a.alpha * sum) : INFINITY;
     float cut[kHeadPad];
 #pragma unroll
     for (int h = 0; h < kHeadPad; ++h)
