@@ -38,7 +38,10 @@
 // stays under alpha in every head cannot reach alpha.  The block then writes only the other
 // entries ("candidates", about a tenth on the benchmark workloads; the appended entry always)
 // as records (7 logits, entry index) into its own region of the logits buffer, and the
-// tracking applies the exact test to the records: the same state bit for bit.
+// tracking applies the exact test to the records: the same state bit for bit.  A wave whose run
+// is longer than the sub-tiles it keeps in LDS (instance <true, true>) writes the candidates of
+// every full segment while it streams, with the cut that the block's waves' running sums give
+// at that moment, and only the last segment after the merge.
 //
 // MFMA operand layouts (lane l, c = l % 16, g = l / 16):
 //   16x16x32: A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]
