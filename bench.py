@@ -134,6 +134,9 @@ def main():
                     help="one lazyev_evict call per layer instead of lazyev_evict_all")
     ap.add_argument("--no-evict", action="store_true",
                     help="full-cache baseline: budget covers prompt + all steps")
+    ap.add_argument("--ragged", action="store_true",
+                    help="per-sequence timing (lazyev_admit): sequence s takes its first step at "
+                         "global step 1 + s %% W, so the sequences' evictions fall on different steps")
     ap.add_argument("--target-blocks", type=int, default=0,
                     help="blocks per decode launch, taken literally (lazyev_set_target_blocks)")
     ap.add_argument("--progress", type=int, default=0,
@@ -155,6 +158,8 @@ def main():
         cfg = cfg.scaled(prompt_len=args.prompt_len, name="%s-prompt%d" % (cfg.name, args.prompt_len))
     if args.window > 0:
         cfg = cfg.scaled(window=args.window, name="%s-window%d" % (cfg.name, args.window))
+    if args.ragged:
+        cfg = cfg.scaled(name=cfg.name + "-ragged")
     if args.no_evict:
         # (alpha stays the workload's: it is defined from the budget, and a budget of the whole
         # generation would put the threshold below the weight of an average entry)
@@ -185,6 +190,9 @@ def main():
             eng.set_variant(args.variant)
         if args.target_blocks:
             eng.set_target_blocks(args.target_blocks)
+        if args.ragged:
+            for sq in range(S):                     # (the prompt rows are in the caches already)
+                eng.admit(sq, cfg.prompt_len, sq % W)
 
     # ---- inputs resident in HBM
     per_step = L * S * (Hq + 2 * Hkv) * d * esz
@@ -215,6 +223,20 @@ def main():
     # saw-tooth, used to attach algorithmic bytes to the profiled calls
     first = (max(cfg.budget - cfg.prompt_len, 0) // W + 1) * W     # first step with P + t > B, t = kW
 
+    def n1_ragged(t, sq):
+        """Entries of sequence sq after the append of global step t (0: it has not started)."""
+        tau = t - sq % W
+        if tau < 1:
+            return 0
+        return lib.lazyev_cached_before_step(cfg.prompt_len, tau, cfg.budget, W) + 1
+
+    def bytes_at(t):
+        """Algorithmic bytes of one layer call at step t."""
+        if not args.ragged:
+            return algorithmic_bytes_decode(cfg, n1_at(t))
+        one = cfg.scaled(batch=1)
+        return sum(algorithmic_bytes_decode(one, n1_ragged(t, sq)) for sq in range(S) if n1_ragged(t, sq))
+
     def n1_at(t):
         if t <= first:
             return cfg.prompt_len + t
@@ -237,7 +259,11 @@ def main():
                 if rc:
                     raise binding.LazyevError(rc, "lazyev_decode_step(layer %d, t %d), HIP error %d"
                                               % (l, t, lib.lazyev_last_hip_error(ctx)))
-            if t % W == 0:
+            if args.ragged:                                  # the library knows which sequences are due
+                rc = lib.lazyev_evict_all(ctx, t, None)
+                if rc:
+                    raise binding.LazyevError(rc, "lazyev_evict_all(t %d)" % t)
+            elif t % W == 0:
                 due = n1_at(t) > cfg.budget
                 if args.evict_per_layer:
                     for l in range(L):
@@ -297,7 +323,7 @@ def main():
     ov_ms = ov.value
     # bytes of the profiled decode calls
     prof_steps = [t for t in range(1, K + 1) if args.profile_every and t % args.profile_every == 0]
-    dec_bytes = sum(algorithmic_bytes_decode(cfg, n1_at(t)) for t in prof_steps)
+    dec_bytes = sum(bytes_at(t) for t in prof_steps)
     ev_steps = [t for t in prof_steps if t % W == 0 and n1_at(t) > cfg.budget]
     split_ms, split_n = prof["split"]
     comb_ms, comb_n = prof["combine"]
@@ -356,7 +382,7 @@ def main():
                 "achieved": mb / (mov_k / mov_n * 1e-3) / 1e9,
                 "frac": mb / (mov_k / mov_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
         # whole-step view: all algorithmic decode bytes of the run over the wall time
-        tot = sum(algorithmic_bytes_decode(cfg, n1_at(t)) for t in range(1, K + 1)) * L
+        tot = sum(bytes_at(t) for t in range(1, K + 1)) * L
         result["roofline"]["whole_run_frac"] = tot / elapsed / 1e9 / HBM_PEAK_GBS
     if not args.no_cpu_baseline:
         eng.close()
