@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kSelBlock) void evict_select_kernel(const EvictArgs
   __shared__ unsigned long long small_thr;
 
   const int tid = threadIdx.x;
-  const int unit = blockIdx.x;
+  const int unit = evict_unit_of(a, blockIdx.x);
   int n = a.n, t = a.t;
   if (a.slots.prompt_len) {                        // per-sequence timing: is this unit's eviction due?
     const int seq = (unit % a.units_per_layer) / a.n_kv_heads;
@@ -352,7 +352,7 @@ template <int U, int LPP>                      // LPP lanes of 16 bytes per row 
 __global__ __launch_bounds__(kMoveBlock) void evict_move_kernel(const EvictArgs a, int row_bytes) {
   constexpr int ROWS = kMoveBlock / LPP;       // rows per block load
   const int tid = threadIdx.x;
-  const int part = blockIdx.x, unit = blockIdx.z;
+  const int part = blockIdx.x, unit = evict_unit_of(a, blockIdx.z);
   if (a.slots.prompt_len) {                        // only units whose eviction was due have a gather list
     const int seq = (unit % a.units_per_layer) / a.n_kv_heads;
     const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
@@ -429,20 +429,27 @@ hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev) 
     return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(n_cand) * sizeof(unsigned long long);
   if (n_cand > kLdsCandidates && !a.ws.sel_keys) return hipErrorInvalidValue;
+  int n_blocks = a.units;                          // one per unit, or only the due sequences' units
+  if (a.n_due > 0) {
+    if (!a.slots.prompt_len || a.n_due > 8) return hipErrorInvalidValue;
+    for (int i = 0; i < a.n_due; ++i)
+      if (a.due_seq[i] < 0 || a.due_seq[i] * a.n_kv_heads >= a.units_per_layer) return hipErrorInvalidValue;
+    n_blocks = a.units / a.units_per_layer * a.n_due * a.n_kv_heads;
+  }
   if (ev) (void)hipEventRecord(ev[0], stream);
   if (n_cand <= kLdsCandidates)
-    hipLaunchKernelGGL(evict_select_kernel<true>, dim3(a.units), dim3(kSelBlock), lds, stream, a);
+    hipLaunchKernelGGL(evict_select_kernel<true>, dim3(n_blocks), dim3(kSelBlock), lds, stream, a);
   else
-    hipLaunchKernelGGL(evict_select_kernel<false>, dim3(a.units), dim3(kSelBlock), 0, stream, a);
+    hipLaunchKernelGGL(evict_select_kernel<false>, dim3(n_blocks), dim3(kSelBlock), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev) (void)hipEventRecord(ev[1], stream);
   const int row_bytes = a.head_dim * (a.dtype == 0 ? 4 : 2);
   if (row_bytes % 256 == 0) {
-    hipLaunchKernelGGL((evict_move_kernel<8, 16>), dim3(row_bytes / 256, 2, a.units), dim3(kMoveBlock),
+    hipLaunchKernelGGL((evict_move_kernel<8, 16>), dim3(row_bytes / 256, 2, n_blocks), dim3(kMoveBlock),
                        0, stream, a, row_bytes);
   } else {
-    hipLaunchKernelGGL((evict_move_kernel<8, 8>), dim3(row_bytes / 128, 2, a.units), dim3(kMoveBlock),
+    hipLaunchKernelGGL((evict_move_kernel<8, 8>), dim3(row_bytes / 128, 2, n_blocks), dim3(kMoveBlock),
                        0, stream, a, row_bytes);
   }
   e = hipGetLastError();

@@ -114,7 +114,20 @@ struct EvictArgs {
   int32_t group, p_stride;
   int32_t n_kv_heads;
   Slots slots;            // with slots: n is the largest of the due sequences', t global
+  // with slots, when few sequences are due: only their units are launched.  Block index i then
+  // stands for layer i / (n_due * n_kv_heads), due sequence (i / n_kv_heads) % n_due and KV head
+  // i % n_kv_heads.  n_due = 0: one block per unit as usual.
+  int32_t n_due;
+  int32_t due_seq[8];
 };
+
+// The unit a block of an eviction launch works on.
+__host__ __device__ inline int32_t evict_unit_of(const EvictArgs &a, int32_t i) {
+  if (a.n_due <= 0) return i;
+  const int32_t per_layer = a.n_due * a.n_kv_heads;
+  const int32_t layer = i / per_layer, r = i % per_layer;
+  return layer * a.units_per_layer + a.due_seq[r / a.n_kv_heads] * a.n_kv_heads + r % a.n_kv_heads;
+}
 
 // Tracking over the prompt (Alg. 1 first loop and Eq. 1 on the prompt's causal attention).
 struct PrefillArgs {

@@ -197,6 +197,19 @@ int32_t slot_len_now(const lazyev_ctx *ctx, int layer, int s) {
   return n_old + 1;
 }
 
+// With per-sequence timing: when at most 8 sequences are due after step t, an eviction launch
+// covers only their units.
+void fill_due(const lazyev_ctx *ctx, int32_t t, lazyev::EvictArgs &a) {
+  a.n_due = 0;
+  if (!ctx->slots_on) return;
+  int32_t n_tmp;
+  for (int s = 0; s < ctx->cfg.batch; ++s) {
+    if (!slot_due(ctx, s, t, &n_tmp)) continue;
+    if (a.n_due == 8) { a.n_due = 0; return; }     // many: one block per unit, the others return at once
+    a.due_seq[a.n_due++] = s;
+  }
+}
+
 // Applies the tracking of the last fused decode call if it is still pending.
 hipError_t flush_tracking(lazyev_ctx *ctx) {
   if (!ctx->pend.valid) return hipSuccess;
@@ -556,6 +569,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.rows_moved = ctx->ws.rows_moved + static_cast<size_t>(layer) * ctx->units;
   a.n_kv_heads = c.n_kv_heads;
   a.slots = slots_of(ctx);
+  fill_due(ctx, t, a);
   if (c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) {
     // the weights of step t: only there if this layer's decode call was the last one
     if (ctx->last_layer != layer || !ctx->last_logits) return LAZYEV_EINVAL;
@@ -625,6 +639,7 @@ int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted) {
   a.rows_moved = ctx->ws.rows_moved;
   a.n_kv_heads = c.n_kv_heads;
   a.slots = slots_of(ctx);
+  fill_due(ctx, t, a);
   const hipError_t ef = flush_tracking(ctx);       // scores use TS and MRI of step t (Alg. 1 order)
   if (ef != hipSuccess) return fail_hip(ctx, ef);
   const hipError_t e = lazyev::launch_evict(a, ctx->stream, arm_events(ctx, 1));

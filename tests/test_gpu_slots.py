@@ -154,3 +154,52 @@ def test_slot_calls_reject_what_they_cannot_do(lazyev_lib):
     fp32 = b.LazyEviction(1, 2, 4, 4, 64, 32, 4, 8, 0.1, dtype=torch.float32).init()
     with pytest.raises(b.LazyevError):
         fp32.admit(0, 4, 0)
+
+
+def test_admitted_batch_on_one_clock_equals_the_uniform_batch(lazyev_lib):
+    """Ten sequences admitted with the same prompt length and start step behave as the uniform
+    batch: all ten are due at the same steps (more than an eviction launch lists one by one, so it
+    covers every unit), outputs and state bit for bit; then with two start steps (five sequences
+    due at a time: the launch covers only those) against each sequence's own uniform run."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import CONFIGS, Workload
+    cfg = CONFIGS["cfg2"].scaled(batch=10, prompt_len=100, steps=75, budget=120, window=16)
+    wl = Workload(cfg)
+    S, steps = cfg.batch, cfg.steps
+    ins = wl.step_inputs(0, 1, steps + 1, device="cuda")
+
+    def run(offsets):
+        """offsets[s]: the global step before sequence s's first one (None: no admit calls)."""
+        eng = make_engine(lazyev_lib, cfg, wl, target_blocks=2 * S * cfg.n_kv_heads)   # two blocks per unit throughout
+        if offsets is not None:
+            for s in range(S):
+                eng.admit(s, cfg.prompt_len, offsets[s])
+        out = torch.empty((S, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+        outs = []
+        q, kn, vn = ins
+        last = steps + (max(offsets) if offsets else 0)
+        for t in range(1, last + 1):
+            # sequence s is fed the inputs of ITS local step
+            loc = [min(max(t - (offsets[s] if offsets else 0), 1), steps) for s in range(S)]
+            idx = torch.tensor(loc, device="cuda") - 1
+            ar = torch.arange(S, device="cuda")
+            eng.decode_step(0, t, q[idx, ar].contiguous(), kn[idx, ar].contiguous(), vn[idx, ar].contiguous(), out)
+            outs.append(out.clone())
+            eng.evict_all(t)
+        eng.stats()
+        state = (eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(), eng.mri.clone(), eng.pos.clone())
+        eng.close()
+        return outs, state
+
+    base_outs, base_state = run(None)
+    same_outs, same_state = run([0] * S)
+    n = cfg.budget + (steps % cfg.window)
+    for a, b in zip(base_outs, same_outs):
+        assert torch.equal(a, b)
+    for a, b in zip(base_state, same_state):
+        assert torch.equal(a[:, :, :, :n], b[:, :, :, :n])
+    offs = [0 if s % 2 == 0 else 5 for s in range(S)]
+    two_outs, two_state = run(offs)
+    for s in range(S):
+        for tau in range(1, steps + 1):                        # local step tau of sequence s
+            assert torch.equal(two_outs[tau + offs[s] - 1][s], base_outs[tau - 1][s]), (s, tau)
