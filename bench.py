@@ -4,14 +4,25 @@
 A "step" is one decode step of the whole model: for every layer one lazyev_decode_step
 (append, attention, recurrence tracking) and, when t is a multiple of W, the eviction of every
 layer (score, select, compact: lazyev_evict_all, or one lazyev_evict per layer with
---evict-per-layer).  The run replays the workload from its prompt: W warm-up steps on a
-throw-away pass, the state is reset, then exactly K steps are timed between two
-synchronisations.  Inputs (prompt K/V and every step's q, k_new, v_new) are generated on the
-GPU beforehand and are resident in HBM when the clock starts.
+--evict-per-layer).  Two ways to place the K timed steps:
+
+  from the prompt   (K reaches the workload's first eviction, e.g. the default K = all 16384
+                    steps): the run replays the workload from its prompt.
+  steady state      (a short K, e.g. --steps 20): the metric is quoted on a cache AT its budget
+                    with evictions running, which a short run from a 256-token prompt never
+                    reaches.  The prompt is then as long as the budget, TS / MRI start from the
+                    prompt's own attention (lazyev_prefill_track), an untimed pre-roll brings the
+                    cache to the step where the K timed steps straddle an eviction (they lie
+                    around t = W), and the K steps are timed from there.
+
+In both, --warmup steps run first on a throw-away pass, the state is rebuilt, and exactly K steps
+are timed between two synchronisations.  Inputs (prompt K/V and every step's q, k_new, v_new)
+are generated on the GPU beforehand and are resident in HBM when the clock starts.
 
 Prints one JSON line: whole-job steps/s (value), tokens/s, the HBM roofline of the attention
-split kernel measured with HIP events inside the timed region, and the CPU oracle timed on the
-host cores on a bounded sample of the same workload.
+kernel measured with HIP events inside the timed region (one event pair around the L layer calls
+of a step: interval / L, nothing subtracted), and the CPU oracle timed on the host cores on a
+bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -27,12 +38,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the attention split kernel at the steady-state cache length, from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (summaries under profiles/; the
-# counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb).
-MEASURED_TRAFFIC_BYTES = {"cfg3": 2 * 68540 * 1024 + 2545 * 1024,      # 137.4 MB algorithmic at N = 2080.5
-                          "cfg4": 2 * 38180 * 1024 + 5776 * 1024,      # 72.4 MB at N = 1088.5 (every logit kept)
-                          "cfg5": 2 * 134900 * 1024 + 4395 * 1024}     # 271.5 MB at N = 4128.5
+# HBM bytes per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this script in the steady state (summaries under profiles/decode_fused_<cfg>_steady.txt; the
+# counters are scaled by what they read for the plain copy kernel of --calibrate-copy-mb):
+# (mean entries per unit after the append in that profile, bytes).  Printed as roofline.traffic
+# only when the timed steps of this run have the same mean cache length.
+PROFILED_TRAFFIC = {"cfg3": (2080.5, 2 * 68540 * 1024 + 2545 * 1024),      # 137.4 MB algorithmic
+                    "cfg4": (1088.5, 2 * 38180 * 1024 + 5776 * 1024),      # 72.4 MB (every logit kept)
+                    "cfg5": (4128.5, 2 * 134900 * 1024 + 4395 * 1024)}     # 271.5 MB
 
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
@@ -58,6 +71,7 @@ def _oracle_worker(job):
     steps and the eviction that follows."""
     name, seed = job
     import numpy as np
+    from dataclasses import replace
     try:
         from threadpoolctl import threadpool_limits
         limiter = threadpool_limits(1)
@@ -65,7 +79,10 @@ def _oracle_worker(job):
         limiter = None
     from oracle.lazyev_oracle import OracleUnit
     from paper_2506_15969_amd.workload import CONFIGS
-    cfg = CONFIGS[name]
+    base, _, over = name.partition("|")               # "cfg3" or "cfg3|budget=..,window=.."
+    cfg = CONFIGS[base]
+    if over:
+        cfg = replace(cfg, **{k: int(v) for k, v in (kv.split("=") for kv in over.split(","))})
     rng = np.random.default_rng(seed)
     G, d, B, W = cfg.group, cfg.head_dim, cfg.budget, cfg.window
     u = OracleUnit(rng.standard_normal((B, d)), rng.standard_normal((B, d)), G, B, W, cfg.alpha)
@@ -86,14 +103,19 @@ def cpu_baseline(cfg, target_seconds: float = 15.0) -> dict:
     import multiprocessing as mp
     cores = max(1, min(16, len(os.sched_getaffinity(0))))
     ctx = mp.get_context("spawn")
-    with ctx.Pool(cores) as pool:
-        w, dt = pool.map(_oracle_worker, [(cfg.name, 0)])[0]          # calibrate on one unit
+    pool = ctx.Pool(cores)
+    try:
+        key = "%s|budget=%d,window=%d" % (cfg.name.split("-")[0], cfg.budget, cfg.window)
+        w, dt = pool.map(_oracle_worker, [(key, 0)])[0]               # calibrate on one unit
         per_unit = max(dt, 1e-3)
         rounds = max(1, int(target_seconds / per_unit))
-        jobs = [(cfg.name, 1 + i) for i in range(cores * rounds)]
+        jobs = [(key, 1 + i) for i in range(cores * rounds)]
         t0 = time.perf_counter()
         res = pool.map(_oracle_worker, jobs, chunksize=1)
         wall = time.perf_counter() - t0
+    finally:
+        pool.close()                                    # let the workers exit by themselves
+        pool.join()
     unit_steps = sum(r[0] for r in res)
     unit_steps_per_s = unit_steps / wall
     units_per_model = cfg.n_layers * cfg.batch * cfg.n_kv_heads
@@ -113,16 +135,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--chunk", type=int, default=0, help="split-block size override")
-    ap.add_argument("--input-steps", type=int, default=0,
-                    help="steps of inputs kept in HBM (0: all timed steps if they fit in "
-                         "--input-gb, else as many as fit; later steps reuse them cyclically)")
-    ap.add_argument("--input-gb", type=float, default=150.0)
-    ap.add_argument("--profile-every", type=int, default=16,
-                    help="time one layer call with HIP events every this many steps")
+    ap.add_argument("--input-gb", type=float, default=150.0,
+                    help="cap on the inputs kept in HBM; beyond it later steps reuse them cyclically")
+    ap.add_argument("--profile-every", type=int, default=0,
+                    help="bracket the layer calls of every this many steps with a HIP event pair "
+                         "(0: every step up to 1024 timed steps, every 16th beyond)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--from-prompt", action="store_true",
+                    help="time the K steps from the workload's own prompt even when K is too short "
+                         "to reach the first eviction (the cache then stays below its budget)")
     ap.add_argument("--prompt-len", type=int, default=-1,
-                    help="override the workload's prompt length (prompt = budget puts the cache "
-                         "in its steady state from the first step; used for short profiling runs)")
+                    help="override the workload's prompt length and time from that prompt")
     ap.add_argument("--variant", type=int, default=-1, help="attention kernel override (lazyev_set_variant)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="after the timed region, run one plain copy kernel of this many MiB "
@@ -139,6 +162,10 @@ def main():
                          "global step 1 + s %% W, so the sequences' evictions fall on different steps")
     ap.add_argument("--target-blocks", type=int, default=0,
                     help="blocks per decode launch, taken literally (lazyev_set_target_blocks)")
+    ap.add_argument("--single-call-window", action="store_true",
+                    help="after the timed region, run one more untimed window of W steps with ONE "
+                         "layer call per step bracketed by the library's own events "
+                         "(roofline.single_call)")
     ap.add_argument("--progress", type=int, default=0,
                     help="write a line to stderr every this many submitted steps (long runs)")
     args = ap.parse_args()
@@ -154,10 +181,24 @@ def main():
 
     cfg = CONFIGS[args.config]
     K = args.steps or cfg.steps
-    if args.prompt_len >= 0:
-        cfg = cfg.scaled(prompt_len=args.prompt_len, name="%s-prompt%d" % (cfg.name, args.prompt_len))
     if args.window > 0:
         cfg = cfg.scaled(window=args.window, name="%s-window%d" % (cfg.name, args.window))
+    W = cfg.window
+
+    def first_eviction(c):
+        """First step after which an eviction fires: the smallest t = kW with P + t > B."""
+        return (max(c.budget - c.prompt_len, 0) // c.window + 1) * c.window
+
+    # ---- where the K timed steps lie
+    steady = (not args.from_prompt and args.prompt_len < 0 and not args.no_evict and not args.ragged
+              and K < first_eviction(cfg) and cfg.dtype == "bf16" and cfg.head_dim == 128)
+    pre = 0
+    if steady:
+        cfg = cfg.scaled(prompt_len=cfg.budget, name=cfg.name + "-steady")
+        if K < W:
+            pre = W - (K + 1) // 2                  # the timed steps pre+1 .. pre+K straddle t = W
+    elif args.prompt_len >= 0:
+        cfg = cfg.scaled(prompt_len=args.prompt_len, name="%s-prompt%d" % (cfg.name, args.prompt_len))
     if args.ragged:
         cfg = cfg.scaled(name=cfg.name + "-ragged")
     if args.no_evict:
@@ -169,8 +210,10 @@ def main():
     wl = Workload(cfg)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    L, S, Hq, Hkv, d, W = cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window
+    L, S, Hq, Hkv, d = cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     esz = 4 if cfg.dtype == "fp32" else 2
+    follow = W if args.single_call_window else 0    # untimed steps after the timed ones
+    total_steps = pre + K + follow
 
     try:
         eng = binding.LazyEviction(L, S, Hq, Hkv, d, cfg.budget, W, cfg.prompt_len, cfg.alpha,
@@ -190,14 +233,18 @@ def main():
             eng.set_variant(args.variant)
         if args.target_blocks:
             eng.set_target_blocks(args.target_blocks)
+        if steady:
+            # TS / MRI of the budget-long prompt from the prompt's own attention, so that the
+            # eviction ranks a varied state and not 2048 untouched entries
+            for l in range(L):
+                eng.prefill_track(l, wl.prompt_queries(l, device=dev))
         if args.ragged:
             for sq in range(S):                     # (the prompt rows are in the caches already)
                 eng.admit(sq, cfg.prompt_len, sq % W)
 
     # ---- inputs resident in HBM
     per_step = L * S * (Hq + 2 * Hkv) * d * esz
-    R = args.input_steps or K
-    R = max(1, min(R, K, int(args.input_gb * 1e9 // per_step)))
+    R = max(1, min(total_steps, int(args.input_gb * 1e9 // per_step)))
     t_gen = time.perf_counter()
     q_all = torch.empty((R, L, S, Hq, d), dtype=cfg.torch_dtype, device=dev)
     k_all = torch.empty((R, L, S, Hkv, d), dtype=cfg.torch_dtype, device=dev)
@@ -214,14 +261,20 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    lib, ctx = binding.lib, None
+    lib = binding.lib
     q_base, k_base, v_base, o_base = q_all.data_ptr(), k_all.data_ptr(), v_all.data_ptr(), out.data_ptr()
     q_sz, kv_sz = S * Hq * d * esz, S * Hkv * d * esz
     decode, evict = lib.lazyev_decode_step, lib.lazyev_evict
 
     # cache length (after the append) seen by the decode call of step t: closed form of the
-    # saw-tooth, used to attach algorithmic bytes to the profiled calls
-    first = (max(cfg.budget - cfg.prompt_len, 0) // W + 1) * W     # first step with P + t > B, t = kW
+    # saw-tooth, used to attach algorithmic bytes to the bracketed calls
+    first = first_eviction(cfg)
+
+    def n1_at(t):
+        if t <= first:
+            return cfg.prompt_len + t
+        last_ev = (t - 1) // W * W
+        return cfg.budget + (t - last_ev)
 
     def n1_ragged(t, sq):
         """Entries of sequence sq after the append of global step t (0: it has not started)."""
@@ -237,67 +290,87 @@ def main():
         one = cfg.scaled(batch=1)
         return sum(algorithmic_bytes_decode(one, n1_ragged(t, sq)) for sq in range(S) if n1_ragged(t, sq))
 
-    def n1_at(t):
-        if t <= first:
-            return cfg.prompt_len + t
-        last_ev = (t - 1) // W * W
-        return cfg.budget + (t - last_ev)
+    def due_at(t):
+        return t % W == 0 and n1_at(t) > cfg.budget
 
-    def run(n_steps, profile_every=0):
-        """n_steps decode steps from t = 1; one layer call is event-timed every
-        `profile_every` steps (the layer rotates)."""
+    brackets = []                                    # (step, event before layer 0, event after layer L-1)
+
+    def run(t_from, t_to, bracket_every=0, single_call=False):
+        """Decode steps t_from .. t_to.  bracket_every: one event pair around the L layer calls
+        of every bracket_every-th step (the due eviction comes after the closing event).
+        single_call: the library brackets ONE layer call per step itself (the layer rotates)."""
         ctx = eng._ctx
-        for t in range(1, n_steps + 1):
+        for t in range(t_from, t_to + 1):
             r = (t - 1) % R
-            prof_layer = (t // profile_every) % L if profile_every and t % profile_every == 0 else -1
+            bracket = bracket_every and (t - t_from) % bracket_every == 0
+            armed = t % L if single_call else -1
+            if bracket:
+                ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                ev[0].record()
             for l in range(L):
                 i = r * L + l
-                if l == prof_layer:
+                if l == armed:
                     lib.lazyev_profile_arm(ctx, 1)
                 rc = decode(ctx, l, t, q_base + i * q_sz, k_base + i * kv_sz, v_base + i * kv_sz,
                             o_base + l * q_sz, None, None)
                 if rc:
                     raise binding.LazyevError(rc, "lazyev_decode_step(layer %d, t %d), HIP error %d"
                                               % (l, t, lib.lazyev_last_hip_error(ctx)))
+            if bracket:
+                ev[1].record()
+                brackets.append((t, ev[0], ev[1]))
             if args.ragged:                                  # the library knows which sequences are due
                 rc = lib.lazyev_evict_all(ctx, t, None)
                 if rc:
                     raise binding.LazyevError(rc, "lazyev_evict_all(t %d)" % t)
             elif t % W == 0:
-                due = n1_at(t) > cfg.budget
+                due = due_at(t)
                 if args.evict_per_layer:
                     for l in range(L):
-                        if l == prof_layer and due:
+                        if l == 0 and due and bracket_every:
                             lib.lazyev_profile_arm(ctx, 1)
                         rc = evict(ctx, l, t, None)
                         if rc:
                             raise binding.LazyevError(rc, "lazyev_evict(layer %d, t %d)" % (l, t))
                 else:                                        # all layers in one launch pair
-                    if prof_layer >= 0 and due:
-                        lib.lazyev_profile_arm(ctx, 1)
+                    if due and bracket_every:
+                        lib.lazyev_profile_arm(ctx, 1)       # select and move kernels, timed apart
                     rc = lib.lazyev_evict_all(ctx, t, None)
                     if rc:
                         raise binding.LazyevError(rc, "lazyev_evict_all(t %d)" % t)
             if args.progress and t % args.progress == 0:
-                print("bench.py: step %d of %d submitted" % (t, n_steps), file=sys.stderr, flush=True)
+                print("bench.py: step %d of %d submitted" % (t, t_to), file=sys.stderr, flush=True)
 
-    # ---- warm-up on a throw-away pass, then the timed pass from the prompt
+    # ---- warm-up on a throw-away pass, then the state the timed steps start from
     reset_state()
-    run(args.warmup)
+    run(1, args.warmup)
     torch.cuda.synchronize()
     reset_state()
-    torch.cuda.synchronize()
+    run(1, pre)                                      # untimed pre-roll (steady state only)
+    st0 = eng.stats()                                # (applies pending tracking, waits for the stream)
+    eng.profile_read()                               # forget anything armed so far
+    every = args.profile_every or (1 if K <= 1024 else 16)
     t_start = time.perf_counter()
-    run(K, args.profile_every)
+    run(pre + 1, pre + K, every)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    prof = eng.profile_read()
+    st = eng.stats()
+    timed_evictions = sum(1 for t in range(pre + 1, pre + K + 1) if due_at(t)) if not args.ragged else None
 
+    single = None
+    if follow:
+        run(pre + K + 1, pre + K + follow, 0, single_call=True)
+        torch.cuda.synchronize()
+        single = eng.profile_read()
+
+    probes = binding.bench_lib()
+    stream_ptr = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     if args.calibrate_copy_mb:
         nbytes = args.calibrate_copy_mb << 20
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        lib.lazyev_stream_probe(dst.data_ptr(), src.data_ptr(), nbytes, 2048,
-                                torch.cuda.current_stream(dev).cuda_stream)
+        probes.lazyev_stream_probe(dst.data_ptr(), src.data_ptr(), nbytes, 2048, stream_ptr)
         torch.cuda.synchronize()
         del src, dst
     # what a plain streaming read reaches on this box (1 GiB, non-temporal loads, two blocks per
@@ -305,36 +378,28 @@ def main():
     probe_bytes = 1 << 30
     probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
     probe_sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    stream_ptr = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    lib.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
+    probes.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
     ev0.record()
     for _ in range(5):
-        lib.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
+        probes.lazyev_stream_read_probe(probe_src.data_ptr(), probe_bytes, 512, probe_sink.data_ptr(), stream_ptr)
     ev1.record()
     torch.cuda.synchronize()
     read_probe_gbs = 5 * probe_bytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del probe_src
-    prof = eng.profile_read()
-    st = eng.stats()
-    # what a pair of HIP events adds to the kernel it brackets (empty kernel, same stream)
+    # what a pair of HIP events adds to the interval it brackets (empty kernel, same stream)
     ov = C.c_double(0.0)
-    lib.lazyev_event_overhead(200, C.c_void_p(torch.cuda.current_stream(dev).cuda_stream), C.byref(ov))
+    probes.lazyev_event_overhead(200, stream_ptr, C.byref(ov))
     ov_ms = ov.value
-    # bytes of the profiled decode calls
-    prof_steps = [t for t in range(1, K + 1) if args.profile_every and t % args.profile_every == 0]
-    dec_bytes = sum(bytes_at(t) for t in prof_steps)
-    ev_steps = [t for t in prof_steps if t % W == 0 and n1_at(t) > cfg.budget]
-    split_ms, split_n = prof["split"]
-    comb_ms, comb_n = prof["combine"]
-    sel_ms, sel_n = prof["select"]
-    mov_ms, mov_n = prof["move"]
-    assert split_n == len(prof_steps), (split_n, len(prof_steps))
 
+    timed_steps = list(range(pre + 1, pre + K + 1))
+    n1s = [n1_at(t) for t in timed_steps] if not args.ragged else []
     steps_per_s = K / elapsed
+    with_ev = bool(timed_evictions) or (args.ragged and sum(st["n_evict_events"]) > sum(st0["n_evict_events"]))
     result = {
-        "metric": "decode steps/s at batch %d, budget %d (incl. eviction); tokens/s = value x batch"
-                  % (S, cfg.budget),
+        "metric": "decode steps/s at batch %d, budget %d (%s); tokens/s = value x batch"
+                  % (S, cfg.budget, "incl. eviction" if with_ev else
+                     "NO eviction fell into the timed steps: the cache is below its budget"),
         "value": steps_per_s, "unit": "steps/s", "tokens_per_s": steps_per_s * S,
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -342,48 +407,86 @@ def main():
         "config": {"workload": cfg.name, "layers": L, "batch": S, "q_heads": Hq, "kv_heads": Hkv,
                    "head_dim": d, "prompt_len": cfg.prompt_len, "budget": cfg.budget,
                    "window": W, "alpha": cfg.alpha, "input_steps_resident": R,
-                   "evictions_per_layer": st["n_evict_events"][0],
-                   "activations_per_unit_step": sum(st["n_activations"]) / (K * L * S * Hkv)},
+                   "placement": ("steady state: prompt = budget with TS/MRI from the prompt's own "
+                                 "attention, %d untimed pre-roll steps, timed steps t = %d..%d"
+                                 % (pre, pre + 1, pre + K)) if steady else
+                                "from the prompt: timed steps t = 1..%d" % K,
+                   "entries_per_unit_in_timed_steps": [min(n1s), max(n1s)] if n1s else None,
+                   "mean_entries_per_unit": sum(n1s) / len(n1s) if n1s else None,
+                   "evictions_in_timed_region": timed_evictions,
+                   "evictions_per_layer": st["n_evict_events"][0] - st0["n_evict_events"][0],
+                   "activations_per_unit_step": (sum(st["n_activations"]) - sum(st0["n_activations"]))
+                                                / (K * L * S * Hkv)},
         "input_generation_s": t_gen,
     }
-    # which attention kernel the library picks for this shape (see lazyev_set_variant)
-    fused = cfg.dtype == "bf16" and d == 128 and args.variant in (-1, 1, 4)
-    if split_n:
-        # event intervals minus the fixed cost of the event pair itself
-        split_k = split_ms - ov_ms * split_n
-        call_k = split_ms + comb_ms - 2 * ov_ms * split_n
-        ach = dec_bytes / (split_k * 1e-3) / 1e9
-        result["roofline"] = {
+    if steady and K < W:
+        # one eviction per K < W steps over-weights it; what a whole window of W such steps costs
+        sel_ms, sel_n = prof["select"]
+        mov_ms, mov_n = prof["move"]
+        if sel_n and mov_n:
+            ev_ms = (sel_ms + mov_ms) / sel_n
+            dec_ms = (1e3 * elapsed - ev_ms * timed_evictions) / K
+            result["config"]["steps_per_s_over_a_whole_window"] = 1e3 / (dec_ms + ev_ms / W)
+    fused = cfg.dtype == "bf16" and d == 128 and args.variant in (-1, 1, 4, 5, 6)
+    if brackets:
+        group_ms = sum(a.elapsed_time(b) for _, a, b in brackets)
+        n_launch = L * len(brackets)
+        dec_bytes = sum(bytes_at(t) for t, _, _ in brackets) * L
+        avg_us = 1e3 * group_ms / n_launch
+        ach = dec_bytes / (group_ms * 1e-3) / 1e9
+        roof = {
             "kernel": ("decode_fused_kernel (the one kernel of lazyev_decode_step)"
-                       if fused else "first of the two kernels of lazyev_decode_step (split; "
-                                     "decode_call covers split + merge)"),
+                       if fused else "the two kernels of lazyev_decode_step (split, merge)"),
             "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "frac": ach / HBM_PEAK_GBS, "traffic": None,
+            "avg_us": avg_us, "launches_timed": n_launch,
+            "algorithmic_bytes_per_launch": dec_bytes / n_launch,
+            "how": "one HIP event pair on the library's stream around the %d layer calls of a step, "
+                   "interval / %d, nothing subtracted (the pair itself costs %.1f us per step, the "
+                   "turn-around between two dependent launches is inside)" % (L, L, 1e3 * ov_ms),
             "plain_read_on_this_box": {"GB/s": read_probe_gbs, "frac_of_it": ach / read_probe_gbs,
-                                       "what": "1 GiB read once with non-temporal loads, grid-stride, 512 blocks of 256 threads (the fastest of 512..65536 blocks: 7.0 TB/s; 1024..16384 blocks reach 5.6-6.2)"},
-            "avg_us": 1e3 * split_k / split_n, "avg_us_between_events": 1e3 * split_ms / split_n,
-            "event_pair_overhead_us": 1e3 * ov_ms, "launches_timed": split_n,
-            "algorithmic_bytes_per_launch": dec_bytes / split_n,
-            "decode_call": {"avg_us": 1e3 * call_k / split_n,
-                            "achieved": dec_bytes / (call_k * 1e-3) / 1e9,
-                            "frac": dec_bytes / (call_k * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                                       "what": "1 GiB read once with non-temporal loads, grid-stride, 512 blocks of 256 threads"},
         }
+        prof_n1 = PROFILED_TRAFFIC.get(cfg.name.split("-")[0])
+        mean_n1 = result["config"]["mean_entries_per_unit"]
+        if fused and prof_n1 and mean_n1 and abs(mean_n1 - prof_n1[0]) <= 0.01 * prof_n1[0]:
+            roof["traffic"] = prof_n1[1]
+            roof["traffic_source"] = ("profiles/decode_fused_%s_steady.txt (FETCH_SIZE x 2 + WRITE_SIZE per "
+                                      "launch at a mean of %.1f entries per unit; this run: %.1f); a "
+                                      "profile constant, not a counter read in this run"
+                                      % (cfg.name.split("-")[0], prof_n1[0], mean_n1))
+        if single and single["split"][1]:
+            s_ms, s_n = single["split"]
+            c_ms, c_n = single["combine"]
+            tf = range(pre + K + 1, pre + K + follow + 1)
+            b1 = sum(bytes_at(t) for t in tf) / len(tf)
+            k_us = 1e3 * (s_ms - ov_ms * s_n) / s_n
+            roof["single_call"] = {
+                "what": "untimed follow-up window of %d steps, ONE layer call per step between two events "
+                        "recorded by the library, the cost of an empty event pair subtracted" % follow,
+                "avg_us": k_us, "avg_us_between_events": 1e3 * s_ms / s_n,
+                "event_pair_overhead_us": 1e3 * ov_ms, "launches_timed": s_n,
+                "algorithmic_bytes_per_launch": b1, "frac": b1 / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        sel_ms, sel_n = prof["select"]
+        mov_ms, mov_n = prof["move"]
         if mov_n:
-            events = sum(st["n_evict_events"])
+            events = sum(st["n_evict_events"]) - sum(st0["n_evict_events"])
+            rows = sum(st["n_rows_moved"]) - sum(st0["n_rows_moved"])
             # bytes of one launch of the row-move kernel: one layer's, or all layers' at once
-            mb = algorithmic_bytes_move(cfg, sum(st["n_rows_moved"]) / max(events, 1)) * (1 if args.evict_per_layer else L)
+            mb = algorithmic_bytes_move(cfg, rows / max(events, 1)) * (1 if args.evict_per_layer else L)
             mov_k = mov_ms - ov_ms * mov_n
-            result["roofline"]["compaction"] = {
+            roof["compaction"] = {
                 "kernel": "evict_move_kernel", "layers_per_launch": 1 if args.evict_per_layer else L,
                 "avg_us": 1e3 * mov_k / mov_n,
                 "select_avg_us": 1e3 * (sel_ms - ov_ms * sel_n) / sel_n, "launches_timed": mov_n,
                 "algorithmic_bytes_per_launch": mb,
-                "rows_moved_per_unit_event": sum(st["n_rows_moved"]) / max(events, 1) / (S * Hkv),
+                "rows_moved_per_unit_event": rows / max(events, 1) / (S * Hkv),
                 "achieved": mb / (mov_k / mov_n * 1e-3) / 1e9,
                 "frac": mb / (mov_k / mov_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        # whole-step view: all algorithmic decode bytes of the run over the wall time
-        tot = sum(bytes_at(t) for t in range(1, K + 1)) * L
-        result["roofline"]["whole_run_frac"] = tot / elapsed / 1e9 / HBM_PEAK_GBS
+        # whole-step view: all algorithmic decode bytes of the timed steps over the wall time
+        tot = sum(bytes_at(t) for t in timed_steps) * L
+        roof["whole_run_frac"] = tot / elapsed / 1e9 / HBM_PEAK_GBS
+        result["roofline"] = roof
     if not args.no_cpu_baseline:
         eng.close()
         del q_all, k_all, v_all

@@ -171,7 +171,9 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * Errors: EINVAL, EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
-/* The same check for EVERY layer after decode step t (every layer must have taken step t).
+/* The same check (Sec. 4 "MRI-Centric Eviction"; Eq. 3; Eq. 6; the eviction branch of Alg. 1)
+ * for EVERY layer after decode step t (every layer must have taken step t).  The paper states
+ * Alg. 1 for one attention module; the modules of a model are independent of one another.
  * Where the layers stand at the same point, which is the normal course of a model, the
  * selection and the row move of all layers go in one launch each (the units of different
  * layers are independent); otherwise this is lazyev_evict layer by layer.  Results are those
@@ -179,8 +181,13 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /
  * layers differ).  Errors: those of lazyev_evict. */
 int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted /*host*/);
 
-/* Applies any tracking still pending, waits for the stream, then fills the non-null arrays of
- * *out.  Errors: EINVAL, EHIP, ENOMEM. */
+/* The bookkeeping of Alg. 1 as the host sees it: cache length per layer (the saw-tooth of
+ * Fig. 6: at most B + W entries, exactly B after an eviction, Sec. 4 / Eq. 6), evictions that
+ * fired, entries removed, activations (entries with A_t[i] >= alpha, first loop of Alg. 1) and
+ * rows the compaction moved.  Applies any tracking still pending, waits for the stream, then
+ * fills the non-null arrays of *out.  The TS / MRI / pos arrays themselves belong to the caller,
+ * who reads them directly after this call (there is no copy-out argument).
+ * Errors: EINVAL, EHIP, ENOMEM. */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
 
 /* Per-sequence timing, for a batch whose sequences do not start together (the paper decodes one
@@ -226,68 +233,21 @@ int lazyev_retire(lazyev_ctx *ctx, int32_t seq);
  * Errors: EINVAL (2 <= n_bins <= LAZYEV_MAX_HIST_BINS, layer range, null), EHIP, ENOMEM. */
 int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t *hist /*host*/);
 
+/* Observation window from such a histogram (Sec. 4 "Observation Window": W is set to the MRI
+ * below which 80 % of the tokens fall): over the entries that were re-activated at least once
+ * (MRI >= 1; an entry with MRI = 0 never recurred), the smallest W with at least `quantile` of
+ * them at MRI <= W.  *window = 0 if no entry was ever re-activated; an answer of n_bins - 1 means
+ * the histogram was too short.  Host arithmetic only, no GPU work.
+ * Errors: EINVAL (null, n_bins < 2, quantile outside (0, 1], a negative count). */
+int lazyev_window_from_histogram(const int64_t *hist /*host*/, int32_t n_bins, double quantile,
+                                 int32_t *window /*host*/);
+
 /* Score of Eq. 3 for n (t - TS, MRI) pairs, on the device, with the same code the eviction
  * uses; result as binary64.  For checking the scoring arithmetic in isolation.
  * Errors: EINVAL, EHIP. */
 int lazyev_score_pairs(const int32_t *delta_t /*device*/, const int32_t *mri /*device*/,
                        double *score /*device*/, int64_t n, int32_t score_flags,
                        void *stream);
-
-/* Tuning knobs for how a unit's cache is split over thread blocks.  Results do not depend on
- * them beyond floating-point summation order.
- *   lazyev_set_chunk: entries per block of the vector-ALU attention kernel (a power of two,
- *     64..256; default 128).
- *   lazyev_set_target_blocks: blocks per layer call the MFMA attention kernels aim for
- *     (default 512 = two per compute unit); each unit gets round(n_blocks / units) blocks,
- *     at least one (kernel 2: each owning at most 1024 entries; kernel 4: at most 64 blocks;
- *     until this is called, kernel 4 also uses fewer blocks for short caches: about 16
- *     sub-tiles of 16 entries per wave, but at least one block per compute unit).
- * Errors: EINVAL. */
-int lazyev_set_chunk(lazyev_ctx *ctx, int32_t chunk);
-int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
-
-/* Tuning knob: attention kernel.
- *   0  vector-ALU split kernel + merge kernel (any supported shape);
- *   2  MFMA split kernel + merge kernel (bf16, head_dim 128);
- *   3  one MFMA block per unit, no merge kernel and no workspace traffic (bf16, head_dim 128,
- *      group * capacity small enough for the logits of a unit to stay in LDS);
- *   4  one launch: MFMA stream blocks, the block that finishes a unit last merges the partials
- *      into the output; the tracking rides with the next launch (bf16, head_dim 128).  Over a
- *      cache of 1792 entries or more a block leaves only the logits of entries that can still
- *      reach alpha for the tracking; it leaves all of them over a shorter cache, when the
- *      caller passes p_out / p_override, with LAZYEV_SCORE_CURRENT_ATTENTION, with 8 query
- *      heads per KV head, or when a block owns more than 1280 entries;
- *   5  kernel 4 leaving every logit in all cases, 6 kernel 4 leaving only those of the entries
- *      that can reach alpha also over short caches (same results bit for bit; for comparison
- *      and tests);
- *   1  (default) picks 4 when it applies, else 0.
- * A kernel that does not apply to the shape falls back in the order 3 -> 2 -> 0, 4 -> 0.
- * Errors: EINVAL. */
-int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
-
-/* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels
- * (decode_step, or an evict that is due) record HIP events on the stream before, between and
- * after their two kernels.  lazyev_profile_read waits for the stream, adds up the elapsed
- * times of the armed calls since the last read and forgets them:
- *   index 0 attention kernel (the only one of kernels 3 and 4), 1 combine + tracking kernel,
- *         2 eviction score/select kernel, 3 eviction row-move kernel.
- * ms_total, launches: (host) arrays of 4.  Errors: EINVAL, EHIP. */
-int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls);
-int lazyev_profile_read(lazyev_ctx *ctx, double ms_total[4], int64_t launches[4]);
-
-/* Plain streaming kernels of known traffic, for the bandwidth a simple kernel reaches on the
- * same chip and for calibrating hardware byte counters.  lazyev_stream_probe copies `bytes`
- * (a multiple of 16) from src to dst; lazyev_stream_read_probe only reads src (sink: 4 bytes of
- * device memory that is practically never written).  n_blocks blocks of 256 threads, grid-stride.
- * All pointers are device memory.  Asynchronous on `stream`.  Errors: EINVAL, EHIP. */
-int lazyev_stream_probe(void *dst, const void *src, size_t bytes, int32_t n_blocks, void *stream);
-int lazyev_stream_read_probe(const void *src, size_t bytes, int32_t n_blocks, void *sink,
-                             void *stream);
-
-/* Average time, in milliseconds, between two HIP events recorded back to back on `stream`
- * with nothing between them: the fixed cost an event pair adds to the interval measured around
- * a kernel.  Waits for the stream.  ms_avg: (host).  Errors: EINVAL, EHIP. */
-int lazyev_event_overhead(int32_t n_pairs, void *stream, double *ms_avg);
 
 void lazyev_destroy(lazyev_ctx *ctx);              /* frees host memory only; NULL is allowed */
 const char *lazyev_strerror(int code);

@@ -43,12 +43,37 @@ class Stats(C.Structure):
                 ("n_rows_moved", C.POINTER(C.c_int64))]
 
 
-EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step", "lazyev_prefill_track", "lazyev_prefill_track_seq",
-           "lazyev_evict", "lazyev_evict_all", "lazyev_stats", "lazyev_admit", "lazyev_retire", "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_score_pairs", "lazyev_set_chunk",
-           "lazyev_profile_arm", "lazyev_profile_read", "lazyev_set_variant",
-           "lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_set_target_blocks",
-           "lazyev_event_overhead",
-           "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
+# what include/lazyev.h declares (the contract) ...
+EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
+           "lazyev_prefill_track", "lazyev_prefill_track_seq", "lazyev_evict", "lazyev_evict_all",
+           "lazyev_stats", "lazyev_admit", "lazyev_retire",
+           "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_window_from_histogram",
+           "lazyev_score_pairs", "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
+# ... and include/lazyev_bench.h (knobs and the per-kernel timer in the same library; the plain
+# streaming probes in liblazyev_bench.so, loaded by bench_lib() when somebody measures)
+BENCH_EXPORTS = ["lazyev_set_chunk", "lazyev_set_target_blocks", "lazyev_set_variant",
+                 "lazyev_profile_arm", "lazyev_profile_read"]
+BENCH_LIB_EXPORTS = ["lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_event_overhead"]
+_BENCH_LIB_PATH = os.path.join(os.path.dirname(_LIB_PATH), "liblazyev_bench.so")
+_bench_lib = None
+
+
+def bench_lib():
+    """liblazyev_bench.so (plain streaming probes, event-pair cost), loaded on first use."""
+    global _bench_lib
+    if _bench_lib is None:
+        if not os.path.exists(_BENCH_LIB_PATH):
+            raise ImportError("liblazyev_bench.so is not built: run `python -m paper_2506_15969_amd.build`")
+        b = C.CDLL(_BENCH_LIB_PATH)
+        b.lazyev_stream_probe.restype = C.c_int
+        b.lazyev_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+        b.lazyev_stream_read_probe.restype = C.c_int
+        b.lazyev_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+        b.lazyev_event_overhead.restype = C.c_int
+        b.lazyev_event_overhead.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+        _bench_lib = b
+    return _bench_lib
+
 
 lib.lazyev_capacity.restype = C.c_int32
 lib.lazyev_capacity.argtypes = [C.POINTER(Config)]
@@ -67,6 +92,8 @@ lib.lazyev_evict.restype = C.c_int
 lib.lazyev_evict.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_evict_all.restype = C.c_int
 lib.lazyev_evict_all.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+lib.lazyev_window_from_histogram.restype = C.c_int
+lib.lazyev_window_from_histogram.argtypes = [C.POINTER(C.c_int64), C.c_int32, C.c_double, C.POINTER(C.c_int32)]
 lib.lazyev_stats.restype = C.c_int
 lib.lazyev_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
 lib.lazyev_admit.restype = C.c_int
@@ -82,12 +109,6 @@ lib.lazyev_score_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64
                                    C.c_void_p]
 lib.lazyev_set_chunk.restype = C.c_int
 lib.lazyev_set_chunk.argtypes = [C.c_void_p, C.c_int32]
-lib.lazyev_stream_probe.restype = C.c_int
-lib.lazyev_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
-lib.lazyev_stream_read_probe.restype = C.c_int
-lib.lazyev_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
-lib.lazyev_event_overhead.restype = C.c_int
-lib.lazyev_event_overhead.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
 lib.lazyev_set_target_blocks.restype = C.c_int
 lib.lazyev_set_target_blocks.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_set_variant.restype = C.c_int
@@ -131,19 +152,12 @@ def score_pairs(delta_t: torch.Tensor, mri: torch.Tensor, score_flags: int = SCO
 
 
 def window_from_histogram(hist, quantile: float = 0.8) -> int:
-    """Observation window from an MRI histogram (Sec. 4, "Observation Window"): the smallest W
-    such that at least `quantile` of the re-activated entries (MRI >= 1) have MRI <= W.
-    Returns 0 if no entry was ever re-activated; an answer in the overflow bin means the
-    histogram was too short (raise n_bins)."""
-    total = sum(hist[1:])
-    if total == 0:
-        return 0
-    seen = 0
-    for m in range(1, len(hist)):
-        seen += hist[m]
-        if seen >= quantile * total:
-            return m
-    return len(hist) - 1
+    """lazyev_window_from_histogram on a sequence of counts (host only)."""
+    n = len(hist)
+    arr = (C.c_int64 * n)(*[int(x) for x in hist])
+    w = C.c_int32(0)
+    _check(lib.lazyev_window_from_histogram(arr, n, quantile, C.byref(w)), "lazyev_window_from_histogram")
+    return w.value
 
 
 class LazyEviction:

@@ -1,4 +1,5 @@
-"""Compiles the HIP sources into paper_2506_15969_amd/lib/liblazyev.so for gfx950.
+"""Compiles the HIP sources into paper_2506_15969_amd/lib/liblazyev.so (the decode path) and
+liblazyev_bench.so (plain streaming probes for measurements) for gfx950.
 
 hipcc cross-compiles without a GPU.  Run as `python -m paper_2506_15969_amd.build`.
 """
@@ -19,8 +20,11 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I" + INCLUDE,
           # packed-fp32 VALU forms are kept out of all device code
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the eviction file holds the bit-reproducible binary64 score: no fused multiply-add there
-SOURCES = {"decode_kernels.hip": [], "decode_unit.hip": [], "decode_fused.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=13"], "evict_kernels.hip": ["-ffp-contract=off"],
-           "lazyev_api.hip": [], "probe_kernels.hip": [], "prefill_kernels.hip": []}
+SOURCES = {"decode_kernels.hip": [], "decode_fused.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=13"], "evict_kernels.hip": ["-ffp-contract=off"],
+           "lazyev_api.hip": [], "prefill_kernels.hip": []}
+# measuring aids (plain streaming probes): a library of their own, not part of the path
+BENCH_LIB = os.path.join(LIBDIR, "liblazyev_bench.so")
+BENCH_SOURCES = {"probe_kernels.hip": []}
 
 
 def _compile(item):
@@ -35,14 +39,15 @@ def _compile(item):
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES.items()))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
-    if verbose:
-        print("built", LIB)
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + len(BENCH_SOURCES)) as ex:
+        objs = list(ex.map(_compile, list(SOURCES.items()) + list(BENCH_SOURCES.items())))
+    for lib, group in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", lib],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
+        if verbose:
+            print("built", lib)
     build_c_example(verbose)
     return LIB
 

@@ -88,11 +88,7 @@ int main(void) {
     HIP_OK(hipDeviceSynchronize());
     HIP_OK(hipMemcpy(out, out_d, sizeof(out), hipMemcpyDeviceToHost));
     printf("step %d evicted %d out", t, (int)n_evicted);
-    for (int h = 0; h < HQ; ++h) {
-      double sum = 0.0;
-      for (int l = 0; l < D; ++l) sum += (double)out[h * D + l] * (double)(l + 1);
-      printf(" %.9e", sum);
-    }
+    for (int i = 0; i < HQ * D; ++i) printf(" %.9e", (double)out[i]);   /* every element, [HQ][D] */
     printf("\n");
   }
 

@@ -395,231 +395,6 @@ __global__ __launch_bounds__(kBlock) void decode_combine_kernel(const DecodeArgs
   }
 }
 
-// ------------------------------------------------------------------------------ split, MFMA
-// bf16, head_dim 128.  The G query rows of a unit are padded to the 16 rows of an MFMA tile,
-// which takes the arithmetic off the vector ALU (the vector-ALU kernel above needs about 70
-// wave instructions per cached entry, more than the memory system leaves time for).
-//
-// v_mfma_f32_16x16x32_bf16 operand layout (lane l, c = l % 16, g = l / 16):
-//   A[row c][k = 8g..8g+7]   B[k = 8g..8g+7][col c]   C[row 4g+i][col c], i = 0..3
-//
-// logits   S^T[entry][head] = K[entry][d] * Q^T[d][head]: A = 16 entries x 32 d of K (one
-//          16-byte load per lane), B = Q^T.  A lane ends up with head c and, per 32-entry
-//          tile, the 8 entries {16*st + 4g + i}.
-// output   O[head][d] = P[head][entry] * V[entry][d]: A = P, which is exactly what the lane
-//          already holds (head c, its 8 entries, rounded to bf16); B = V for those same 8
-//          entries and one column per lane, built from eight 16-byte row loads by an in-lane
-//          8x8 transpose (v_perm_b32).  Instruction e produces columns d = 8c + e.
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
-
-// A block owns 4 * N_IT consecutive 32-entry tiles of one unit; its four waves take them
-// round-robin.  Two software-pipelined passes keep row loads in flight while the previous tile
-// is being multiplied: K tiles -> logits (kept in registers), block-wide max, then V tiles ->
-// exp, p_tilde store, output product.  The loops contain no branches: tiles past the end of
-// the cache are clamped to the last row (their logits are masked to -inf), so the hardware
-// load counter the compiler waits on is exact and the next tile's loads really stay in flight.
-template <int N_IT>
-__global__ __launch_bounds__(kBlock) void decode_split_mfma_kernel(const DecodeArgs a) {
-  constexpr int D = 128, KC = D / 32, EV = 8;
-  __shared__ float red_lds[kWaves][16];
-  __shared__ float acc_lds[kWaves][8 * D];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = lane & 15, g = lane >> 4;
-  const int unit = blockIdx.y, split = blockIdx.x;
-  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
-  const int G = a.group;
-  const int n_old = a.n_old, n1 = a.n_old + 1;
-  const int tile0 = split * (4 * N_IT) + wave;          // this wave's tiles: tile0 + 4 * it
-
-  const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache) + static_cast<size_t>(unit) * a.capacity * D;
-  const bf16_t *vc = static_cast<const bf16_t *>(a.v_cache) + static_cast<size_t>(unit) * a.capacity * D;
-  const bf16_t *k_new = static_cast<const bf16_t *>(a.k_new) + static_cast<size_t>(unit) * D;
-  const bf16_t *v_new = static_cast<const bf16_t *>(a.v_new) + static_cast<size_t>(unit) * D;
-
-  // B operand of the logits: Q^T, head c (zero rows beyond the group)
-  u32x4_t qb[KC];
-  {
-    const bf16_t *q = static_cast<const bf16_t *>(a.q) +
-                      (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G) * D +
-                      min(c, G - 1) * D + g * 8;
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      const u32x4_t v = *reinterpret_cast<const u32x4_t *>(q + kk * 32);
-      qb[kk] = c < G ? v : u32x4_t{0, 0, 0, 0};
-    }
-  }
-
-  auto load_k = [&](u32x4_t (&dst)[2][KC], int tile) {
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      const int row = min(tile * 32 + st * 16 + c, n_old);
-      const bf16_t *src = (row == n_old) ? k_new : kc + static_cast<size_t>(row) * D;
-#pragma unroll
-      for (int kk = 0; kk < KC; ++kk)
-        dst[st][kk] = *reinterpret_cast<const u32x4_t *>(src + kk * 32 + g * 8);
-    }
-  };
-  auto load_v = [&](u32x4_t (&dst)[EV], int tile) {
-#pragma unroll
-    for (int jp = 0; jp < EV; ++jp) {
-      const int row = min(tile * 32 + (jp >> 2) * 16 + 4 * g + (jp & 3), n_old);
-      const bf16_t *src = (row == n_old) ? v_new : vc + static_cast<size_t>(row) * D;
-      dst[jp] = *reinterpret_cast<const u32x4_t *>(src + c * 8);
-    }
-  };
-
-  // ---- pass 1: logits of head c for this lane's entries {32*tile + 16*st + 4g + i}
-  float sv[N_IT][2][4];
-  float mx = -INFINITY;
-  u32x4_t vbuf[2][EV];
-  {
-    u32x4_t kbuf[2][2][KC];
-    load_k(kbuf[0], tile0);
-#pragma unroll
-    for (int it = 0; it < N_IT; ++it) {
-      const int tile = tile0 + 4 * it;
-      if (it + 1 < N_IT) load_k(kbuf[(it + 1) & 1], tile + 4);
-      else load_v(vbuf[0], tile0);                      // first V tile rides behind the last K tile
-      __builtin_amdgcn_sched_barrier(0);                // issue the loads before this tile's math
-#pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < KC; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8_t, kbuf[it & 1][st][kk]),
-              __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int tok = tile * 32 + st * 16 + 4 * g + i;
-          const float v = tok < n1 ? acc[i] * a.scale : -INFINITY;
-          sv[it][st][i] = v;
-          mx = fmaxf(mx, v);
-        }
-      }
-    }
-  }
-
-  // ---- block-wide max per head (every block holds at least one real entry)
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  if (g == 0) red_lds[wave][c] = mx;
-  lds_barrier();
-  float m_loc = red_lds[0][c];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) m_loc = fmaxf(m_loc, red_lds[w][c]);
-  lds_barrier();
-
-  // ---- pass 2
-  float lsum = 0.f;
-  f32x4_t o[EV];
-#pragma unroll
-  for (int e = 0; e < EV; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float *p_tilde = a.ws.p_tilde +
-                   (static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G + min(c, G - 1)) * a.p_stride;
-#pragma unroll
-  for (int it = 0; it < N_IT; ++it) {
-    const int tile = tile0 + 4 * it;
-    if (it + 1 < N_IT) load_v(vbuf[(it + 1) & 1], tile + 4);
-    __builtin_amdgcn_sched_barrier(0);
-    // exp(s - local max): fp32 for the tracking, rounded to bf16 for the output product
-    bf16x8_t pa;
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      const int tokb = tile * 32 + st * 16 + 4 * g;
-      float e[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        e[i] = __expf(sv[it][st][i] - m_loc);
-        lsum += e[i];
-        pa[st * 4 + i] = static_cast<__bf16>(e[i]);
-      }
-      if (c < G) {
-        if (tokb + 4 <= n1) {
-          *reinterpret_cast<float4 *>(p_tilde + tokb) = make_float4(e[0], e[1], e[2], e[3]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (tokb + i < n1) p_tilde[tokb + i] = e[i];
-        }
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < EV; ++e) {
-      u32x4_t vb;
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        vb[w] = __builtin_amdgcn_perm(vbuf[it & 1][2 * w + 1][e >> 1], vbuf[it & 1][2 * w][e >> 1],
-                                      (e & 1) ? 0x07060302u : 0x05040100u);
-      o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8_t, vb), o[e], 0, 0, 0);
-    }
-  }
-  lsum += __shfl_xor(lsum, 16);
-  lsum += __shfl_xor(lsum, 32);
-  if (g == 0) red_lds[wave][c] = lsum;
-
-  // o[e][i] = O[head 4g+i][d = 8c+e]: add up the four waves, store the block's partial
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int head = 4 * g + i;
-    if (head < G) {
-      float *dst = &acc_lds[wave][head * D + 8 * c];
-      *reinterpret_cast<float4 *>(dst) = make_float4(o[0][i], o[1][i], o[2][i], o[3][i]);
-      *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][i], o[5][i], o[6][i], o[7][i]);
-    }
-  }
-  lds_barrier();
-  const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
-  float *pacc = a.ws.part_acc + part * (G * D);
-  for (int i = tid; i < G * D; i += kBlock) {
-    float v = acc_lds[0][i];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) v += acc_lds[w][i];
-    pacc[i] = v;
-  }
-  if (tid < G) {                               // wave 0, g == 0, c == tid: this lane's head
-    float l_loc = red_lds[0][tid];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) l_loc += red_lds[w][tid];
-    float *ml = a.ws.part_ml + part * (2 * G);
-    ml[tid] = m_loc;
-    ml[G + tid] = l_loc;
-  }
-
-  // the block that owns slot N stores the appended row (everybody read it from k_new / v_new)
-  if (n_old / (128 * N_IT) == split) {
-    if (tid < 16) {
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(kc) + static_cast<size_t>(n_old) * D)[tid] =
-          reinterpret_cast<const uint4 *>(k_new)[tid];
-    } else if (tid >= 64 && tid < 80) {
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[tid - 64] =
-          reinterpret_cast<const uint4 *>(v_new)[tid - 64];
-    }
-  }
-}
-
-template <int N_IT>
-hipError_t launch_mfma(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
-  const int units = a.batch * a.n_kv_heads;
-  dim3 grid_s(a.n_split, units);
-  if (ev) (void)hipEventRecord(ev[0], stream);
-  hipLaunchKernelGGL((decode_split_mfma_kernel<N_IT>), grid_s, dim3(kBlock), 0, stream, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (ev) (void)hipEventRecord(ev[1], stream);
-  int n_slice = (a.n_old + 1 + kBlock - 1) / kBlock;
-  if (n_slice > kSliceMax) n_slice = kSliceMax;
-  dim3 grid_c(n_slice, units);
-  hipLaunchKernelGGL((decode_combine_kernel<bf16_t, 128>), grid_c, dim3(kBlock),
-                     2 * a.n_split * a.group * sizeof(float), stream, a);
-  e = hipGetLastError();
-  if (ev) (void)hipEventRecord(ev[2], stream);
-  return e;
-}
-
 template <typename T, int D, int G>
 hipError_t launch_typed(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
@@ -663,26 +438,9 @@ int decode_slice_max() { return kSliceMax; }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   if (a.variant == 4 || a.variant == 6) return launch_decode_fused(a, stream, ev);
-  if (a.variant == 3) return launch_decode_unit(a, stream, ev);
-  const bool mfma = a.variant == 2 && a.dtype == 1 && a.head_dim == 128;
-  if (a.chunk <= 0 || (!mfma && a.chunk > kChunkMax) || a.n_split > kSplitMaxLds ||
+  if (a.chunk <= 0 || a.chunk > kChunkMax || a.n_split > kSplitMaxLds ||
       a.n_split > a.n_split_max || static_cast<long long>(a.n_split) * a.chunk < a.n_old + 1)
     return hipErrorInvalidValue;
-  if (mfma) {
-    // chunk = 128 * N_IT entries per block
-    if (a.chunk % 128 != 0) return hipErrorInvalidValue;
-    switch (a.chunk / 128) {
-      case 1: return launch_mfma<1>(a, stream, ev);
-      case 2: return launch_mfma<2>(a, stream, ev);
-      case 3: return launch_mfma<3>(a, stream, ev);
-      case 4: return launch_mfma<4>(a, stream, ev);
-      case 5: return launch_mfma<5>(a, stream, ev);
-      case 6: return launch_mfma<6>(a, stream, ev);
-      case 7: return launch_mfma<7>(a, stream, ev);
-      case 8: return launch_mfma<8>(a, stream, ev);
-      default: return hipErrorInvalidValue;
-    }
-  }
   if (a.dtype == 0) {
     if (a.head_dim == 64) return launch_group<float, 64>(a, stream, ev);
     if (a.head_dim == 128) return launch_group<float, 128>(a, stream, ev);

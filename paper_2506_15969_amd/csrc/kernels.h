@@ -75,11 +75,8 @@ struct DecodeArgs {
   int32_t chunk, n_split; // entries per split block, number of split blocks per unit
   int32_t n_split_max;    // stride of the partial arrays
   int32_t p_stride;       // row stride of p_tilde (C rounded up to a multiple of 4)
-  int32_t lds_stride;     // unit kernel: row stride of the logits in LDS
-  int32_t lds_stage_offset;  // unit kernel: byte offset of the K staging areas in dynamic LDS
   int32_t variant;        // attention kernel actually launched: 0 vector ALU + merge,
-                          // 2 MFMA split + merge, 3 one MFMA block per unit, 4 fused MFMA,
-                          // 6 fused MFMA leaving candidate lists (see TrackArgs)
+                          // 4 fused MFMA, 6 fused MFMA leaving candidate lists (see TrackArgs)
   float   alpha, scale;
   int32_t dtype;
   const void *q, *k_new, *v_new;
@@ -151,8 +148,6 @@ hipError_t launch_prefill_track(const PrefillArgs &a, hipStream_t stream);
 // `ev`, when not null, points at three events recorded before the first kernel, between the two
 // kernels and after the second (per-kernel timing for the profiling aid).
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
-// One block per unit, no workspace traffic (bf16, head_dim 128, logits of a unit fit in LDS).
-hipError_t launch_decode_unit(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 // One launch per call: split blocks, the last block of a unit merges and tracks (bf16, d 128).
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 int decode_fused_split_max();
@@ -161,9 +156,6 @@ int decode_fused_split_max();
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group);
 int decode_fused_head_pad();
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
-hipError_t decode_unit_prepare();
-size_t decode_unit_lds_bytes(int group, int lds_stride);
-size_t decode_unit_stage_offset(int group, int lds_stride);
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 int evict_lds_candidates();   // candidates per unit whose keys the selection keeps in LDS
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,

@@ -2,6 +2,7 @@
 // each layer's cache length (it evolves deterministically: +1 per decode step, back to B at an
 // eviction, so no device read-back is ever needed), workspace carve-up and kernel launches.
 #include "lazyev.h"
+#include "lazyev_bench.h"
 
 #include <cmath>
 #include <cstring>
@@ -54,7 +55,7 @@ struct lazyev_ctx {
 namespace {
 
 constexpr int kMinChunk = 64;
-constexpr int kTile = 32;            // entries per MFMA tile; finest split granularity
+constexpr int kTile = 32;            // finest split granularity the partial arrays are sized for
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -291,11 +292,6 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->slots_on = false;
   ctx->last_hip_error = 0;
   ctx->prof_armed = 0;
-  if (cfg->dtype == LAZYEV_DTYPE_BF16 && cfg->head_dim == 128 &&
-      lazyev::decode_unit_prepare() != hipSuccess) {
-    delete ctx;
-    return LAZYEV_EHIP;
-  }
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
 
   // activation counters, moved-row counters and tickets lie next to each other
@@ -325,7 +321,7 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
 }
 
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant) {
-  if (!ctx || variant < 0 || variant > 6) return LAZYEV_EINVAL;
+  if (!ctx || variant < 0 || variant > 6 || variant == 2 || variant == 3) return LAZYEV_EINVAL;
   ctx->variant = variant;
   return LAZYEV_OK;
 }
@@ -364,19 +360,11 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.n_old = n_old; a.t = t; a.prompt_len = c.prompt_len;
   // which attention kernel: see lazyev_set_variant
   const bool mfma_shape = c.dtype == LAZYEV_DTYPE_BF16 && c.head_dim == 128;
-  const int lds_stride = (ctx->capacity + 31) / 32 * 32 + 8;
-  const bool unit_fits = mfma_shape && lazyev::decode_unit_lds_bytes(ctx->group, lds_stride) <= 150 * 1024;
-  int kind = 0;
+  // (5 and 6 are 4 with the logits always / never written in full)
+  const int kind = (mfma_shape && ctx->variant != 0) ? 4 : 0;
   bool compact = false;
-  if (mfma_shape && ctx->variant != 0) {
-    kind = 4;                                      // (5 and 6 are 4 with the logits always / never written in full)
-    if (ctx->variant == 2) kind = 2;
-    if (ctx->variant == 3) kind = unit_fits ? 3 : 2;
-  }
   if (ctx->slots_on && kind != 4) return LAZYEV_EINVAL;   // only the single-launch kernel knows slots
   a.slots = slots_of(ctx);
-  a.lds_stride = lds_stride;
-  a.lds_stage_offset = static_cast<int32_t>(lazyev::decode_unit_stage_offset(ctx->group, lds_stride));
   if (kind == 4) {
     // fused kernel: n_split blocks of four waves per unit, every wave a run of 16-entry sub-tiles
     const int n_sub = (n_old + 1 + 15) / 16;
@@ -412,19 +400,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
               !(c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) &&
               lazyev::decode_fused_compact_fits(n_old, n_split, a.p_stride, ctx->group);
   }
-  if (kind == 4) {
-    // set up above
-  } else if (kind == 2) {
-    // MFMA split kernel: a block owns 4 * n_it tiles of 32 entries (n_it = 1..8 per wave)
-    const int n_tiles = (n_old + 1 + kTile - 1) / kTile;
-    int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
-    if (n_split < 1) n_split = 1;
-    int n_it = (n_tiles + 4 * n_split - 1) / (4 * n_split);
-    while (n_it < 8 && (n_tiles + 4 * n_it - 1) / (4 * n_it) > lazyev::decode_split_max()) ++n_it;
-    if (n_it > 8) n_it = 8;
-    a.chunk = 4 * n_it * kTile;
-    a.n_split = (n_tiles + 4 * n_it - 1) / (4 * n_it);
-  } else {
+  if (kind != 4) {
     a.chunk = ctx->chunk;
     a.n_split = (n_old + 1 + ctx->chunk - 1) / ctx->chunk;
   }
@@ -537,7 +513,9 @@ int lazyev_prefill_track_seq(lazyev_ctx *ctx, int32_t layer, int32_t seq, const 
   return LAZYEV_OK;
 }
 
-int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) {
+// The eviction check of one layer.  `gather`: where the units' gather lists go (null: the
+// workspace's area).
+static int evict_layer(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted, int32_t *gather) {
   if (n_evicted) *n_evicted = 0;
   if (!ctx) return LAZYEV_EINVAL;
   const lazyev_config &c = ctx->cfg;
@@ -566,6 +544,7 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   a.mri = c.mri + static_cast<size_t>(layer) * slab;
   a.pos = c.pos + static_cast<size_t>(layer) * slab;
   a.ws = ctx->ws;
+  if (gather) a.ws.src_index = gather;
   a.rows_moved = ctx->ws.rows_moved + static_cast<size_t>(layer) * ctx->units;
   a.n_kv_heads = c.n_kv_heads;
   a.slots = slots_of(ctx);
@@ -594,6 +573,10 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   }
   ctx->last_layer = -1;                            // the stored logits no longer match the slots
   return LAZYEV_OK;
+}
+
+int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) {
+  return evict_layer(ctx, layer, t, n_evicted, nullptr);
 }
 
 int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted) {
@@ -742,6 +725,27 @@ int lazyev_mri_histogram(lazyev_ctx *ctx, int32_t layer, int32_t n_bins, int64_t
   if (e == hipSuccess)
     e = hipMemcpy(hist, ctx->ws.hist, n_bins * sizeof(unsigned long long), hipMemcpyDeviceToHost);
   return e == hipSuccess ? LAZYEV_OK : fail_hip(ctx, e);
+}
+
+int lazyev_window_from_histogram(const int64_t *hist, int32_t n_bins, double quantile, int32_t *window) {
+  if (!hist || !window || n_bins < 2 || !(quantile > 0.0) || !(quantile <= 1.0)) return LAZYEV_EINVAL;
+  // entries that recurred at least once (bin 0 = never re-activated)
+  int64_t total = 0;
+  for (int32_t m = 1; m < n_bins; ++m) {
+    if (hist[m] < 0) return LAZYEV_EINVAL;
+    total += hist[m];
+  }
+  *window = 0;
+  if (total == 0) return LAZYEV_OK;
+  // the ceil(quantile * total)-th smallest MRI (inverted-CDF quantile), in binary64
+  const double need = std::ceil(quantile * static_cast<double>(total));
+  int64_t seen = 0;
+  for (int32_t m = 1; m < n_bins; ++m) {
+    seen += hist[m];
+    if (static_cast<double>(seen) >= need) { *window = m; return LAZYEV_OK; }
+  }
+  *window = n_bins - 1;
+  return LAZYEV_OK;
 }
 
 // Common part of lazyev_admit and lazyev_retire.

@@ -1,7 +1,7 @@
 // Plain streaming kernels of known traffic: the denominators the decode path is compared with
 // (what a simple read or copy achieves on the same chip) and the calibration of hardware byte
-// counters.  Not on the decode path.
-#include "lazyev.h"
+// counters.  Not on the decode path: built into a library of its own (liblazyev_bench.so).
+#include "lazyev_bench.h"
 
 #include <hip/hip_runtime.h>
 

@@ -32,7 +32,7 @@ def make_engine(binding, cfg: WorkloadConfig, wl: Workload, layers=None, score_f
 
 def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", score_flags=3,
                  chunk=None, variant=None, target_blocks=None, gen_block=32,
-                 check_rows_every=1, log=None):
+                 check_rows_every=1, log=None, watch=()):
     """Runs `steps` decode steps (default: all) of the layers that `units` touch, full batch on
     the GPU, the listed (layer, seq, kv_head) units in the oracle.
 
@@ -41,6 +41,8 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
     mode "oracle_p":  the oracle's weights, rounded to fp32, are thresholded by both.
     mode "synthetic": seeded random weights are thresholded by both.
     mode "gpu_p":     the library's exported weights are thresholded (and ranked) by the oracle.
+    watch: token positions whose eviction is recorded in stat["evicted_watch"][unit] as
+    (pos, step, TS, MRI at that eviction).
     Returns a dict of counters.  Raises AssertionError on any mismatch.
     """
     wl = Workload(cfg)
@@ -59,7 +61,8 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
     p_out = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
     p_in = torch.zeros((cfg.batch, cfg.n_q_heads, C), dtype=torch.float32, device=dev)
     stat = dict(steps=0, decisions=0, near_threshold=0, evictions=0, max_out_err=0.0,
-                max_p_err=0.0, activations=0, rows_moved=0)
+                max_p_err=0.0, activations=0, rows_moved=0, evicted_watch={u: [] for u in units})
+    watch = set(int(x) for x in watch)
     rng = np.random.default_rng(cfg.seed + 12345)
     alpha32 = np.float32(cfg.alpha)
 
@@ -164,7 +167,11 @@ def run_lockstep(binding, cfg: WorkloadConfig, units, steps=None, mode="e2e", sc
                 # lagged eviction
                 n_ev = eng.evict(l, t)
                 before = {u: orc[u].pos.copy() for u in mine}
+                held = {u: {int(p): (int(a), int(b)) for p, a, b in zip(orc[u].pos, orc[u].TS, orc[u].MRI)
+                            if int(p) in watch} for u in mine} if watch else {}
                 gone = {u: orc[u].evict(t) for u in mine}
+                for u in (mine if watch else ()):
+                    stat["evicted_watch"][u] += [(int(p), t) + held[u][int(p)] for p in gone[u] if int(p) in watch]
                 for u in mine:                       # survivors that changed slot (order is kept)
                     stat["rows_moved"] += int((orc[u].pos != before[u][:len(orc[u])]).sum()) if gone[u] else 0
                 for u in mine:
@@ -215,3 +222,118 @@ def _compare_state(eng, l, mine, orc, t, rows):
             vg = eng.v_cache[l, s, h, :n].double().cpu().numpy()
             assert np.array_equal(kg, orc[u].K), ("K rows", u, t)
             assert np.array_equal(vg, orc[u].V), ("V rows", u, t)
+
+
+def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32,
+                   check_rows_every=1, variant=None, log=None):
+    """The path the benchmark times, next to the oracle: lazyev_decode_step WITHOUT p_out /
+    p_override for every layer of every step (so the tracking of a call is applied by the
+    tracking blocks that ride with the next launch, from all logits or, over a long cache, from
+    the candidate lists) and lazyev_evict_all after every step at which an eviction is due.
+
+    The oracle follows the listed (layer, seq, kv_head) units on its own fp64 weights.  What the
+    library decided at a call is read from TS after the NEXT call has been enqueued (an entry
+    older than the call's appended one has TS == t exactly if the call activated it); before a
+    due eviction lazyev_stats applies the last call's tracking, which is what lazyev_evict_all
+    would do first anyway.  A differing decision is accepted only within tol * alpha of the
+    threshold (counted, adopted); TS / MRI are compared after every call, survivor sets, TS,
+    MRI, pos (and rows) after every eviction, outputs at every call.
+    """
+    wl = Workload(cfg)
+    tol = TOL[cfg.dtype]
+    G, d = cfg.group, cfg.head_dim
+    L = cfg.n_layers
+    steps = cfg.steps if steps is None else steps
+    eng = make_engine(binding, cfg, wl, None, 3, None, variant, None)
+    dev = eng.device
+    by_layer = {l: [u for u in units if u[0] == l] for l in range(L)}
+    orc = {}
+    for (l, s, h) in units:
+        k, v = wl.prompt_kv(l, seq=[s], kv_head=[h])
+        orc[(l, s, h)] = OracleUnit(k[0, 0].double().numpy(), v[0, 0].double().numpy(), G,
+                                    cfg.budget, cfg.window, cfg.alpha)
+    out = torch.empty((2, L, cfg.batch, cfg.n_q_heads, d), dtype=cfg.torch_dtype, device=dev)
+    stat = dict(steps=0, calls_checked=0, decisions=0, near_threshold=0, evictions=0,
+                max_out_err=0.0, compact_calls=0)
+    n_len = cfg.prompt_len                      # entries per unit before the next append
+
+    def resolve(call):
+        """Oracle step for a finished call whose tracking the library has applied."""
+        l, t, n1, cpu_rows = call
+        mine = by_layer[l]
+        if not mine:
+            return
+        ss = torch.tensor([u[1] for u in mine], device=dev)
+        hh = torch.tensor([u[2] for u in mine], device=dev)
+        ts_g = eng.ts[l][ss, hh, :n1].cpu().numpy()
+        mri_g = eng.mri[l][ss, hh, :n1].cpu().numpy()
+        o_gpu = out[t % 2, l].float().cpu().numpy().astype(np.float64)
+        for k_u, u in enumerate(mine):
+            _, s, h = u
+            rows = slice(h * G, (h + 1) * G)
+
+            def adopt(p, act, k_u=k_u):
+                act_gpu = act.copy()
+                act_gpu[:n1 - 1] = ts_g[k_u, :n1 - 1] == t      # (the appended entry's own flag is not visible)
+                diff = np.nonzero(act != act_gpu)[0]
+                for j in diff:
+                    near = np.abs(p[:, j] - cfg.alpha) <= tol * cfg.alpha
+                    assert near.any(), ("decision differs away from the threshold", u, t, j,
+                                        p[:, j], cfg.alpha)
+                stat["near_threshold"] += len(diff)
+                return act_gpu
+            cq, ck, cv = cpu_rows[u]
+            o, p, act = orc[u].decode_step(t, cq, ck, cv, act_override=adopt)
+            _compare_out(o_gpu[s, rows], o, tol, stat, (u, t))
+            assert np.array_equal(ts_g[k_u], orc[u].TS), ("TS", u, t)
+            assert np.array_equal(mri_g[k_u], orc[u].MRI), ("MRI", u, t)
+            stat["decisions"] += n1
+        stat["calls_checked"] += 1
+
+    pending = None
+    for t0 in range(1, steps + 1, gen_block):
+        t1 = min(steps + 1, t0 + gen_block)
+        gpu_in = [wl.step_inputs(l, t0, t1, device="cuda") for l in range(L)]
+        cpu_in = {u: wl.step_inputs(u[0], t0, t1, seq=[u[1]], kv_head=[u[2]]) for u in units}
+        cpu_in = {u: tuple(x.double().numpy() for x in v) for u, v in cpu_in.items()}
+        for t in range(t0, t1):
+            i = t - t0
+            n1 = n_len + 1
+            for l in range(L):
+                q, kn, vn = (x[i] for x in gpu_in[l])
+                eng.decode_step(l, t, q, kn, vn, out[t % 2, l])
+                if n1 >= 1792 and G < 8:
+                    stat["compact_calls"] += 1
+                if pending is not None:
+                    resolve(pending)
+                pending = (l, t, n1, {u: (cpu_in[u][0][i, 0], cpu_in[u][1][i, 0, 0], cpu_in[u][2][i, 0, 0])
+                                      for u in by_layer[l]})
+            n_len = n1
+            if t % cfg.window == 0 and n_len > cfg.budget:
+                eng.stats()                          # the last call's tracking, as lazyev_evict_all applies it
+                resolve(pending)
+                pending = None
+                n_ev = eng.evict_all(t)
+                assert n_ev == n_len - cfg.budget, (t, n_ev)
+                for u in units:
+                    assert len(orc[u].evict(t)) == n_ev, ("eviction count", u, t)
+                stat["evictions"] += 1
+                for l in range(L):
+                    if by_layer[l]:
+                        _compare_state(eng, l, by_layer[l], orc, t,
+                                       rows=(stat["evictions"] % check_rows_every == 0))
+                n_len = cfg.budget
+            stat["steps"] += 1
+        if log:
+            log("t=%d %s" % (t1 - 1, stat))
+    st = eng.stats()
+    if pending is not None:
+        resolve(pending)
+    for l in range(L):
+        assert st["last_step"][l] == steps and st["len"][l] == n_len
+        if by_layer[l]:
+            _compare_state(eng, l, by_layer[l], orc, steps, rows=True)
+    stat["gpu_stats"] = st
+    stat["oracle_units"] = orc
+    eng.close()
+    return stat

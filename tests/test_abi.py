@@ -15,12 +15,27 @@ def _good(b):
                     score_flags=3)
 
 
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)           # declarations, not prose
+    return set(re.findall(r"\b(lazyev_[a-z_]+)\s*\(", header))
+
+
 def test_every_declared_symbol_is_exported(lazyev_lib):
-    header = open(os.path.join(ROOT, "include", "lazyev.h")).read()
-    declared = set(re.findall(r"\b(lazyev_[a-z_]+)\s*\(", header))
+    """include/lazyev.h is the contract of the path; include/lazyev_bench.h holds the knobs and
+    the per-kernel timer (same library) and the streaming probes (liblazyev_bench.so)."""
+    declared = _declared("lazyev.h")
     assert declared == set(lazyev_lib.EXPORTS)
     for name in declared:
         assert hasattr(lazyev_lib.lib, name)
+    bench = _declared("lazyev_bench.h")
+    assert bench == set(lazyev_lib.BENCH_EXPORTS) | set(lazyev_lib.BENCH_LIB_EXPORTS)
+    for name in lazyev_lib.BENCH_EXPORTS:
+        assert hasattr(lazyev_lib.lib, name)
+    probes = lazyev_lib.bench_lib()
+    for name in lazyev_lib.BENCH_LIB_EXPORTS:
+        assert hasattr(probes, name)
+        assert not hasattr(lazyev_lib.lib, name), "the path's library holds no measuring kernels"
 
 
 def test_struct_layout_matches_header(lazyev_lib):
@@ -72,7 +87,7 @@ def test_null_context_calls(lazyev_lib):
     assert b.lib.lazyev_evict(None, 0, 1, None) == b.EINVAL
     assert b.lib.lazyev_evict_all(None, 1, None) == b.EINVAL
     assert b.lib.lazyev_stats(None, None) == b.EINVAL
-    assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL
+    assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL and b.lib.lazyev_set_variant(None, 4) == b.EINVAL
     assert b.lib.lazyev_prefill_track(None, 0, 1, None, None) == b.EINVAL
     assert b.lib.lazyev_prefill_track_seq(None, 0, 0, 1, None, None) == b.EINVAL
     assert b.lib.lazyev_admit(None, 0, 1, 0) == b.EINVAL and b.lib.lazyev_retire(None, 0) == b.EINVAL
@@ -95,6 +110,14 @@ def test_window_from_histogram_is_the_quantile(lazyev_lib):
             assert lazyev_lib.window_from_histogram(hist, q) == window_from_mri(mri, q)
     assert lazyev_lib.window_from_histogram([5, 0, 0, 0]) == 0
     assert lazyev_lib.window_from_histogram([0, 0, 3, 1], 0.8) == 3
+    assert lazyev_lib.window_from_histogram([0, 4, 1], 0.8) == 1          # 4 of 5 is exactly 80 %
+    w = C.c_int32(-7)
+    f = lazyev_lib.lib.lazyev_window_from_histogram
+    one = (C.c_int64 * 3)(1, 2, 3)
+    assert f(None, 3, 0.8, C.byref(w)) == lazyev_lib.EINVAL and f(one, 3, 0.8, None) == lazyev_lib.EINVAL
+    assert f(one, 1, 0.8, C.byref(w)) == lazyev_lib.EINVAL and f(one, 3, 0.0, C.byref(w)) == lazyev_lib.EINVAL
+    assert f(one, 3, 1.5, C.byref(w)) == lazyev_lib.EINVAL
+    assert f((C.c_int64 * 3)(1, -2, 3), 3, 0.8, C.byref(w)) == lazyev_lib.EINVAL
     assert lazyev_lib.lib.lazyev_mri_histogram(None, 0, 16, None) == lazyev_lib.EINVAL
 
 

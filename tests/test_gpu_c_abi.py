@@ -33,20 +33,23 @@ def test_plain_c_program_against_the_oracle():
     assert lines[-1] == "ok"
     G = HQ // HKV
     units = [OracleUnit(_rows(1, range(P), h), _rows(2, range(P), h), G, B, W, ALPHA) for h in range(HKV)]
-    weights = np.arange(1, D + 1, dtype=np.float64)
     for t in range(1, STEPS + 1):
         f = lines[t - 1].split()
         assert f[0] == "step" and int(f[1]) == t and f[2] == "evicted" and f[4] == "out"
-        got = np.array([float(x) for x in f[5:5 + HQ]])
+        got = np.array([float(x) for x in f[5:]]).reshape(HQ, D)          # every output element
         want, gone = [], []
         for h, u in enumerate(units):
             q = np.array([[_value(3, t, h * G + g, l) for l in range(D)] for g in range(G)])
             o, _, _ = u.decode_step(t, q, _rows(1, [P + t - 1], h)[0], _rows(2, [P + t - 1], h)[0])
-            want += [float(o[g] @ weights) for g in range(G)]
+            want.append(o)
             gone.append(len(u.evict(t)))
         assert int(f[3]) == gone[0] == gone[1]
-        scale = np.abs(want).max() + 1.0
-        assert np.all(np.abs(got - np.array(want)) <= 2e-4 * scale), (t, got, want)
+        want = np.concatenate(want)                                        # [HQ, D] fp64
+        # element by element, and the fp32 tolerance of the output rows (1e-5 relative L2)
+        assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want).max(axis=1, keepdims=True)), \
+            (t, "\n", got, "\n", want)
+        err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
+        assert err.max() <= 1e-5, (t, err)
     f = lines[STEPS].split()
     assert f == ["len", str(len(units[0])), "last_step", str(STEPS), "evict_events",
                  str(units[0].n_evict_events)]

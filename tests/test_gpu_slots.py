@@ -148,7 +148,7 @@ def test_slot_calls_reject_what_they_cannot_do(lazyev_lib):
     with pytest.raises(b.LazyevError):                    # its first step would lie in the past
         eng.admit(0, 10, 0)
     eng.admit(0, 10, 1)
-    eng.set_variant(2)                                    # the other kernels know no slots
+    eng.set_variant(0)                                    # the other kernel knows no slots
     with pytest.raises(b.LazyevError):
         eng.decode_step(0, 2, q, kv, kv, out)
     fp32 = b.LazyEviction(1, 2, 4, 4, 64, 32, 4, 8, 0.1, dtype=torch.float32).init()
