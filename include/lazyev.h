@@ -37,6 +37,7 @@ extern "C" {
 #define LAZYEV_EWORKSPACE -3   /* workspace missing or smaller than lazyev_workspace_size        */
 #define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
 #define LAZYEV_ENOMEM     -5   /* host memory for the context or a read-back buffer ran out      */
+#define LAZYEV_ESCRATCH   -6   /* lazyev_evict_static: the shape exceeds the library's static scratch */
 
 #define LAZYEV_DTYPE_FP32  0
 #define LAZYEV_DTYPE_BF16  1
@@ -170,6 +171,26 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t,
  * t must equal the layer's last decode step.
  * Errors: EINVAL, EHIP. */
 int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
+
+/* lazyev_evict for callers that must not allocate and cannot hand over a scratch area of their
+ * own for this call: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and the same result as lazyev_evict; the one
+ * difference is where the kernels' scratch buffer lives.  The selection kernel leaves a gather
+ * list (source entry of every survivor, one int32 per cache entry of the layer's units) that the
+ * row-move kernel then walks; lazyev_evict keeps it in the caller's workspace, this call keeps
+ * it in a device array of LAZYEV_STATIC_SCRATCH_ENTRIES int32 (4 MiB) that is part of the
+ * library image: every GPU the library runs on holds its own copy from load time until the
+ * process ends.  The call allocates nothing, neither device nor host memory.
+ * Limits: batch * n_kv_heads * capacity <= LAZYEV_STATIC_SCRATCH_ENTRIES and at most
+ * LAZYEV_LDS_CANDIDATES candidates per unit (capacity - window); beyond them LAZYEV_ESCRATCH and
+ * nothing is launched.  The device that was current at lazyev_init must be current (EINVAL).
+ * All contexts of a process share one array per GPU and the array keeps the previous call's
+ * list: nothing in it has to start at zero (a call overwrites every entry it later reads), but
+ * two such calls whose kernels overlap on one GPU (different streams) race.  The per-layer
+ * counters lazyev_stats reports stay in the caller's workspace.
+ * Errors: those of lazyev_evict, ESCRATCH. */
+#define LAZYEV_STATIC_SCRATCH_ENTRIES (1 << 20)
+int lazyev_evict_static(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted /*host*/);
 
 /* The same check (Sec. 4 "MRI-Centric Eviction"; Eq. 3; Eq. 6; the eviction branch of Alg. 1)
  * for EVERY layer after decode step t (every layer must have taken step t).  The paper states

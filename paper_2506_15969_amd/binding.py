@@ -17,7 +17,7 @@ if not os.path.exists(_LIB_PATH):
                       "(expected at %s)" % _LIB_PATH)
 lib = C.CDLL(_LIB_PATH)
 
-OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP, ENOMEM, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16
@@ -46,7 +46,7 @@ class Stats(C.Structure):
 # what include/lazyev.h declares (the contract) ...
 EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_decode_step",
            "lazyev_prefill_track", "lazyev_prefill_track_seq", "lazyev_evict", "lazyev_evict_all",
-           "lazyev_stats", "lazyev_admit", "lazyev_retire",
+           "lazyev_evict_static", "lazyev_stats", "lazyev_admit", "lazyev_retire",
            "lazyev_cached_before_step", "lazyev_mri_histogram", "lazyev_window_from_histogram",
            "lazyev_score_pairs", "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
 # ... and include/lazyev_bench.h (knobs and the per-kernel timer in the same library; the plain
@@ -92,6 +92,8 @@ lib.lazyev_evict.restype = C.c_int
 lib.lazyev_evict.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_evict_all.restype = C.c_int
 lib.lazyev_evict_all.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+lib.lazyev_evict_static.restype = C.c_int
+lib.lazyev_evict_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
 lib.lazyev_window_from_histogram.restype = C.c_int
 lib.lazyev_window_from_histogram.argtypes = [C.POINTER(C.c_int64), C.c_int32, C.c_double, C.POINTER(C.c_int32)]
 lib.lazyev_stats.restype = C.c_int
@@ -240,6 +242,15 @@ class LazyEviction:
         code = lib.lazyev_evict(self._ctx, layer, t, C.byref(n))
         if code != OK:
             raise LazyevError(code, "lazyev_evict")
+        return n.value
+
+    def evict_static(self, layer, t) -> int:
+        """lazyev_evict_static: lazyev_evict with the gather list in the library's own static
+        device array instead of the workspace."""
+        n = C.c_int32(0)
+        code = lib.lazyev_evict_static(self._ctx, layer, t, C.byref(n))
+        if code != OK:
+            raise LazyevError(code, "lazyev_evict_static")
         return n.value
 
     def evict_all(self, t) -> int:

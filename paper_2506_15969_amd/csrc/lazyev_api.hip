@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,6 +20,12 @@ int decode_slice_max();
 
 using lazyev::Workspace;
 
+// Gather list of lazyev_evict_static: the library's own device memory, one copy per GPU, held
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; the
+// address a kernel can use is looked up once per device (static_scratch_of below).
+constexpr size_t kStaticScratchEntries = LAZYEV_STATIC_SCRATCH_ENTRIES;
+static __device__ __align__(256) int32_t scratch[kStaticScratchEntries];
+
 struct lazyev_ctx {
   lazyev_config cfg;
   int32_t capacity, group, units;
@@ -30,6 +37,8 @@ struct lazyev_ctx {
   std::vector<int32_t> len, last_step;
   std::vector<int64_t> n_evict_events, n_evicted;
   int last_hip_error;
+  int device;                       // the device that was current at lazyev_init
+  int32_t *static_scratch;          // that device's copy of `scratch` (see static_scratch_of)
   // fused kernel: the call whose tracking has not been applied yet, and the buffer pair in turn
   lazyev::TrackArgs pend;
   int cur_buf;
@@ -153,6 +162,29 @@ void drop_events(lazyev_ctx *ctx) {
   for (auto &t : ctx->prof)
     for (int i = 0; i < 3; ++i) (void)hipEventDestroy(t.ev[i]);
   ctx->prof.clear();
+}
+
+// Device address of `scratch` on the current device, looked up on the first call per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t *g_scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch_of(int *device, int32_t **ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<int32_t *>(p);
+  }
+  *device = dev;
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 int fail_hip(lazyev_ctx *ctx, hipError_t e) {
@@ -293,6 +325,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->last_hip_error = 0;
   ctx->prof_armed = 0;
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
+  if (static_scratch_of(&ctx->device, &ctx->static_scratch) != hipSuccess) { delete ctx; return LAZYEV_EHIP; }
 
   // activation counters, moved-row counters and tickets lie next to each other
   hipError_t e = hipMemsetAsync(ctx->ws.activations, 0, l.total - l.activations, ctx->stream);
@@ -579,6 +612,20 @@ int lazyev_evict(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) 
   return evict_layer(ctx, layer, t, n_evicted, nullptr);
 }
 
+int lazyev_evict_static(lazyev_ctx *ctx, int32_t layer, int32_t t, int32_t *n_evicted) {
+  if (n_evicted) *n_evicted = 0;
+  if (!ctx) return LAZYEV_EINVAL;
+  // one gather-list entry per cache entry of the layer; the selection keeps its keys in LDS
+  if (static_cast<size_t>(ctx->units) * ctx->capacity > kStaticScratchEntries ||
+      ctx->capacity - ctx->cfg.window > lazyev::evict_lds_candidates())
+    return LAZYEV_ESCRATCH;
+  int dev = -1;
+  const hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (dev != ctx->device || !ctx->static_scratch) return LAZYEV_EINVAL;   // (the array is per device)
+  return evict_layer(ctx, layer, t, n_evicted, ctx->static_scratch);
+}
+
 int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted) {
   if (n_evicted) *n_evicted = 0;
   if (!ctx) return LAZYEV_EINVAL;
@@ -850,6 +897,7 @@ const char *lazyev_strerror(int code) {
     case LAZYEV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case LAZYEV_EHIP: return "HIP runtime error";
     case LAZYEV_ENOMEM: return "out of host memory";
+    case LAZYEV_ESCRATCH: return "shape beyond the static scratch of lazyev_evict_static";
     default: return "unknown lazyev error code";
   }
 }

@@ -84,7 +84,7 @@ def test_init_needs_buffers_and_workspace(lazyev_lib):
 def test_null_context_calls(lazyev_lib):
     b = lazyev_lib
     assert b.lib.lazyev_decode_step(None, 0, 1, 1, 1, 1, 1, None, None) == b.EINVAL
-    assert b.lib.lazyev_evict(None, 0, 1, None) == b.EINVAL
+    assert b.lib.lazyev_evict(None, 0, 1, None) == b.EINVAL and b.lib.lazyev_evict_static(None, 0, 1, None) == b.EINVAL
     assert b.lib.lazyev_evict_all(None, 1, None) == b.EINVAL
     assert b.lib.lazyev_stats(None, None) == b.EINVAL
     assert b.lib.lazyev_set_chunk(None, 128) == b.EINVAL and b.lib.lazyev_set_variant(None, 4) == b.EINVAL
