@@ -128,6 +128,121 @@ def cpu_baseline(cfg, target_seconds: float = 15.0) -> dict:
                          units_per_model)}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_track_mode(args):
+    """--prefill-track: times lazyev_prefill_track (the tracking loop of Alg. 1 and Eq. 1 over the
+    prompt's own causal attention) on one layer of the workload with a prompt of --prompt-len
+    (default 2048) positions, and prints one JSON line: milliseconds per layer and the rate of
+    the two causal Q K^T passes against the dense bf16 MFMA peak."""
+    import torch
+    from paper_2506_15969_amd import binding
+    from paper_2506_15969_amd.workload import CONFIGS, Workload
+    P = args.prompt_len if args.prompt_len > 0 else 2048
+    reps = args.steps or 5
+    cfg = CONFIGS[args.config].scaled(n_layers=1, prompt_len=P, steps=8)
+    wl = Workload(cfg)
+    eng = binding.LazyEviction(1, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.budget,
+                               cfg.window, P, cfg.alpha, dtype=cfg.torch_dtype)
+    eng.load_prompt(0, *wl.prompt_kv(0, device="cuda"))
+    eng.init()
+    q = wl.prompt_queries(0, device="cuda")
+    eng.prefill_track(0, q)                                   # warm-up
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(reps):
+        eng.prefill_track(0, q)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / reps
+    units = cfg.batch * cfg.n_kv_heads
+    # 2 flops per multiply-add, causal triangle incl. the diagonal, G heads, two passes
+    flops = 2.0 * 2.0 * units * cfg.group * (P * (P + 1) / 2.0) * cfg.head_dim
+    st = eng.stats()
+    print(json.dumps({
+        "metric": "prompt_tracking_ms_per_layer", "value": ms, "unit": "ms", "higher_is_better": False,
+        "config": {"workload": "%s-prompt%d" % (cfg.name, P), "batch": cfg.batch, "prompt_len": P,
+                   "n_q_heads": cfg.n_q_heads, "n_kv_heads": cfg.n_kv_heads, "alpha": cfg.alpha},
+        "prompt_tokens_per_s": cfg.batch * P / (ms * 1e-3), "dtype": "bf16", "data": "synthetic",
+        "activations_per_call": st["n_activations"][0] // (reps + 1),
+        "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "flops_per_call": flops}}))
+    eng.close()
+
+
+def timeline_mode(args):
+    """--timeline: where the time of one decode launch goes.  Runs the workload's shapes (4 layers,
+    prompt = budget, so the cache is at its budget) on the instrumented build of the library
+    (liblazyev_timeline.so: every block of the fused decode kernel leaves time stamps of the
+    100 MHz counter) and prints, over the blocks of the sampled launches, when the stream, the
+    ticket and the block end fall, counted from the start of the launch's first block."""
+    os.environ["LAZYEV_LIBRARY"] = "liblazyev_timeline.so"
+    import numpy as np
+    import torch
+    from paper_2506_15969_amd import binding
+    from paper_2506_15969_amd.workload import CONFIGS, Workload
+    base = CONFIGS[args.config]
+    L, steps = 4, max(args.steps or 40, 24)
+    P = args.prompt_len if args.prompt_len >= 0 else base.budget
+    cfg = base.scaled(n_layers=L, prompt_len=P, steps=steps)
+    wl = Workload(cfg)
+    eng = binding.LazyEviction(L, cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.budget,
+                               cfg.window, cfg.prompt_len, cfg.alpha, dtype=cfg.torch_dtype)
+    for l in range(L):
+        eng.load_prompt(l, *wl.prompt_kv(l, device="cuda"))
+    eng.init()
+    if args.target_blocks:
+        eng.set_target_blocks(args.target_blocks)
+    ins = [wl.step_inputs(l, 1, steps + 1, device="cuda") for l in range(L)]
+    out = torch.empty((L, cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+    read = binding.lib.lazyev_timeline_read
+    read.restype = C.c_int
+    NB = 2048
+    buf = (C.c_uint64 * (NB * 8))()
+    samples = []
+    for t in range(1, steps + 1):
+        for l in range(L):
+            q, kn, vn = ins[l]
+            eng.decode_step(l, t, q[t - 1], kn[t - 1], vn[t - 1], out[l])
+        if t > steps // 2:                            # the stamps of the step's last launch
+            torch.cuda.synchronize()
+            assert read(buf, NB * 8) == 0
+            a = np.frombuffer(buf, dtype=np.uint64).reshape(NB, 8).astype(np.int64)
+            live = a[:, 0] > 0
+            stream = live & (a[:, 3] >= a[:, 0]) & (a[:, 2] >= a[:, 0])
+            if stream.any():
+                origin = a[stream, 0].min()
+                trk = a[live & ~stream]
+                trk = trk[trk[:, 5] >= trk[:, 0]]
+                samples.append(((a[stream][:, :6] - origin) / 100.0, a[stream][:, 7],
+                                (trk[:, [0, 5]] - origin) / 100.0))
+        eng.evict_all(t)                              # (fires where the schedule says so)
+    n1 = eng.stats()["len"][0]
+    names = ["block start", "first sub-tile multiplied", "end of wave 0's stream", "all four waves done",
+             "ticket taken", "block end"]
+
+    def q(x):
+        return {"min": round(float(np.min(x)), 2), "p50": round(float(np.median(x)), 2),
+                "p90": round(float(np.percentile(x, 90)), 2), "max": round(float(np.max(x)), 2)}
+    res = {"what": "in-kernel timeline of decode_fused_kernel, microseconds from the start of the launch's "
+                   "first block, over the stream blocks of %d launches" % len(samples),
+           "config": {"workload": "%s-prompt%d" % (base.name, P), "layers": L, "entries_per_unit_at_the_end": n1,
+                      "stream_blocks_per_launch": int(samples[0][0].shape[0])},
+           "stamps": {n: dict(q(np.concatenate([s[0][:, i] for s in samples])),
+                              mean_of_per_launch_max=round(float(np.mean([s[0][:, i].max() for s in samples])), 2),
+                              mean_of_per_launch_min=round(float(np.mean([s[0][:, i].min() for s in samples])), 2))
+                      for i, n in enumerate(names)},
+           "finisher_tail_us (block end - end of its stream)":
+               q(np.concatenate([(s[0][:, 5] - s[0][:, 2])[s[1] == 1] for s in samples])),
+           "tracking_blocks": {"start": q(np.concatenate([s[2][:, 0] for s in samples])),
+                               "end": q(np.concatenate([s[2][:, 1] for s in samples]))}}
+    print(json.dumps(res))
+    eng.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,6 +281,12 @@ def main():
                     help="after the timed region, run one more untimed window of W steps with ONE "
                          "layer call per step bracketed by the library's own events "
                          "(roofline.single_call)")
+    ap.add_argument("--prefill-track", action="store_true",
+                    help="time lazyev_prefill_track on one layer instead of the decode path "
+                         "(--prompt-len positions, default 2048; --steps repetitions, default 5)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-block timeline of the fused decode kernel from the instrumented build "
+                         "of the library (liblazyev_timeline.so) instead of the throughput run")
     ap.add_argument("--progress", type=int, default=0,
                     help="write a line to stderr every this many submitted steps (long runs)")
     args = ap.parse_args()
@@ -174,6 +295,12 @@ def main():
               "(every (layer, sequence, KV head) unit is independent). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
+    if args.prefill_track:
+        prefill_track_mode(args)
+        return
+    if args.timeline:
+        timeline_mode(args)
+        return
 
     import torch
     from paper_2506_15969_amd import binding

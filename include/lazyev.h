@@ -87,7 +87,8 @@ typedef struct {
   int32_t *last_step;           /* (host, nullable) out: last decode step seen by each layer     */
   int64_t *n_evict_events;      /* (host, nullable) out: evictions that fired, per layer         */
   int64_t *n_evicted;           /* (host, nullable) out: entries removed per unit, summed over
-                                   the layer's events                                           */
+                                   the layer's events (with per-sequence timing, where the due
+                                   units of an event may differ: the largest per event)         */
   int64_t *n_activations;       /* (host, nullable) out: (entry, step) pairs with p >= alpha,
                                    summed over the layer's units                                */
   int64_t *n_rows_moved;        /* (host, nullable) out: surviving entries that an eviction moved

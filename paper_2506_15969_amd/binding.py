@@ -11,7 +11,10 @@ import os
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "liblazyev.so")
+# (LAZYEV_LIBRARY names another build of the same library in lib/, e.g. the instrumented
+# liblazyev_timeline.so that bench.py --timeline measures with)
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib",
+                         os.path.basename(os.environ.get("LAZYEV_LIBRARY", "liblazyev.so")))
 if not os.path.exists(_LIB_PATH):
     raise ImportError("liblazyev.so is not built: run `python -m paper_2506_15969_amd.build` "
                       "(expected at %s)" % _LIB_PATH)

@@ -25,11 +25,15 @@ SOURCES = {"decode_kernels.hip": [], "decode_fused.hip": ["-mllvm", "-amdgpu-ker
 # measuring aids (plain streaming probes): a library of their own, not part of the path
 BENCH_LIB = os.path.join(LIBDIR, "liblazyev_bench.so")
 BENCH_SOURCES = {"probe_kernels.hip": []}
+# the same library with the fused decode kernel instrumented (per-block time stamps of the last
+# launch; bench.py --timeline reads them): a measuring build, never what the binding loads by default
+TIMELINE_LIB = os.path.join(LIBDIR, "liblazyev_timeline.so")
+TIMELINE_FLAGS = ["-DLAZYEV_TIMELINE"]
 
 
 def _compile(item):
     name, extra = item
-    obj = os.path.join(LIBDIR, name.replace(".hip", ".o"))
+    obj = os.path.join(LIBDIR, name.replace(".hip", "_timeline.o" if TIMELINE_FLAGS[0] in extra else ".o"))
     cmd = [HIPCC, *COMMON, *extra, "-c", os.path.join(CSRC, name), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -39,9 +43,13 @@ def _compile(item):
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(LIBDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES) + len(BENCH_SOURCES)) as ex:
-        objs = list(ex.map(_compile, list(SOURCES.items()) + list(BENCH_SOURCES.items())))
-    for lib, group in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+    fused = "decode_fused.hip"
+    jobs = list(SOURCES.items()) + list(BENCH_SOURCES.items()) + [(fused, SOURCES[fused] + TIMELINE_FLAGS)]
+    with ThreadPoolExecutor(max_workers=len(jobs)) as ex:
+        objs = list(ex.map(_compile, jobs))
+    path_objs = objs[:len(SOURCES)]
+    timeline_objs = [objs[-1] if o.endswith("decode_fused.o") else o for o in path_objs]
+    for lib, group in ((LIB, path_objs), (BENCH_LIB, objs[len(SOURCES):-1]), (TIMELINE_LIB, timeline_objs)):
         r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", lib],
                            capture_output=True, text=True)
         if r.returncode != 0:

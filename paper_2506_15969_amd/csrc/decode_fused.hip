@@ -50,6 +50,8 @@
 // holds the A operand of the second.
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace lazyev {
 namespace {
 
@@ -62,6 +64,35 @@ constexpr float kRaise = 8.0f;          // the reference maximum moves when exce
 constexpr int kTrackRows = 3;           // entries per thread per tracking batch
 constexpr int kHeadPad = 8;             // logits and statistics are stored for 8 heads per unit
 constexpr int kRunMax = 20;             // sub-tiles whose logits a wave keeps in LDS (10 KB) before it writes them out
+// How a unit's n_sub sub-tiles of 16 entries are dealt to the kWaves * n_split waves of its
+// n_split blocks: wave wv (= kWaves * split + wave) takes wv, wv + kWaves * n_split, ..., so the
+// waves of a unit read one moving window of the cache together (measured against a region of
+// consecutive sub-tiles per block: 28.6 against 29.2 us per call on the 2048-entry workload).
+struct WaveMap { int first, step, cnt; };
+__host__ __device__ inline WaveMap fused_wave_map(int n_sub, int n_split, int split, int wave) {
+  WaveMap m;
+  m.first = split * kWaves + wave;
+  m.step = kWaves * n_split;
+  m.cnt = m.first < n_sub ? (n_sub - m.first + m.step - 1) / m.step : 0;
+  return m;
+}
+// Most sub-tiles one wave takes.
+__host__ __device__ inline int fused_wave_run(int n_sub, int n_split) {
+  return (n_sub + kWaves * n_split - 1) / (kWaves * n_split);
+}
+
+#ifdef LAZYEV_TIMELINE
+// Measuring build only (liblazyev_timeline.so, see build.py): every block of the LAST launch
+// leaves time stamps of the constant 100 MHz counter: 0 block start, 1 first sub-tile multiplied,
+// 2 end of wave 0's stream, 3 all four waves done, 4 ticket taken, 5 block end; word 7: 1 if the
+// block finished its unit.  Read with lazyev_timeline_read.
+__device__ unsigned long long lz_stamp[2048 * 8];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 2048) lz_stamp[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#define STAMPV(i, v) do { if (threadIdx.x == 0 && blockIdx.x < 2048) lz_stamp[blockIdx.x * 8 + (i)] = (v); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#define STAMPV(i, v) do {} while (0)
+#endif
 
 typedef unsigned short bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -115,21 +146,28 @@ struct TrackBatch {
 
 // Entry that thread `tid` of part `part` (of n_parts) handles in round r: the parts own the
 // 16-entry sub-tiles exactly as the stream blocks of a launch with n_parts blocks per unit do
-// (sub-tile 4 * part + w + 4 * n_parts * k for wave w), so a tracking block that runs on the
-// XCD of the stream block with the same index finds the logits that block wrote in its L2.
-__device__ __forceinline__ int track_entry(int part, int n_parts, int r) {
-  const int j = r * (kBlock / 16) + (static_cast<int>(threadIdx.x) >> 4);   // the part's j-th sub-tile
-  const int sub = kWaves * part + (j % kWaves) + kWaves * n_parts * (j / kWaves);
-  return sub * 16 + (static_cast<int>(threadIdx.x) & 15);
+// (fused_wave_map), so a tracking block that runs on the XCD of the stream block with the same
+// index finds the logits that block wrote in its L2.  Beyond the part's share: a number no
+// cache reaches.
+__device__ __forceinline__ int track_entry(int n_sub, int part, int n_parts, int r) {
+  const int j = r * (kBlock / 16) + (static_cast<int>(threadIdx.x) >> 4);   // wave j % kWaves, its sub-tile j / kWaves
+  const WaveMap m = fused_wave_map(n_sub, n_parts, part, j % kWaves);
+  const int it = j / kWaves;
+  return it < m.cnt ? (m.first + it * m.step) * 16 + (static_cast<int>(threadIdx.x) & 15) : 0x7FFFFFF0;
+}
+// Rounds of kBlock entries that cover the largest part.
+__device__ __forceinline__ int track_rounds(int n_sub, int n_parts) {
+  return (kWaves * fused_wave_run(n_sub, n_parts) + kBlock / 16 - 1) / (kBlock / 16);
 }
 
 __device__ __forceinline__ void track_load(const TrackArgs &k, int unit, int part, int n_parts, int r0,
                                            TrackBatch &b) {
   const float *lg = k.logits + static_cast<size_t>(unit) * k.p_stride * kHeadPad;
   const int n1 = k.n_old + 1;
+  const int n_sub = (n1 + 15) >> 4;
 #pragma unroll
   for (int r = 0; r < kTrackRows; ++r) {
-    const int i = track_entry(part, n_parts, r0 + r);
+    const int i = track_entry(n_sub, part, n_parts, r0 + r);
     b.sa[r] = b.sb[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i < n1) {
       b.sa[r] = *reinterpret_cast<const float4 *>(lg + static_cast<size_t>(i) * kHeadPad);
@@ -175,13 +213,14 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
   const int seq = unit / k.n_kv_heads, kvh = unit % k.n_kv_heads;
   const int G = k.group;
   const int n_old = k.n_old, n1 = k.n_old + 1;
+  const int n_sub = (n1 + 15) >> 4;
   const size_t head0 = static_cast<size_t>(seq) * k.n_q_heads + static_cast<size_t>(kvh) * G;
   int32_t *ts = k.ts + static_cast<size_t>(unit) * k.capacity;
   int32_t *mri = k.mri + static_cast<size_t>(unit) * k.capacity;
   unsigned n_act = 0;
 #pragma unroll
   for (int r = 0; r < kTrackRows; ++r) {
-    const int i = track_entry(part, n_parts, r0 + r);
+    const int i = track_entry(n_sub, part, n_parts, r0 + r);
     if (i >= n1) continue;
     const float s[kHeadPad] = {b.sa[r].x, b.sa[r].y, b.sa[r].z, b.sa[r].w,
                                b.sb[r].x, b.sb[r].y, b.sb[r].z, b.sb[r].w};
@@ -214,7 +253,7 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
 // for the count and one for each entry the block can own.
 __host__ __device__ inline int fused_part_cap(int n_old, int n_parts) {
   const int n_sub = (n_old + 1 + 15) >> 4;
-  return (n_sub + kWaves * n_parts - 1) / (kWaves * n_parts) * (kWaves * 16) + 1;
+  return fused_wave_run(n_sub, n_parts) * (kWaves * 16) + 1;
 }
 
 // Tracking from the candidate records of the call's blocks b = part, part + step, ...
@@ -281,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
   if (k.compact) {
     n_act = track_records(k, unit, part, n_parts, m, invl);
   } else {
-    const int rounds = (k.n_old + 1 + n_parts * kBlock - 1) / (n_parts * kBlock);
+    const int rounds = track_rounds((k.n_old + 1 + 15) >> 4, n_parts);
     for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
       TrackBatch b;
       track_load(k, unit, part, n_parts, r0, b);
@@ -343,8 +382,12 @@ __device__ __forceinline__ void load_partials(PartialGroup<4> &g, const float *c
 // Merges the unit's block partials (in block order, so the result does not depend on which
 // block came last) into the output row and stores the unit's softmax statistics.  Thread t
 // owns output elements 4t .. 4t+3 (all of one head); GW partials per memory round trip.
-template <int GW>
-__device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
+// The calling block is partial `own_j` itself and has it in registers (own_o: its four output
+// elements, own_m / own_l: its head's max and sum): those are used instead of what memory holds
+// in that place.  kOwn: the unit has no other block and nothing is loaded at all.
+template <int GW, bool kOwn>
+__device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_j, const f32x4_t &own_o,
+                            float own_m, float own_l) {
   const int tid = threadIdx.x;
   const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int G = a.group;
@@ -368,10 +411,11 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split) {
       pm[jj] = ml + j * (2 * G) + h;
       pl[jj] = ml + j * (2 * G) + G + h;
     }
-    load_partials(g, po, pm, pl);
+    if (!kOwn) load_partials(g, po, pm, pl);
 #pragma unroll
     for (int jj = 0; jj < GW; ++jj) {
       if (j0 + jj >= n_split) break;               // uniform
+      if (j0 + jj == own_j) { g.o[jj] = own_o; g.m[jj] = own_m; g.l[jj] = own_l; }   // (never read back)
       const float m_new = fmaxf(m_run, g.m[jj]);
       // a block without entries has max = -inf, sum = 0, values = 0: its factor is 0
       const float fr = m_run == -INFINITY ? 0.f : __expf(m_run - m_new);
@@ -421,6 +465,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   __shared__ float run_lse[kWaves][kHeadPad];      // kLong: each wave's latest log-sum-exp per head (one word: no torn reads)
 
   const int G = a.group;
+  STAMP(0);
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
@@ -434,7 +479,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     if (k.compact) {
       n_act = track_records(k, unit, part, n_split, m, invl);
     } else {
-      const int rounds = (k.n_old + 1 + n_split * kBlock - 1) / (n_split * kBlock);
+      const int rounds = track_rounds((k.n_old + 1 + 15) >> 4, n_split);
       for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
         TrackBatch b;
         track_load(k, unit, part, n_split, r0, b);
@@ -442,6 +487,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       }
     }
     track_count(k, unit, part, n_act, cnt_lds);
+    STAMP(5);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63;
@@ -465,16 +511,17 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   const int n_sub = (n1 + 15) >> 4;
   const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
 
-  // this wave's sub-tiles: wv, wv + n_wv, wv + 2 n_wv, ...
-  const int n_wv = kWaves * n_split, wv = split * kWaves + wave;
-  const int cnt = (n_sub - wv + n_wv - 1) / n_wv;  // may be <= 0 for a short cache
+  // this wave's sub-tiles (fused_wave_map)
+  const WaveMap wm = fused_wave_map(n_sub, n_split, split, wave);
+  const int cnt = wm.cnt;                          // (0 for a wave beyond a short cache)
+  auto sub_of = [&](int it) { return wm.first + it * wm.step; };
 
   const bf16_t *kc = k_cache + static_cast<size_t>(unit) * capacity * D;
   const bf16_t *vc = v_cache + static_cast<size_t>(unit) * capacity * D;
   const bf16_t *k_new = k_new_all + static_cast<size_t>(unit) * D;
   const bf16_t *v_new = v_new_all + static_cast<size_t>(unit) * D;
   const bf16_t *q_row = static_cast<const bf16_t *>(a.q) + (head0 + hc) * D + g * 8;
-  const int run = min((n_sub + kWaves * n_split - 1) / (kWaves * n_split), kRunMax);
+  const int run = min(fused_wave_run(n_sub, n_split), kRunMax);
   float *my_logits = logit_lds + static_cast<size_t>(wave) * run * (16 * kHeadPad);
   int seg0 = 0;                                    // first of this wave's sub-tiles whose logits are still in LDS
   float *logits_out = a.logits_out + static_cast<size_t>(unit) * a.p_stride * kHeadPad;
@@ -493,7 +540,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   }
 
   auto load_k = [&](SubTile &t, int it) {
-    const int sub = wv + it * n_wv;
+    const int sub = sub_of(it);
     // K: whole rows, 16 lanes per row (row 4j+g, 16-byte chunk c); re-laid out through LDS
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -503,7 +550,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     }
   };
   auto load_v = [&](SubTile &t, int it) {
-    const int sub = wv + it * n_wv;
+    const int sub = sub_of(it);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = min(sub * 16 + 4 * g + i, n_old);
@@ -512,8 +559,10 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     }
   };
 
-  auto compute = [&](SubTile &t, int it) {
-    const int sub = wv + it * n_wv;
+  // kMore (a std::bool_constant): the wave has a sub-tile after this one and requests it here
+  auto compute = [&](SubTile &t, int it, auto more_tag) {
+    constexpr bool kMore = decltype(more_tag)::value;
+    const int sub = sub_of(it);
     // K rows -> MFMA A layout (lane (c, g): row c, chunks 4kk+g).  Chunk x of row r sits at
     // slot x ^ r of the row, so both the row-wise writes and the column-wise reads touch
     // every LDS bank once.  The staging area is private to the wave: LDS operations of one
@@ -530,7 +579,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       for (int kk = 0; kk < KC; ++kk) ka[kk] = stage[c * 16 + ((4 * kk + g) ^ c)];
     }
     // the K registers are free again: the next sub-tile's K rows travel during the arithmetic
-    if (it + 1 < cnt) load_k(t, it + 1);
+    if constexpr (kMore) load_k(t, it + 1);
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk)
@@ -579,7 +628,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       vb[1] = __builtin_amdgcn_perm(t.v[3][e >> 1], t.v[2][e >> 1], sel);
       o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(s16x4_t, vb), o[e], 0, 0, 0);
     }
-    if (it + 1 < cnt) load_v(t, it + 1);
+    if constexpr (kMore) load_v(t, it + 1);
   };
 
   SubTile buf;
@@ -592,7 +641,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     for (int it = it0 + (lane >> 5); it < it1; it += 2)
-      *reinterpret_cast<float4 *>(logits_out + static_cast<size_t>(wv + it * n_wv) * (16 * kHeadPad) + (lane & 31) * 4) =
+      *reinterpret_cast<float4 *>(logits_out + static_cast<size_t>(sub_of(it)) * (16 * kHeadPad) + (lane & 31) * 4) =
           *reinterpret_cast<const float4 *>(my_logits + (it - it0) * (16 * kHeadPad) + (lane & 31) * 4);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -612,7 +661,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
         const float *src = my_logits + (it - it_a) * (16 * kHeadPad) + e_in * kHeadPad;
         sa = *reinterpret_cast<const f32x4_t *>(src);
         sb = *reinterpret_cast<const f32x4_t *>(src + 4);
-        entry = (wv + it * n_wv) * 16 + e_in;
+        entry = sub_of(it) * 16 + e_in;
         cand = sa[0] >= cut[0] || sa[1] >= cut[1] || sa[2] >= cut[2] || sa[3] >= cut[3] ||
                sb[0] >= cut[4] || sb[1] >= cut[5] || sb[2] >= cut[6];
         cand = (cand && entry < n1) || entry == n_old;
@@ -664,14 +713,21 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the LDS slots are written again next
     __builtin_amdgcn_wave_barrier();
   };
-  for (int it = 0; it < cnt; ++it) {
-    compute(buf, it);
-    if (it + 1 - seg0 == kRunMax && it + 1 < cnt) {
+  // (the wave's last sub-tile stands outside the loop, so that the loop requests the next
+  // sub-tile unconditionally: no branch between the loads, exact load counts for the waits)
+  for (int it = 0; it + 1 < cnt; ++it) {
+    compute(buf, it, std::true_type{});
+#ifdef LAZYEV_TIMELINE
+    if (it == 0) STAMP(1);
+#endif
+    if (it + 1 - seg0 == kRunMax) {
       if constexpr (kLong) segment_candidates(seg0, it + 1);
       else flush(seg0, it + 1);
       seg0 = it + 1;
     }
   }
+  if (cnt > 0) compute(buf, cnt - 1, std::false_type{});
+  STAMP(2);
   if (!kCompact) flush(seg0, cnt);
   // ---- the four waves of the block -> one partial
   lsum += __shfl_xor(lsum, 16);
@@ -688,44 +744,30 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     }
   }
   __syncthreads();
-  {
-    const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
-    float *pacc = a.ws.part_acc + part * (G * D);
-    const int e0 = 4 * tid;                        // elements 4 tid .. 4 tid + 3, all of one head
-    if (e0 < G * D) {
-      const int h = e0 / D;
-      float mb = m_lds[0][h];
+  STAMP(3);
+  // ---- this block's partial: thread owns output elements 4 tid .. 4 tid + 3, all of one head
+  // (threads beyond the group's rows work on a valid place and store nothing)
+  const int e0 = 4 * tid;
+  const int ec = min(e0, G * D - 4);
+  const int h_own = ec / D;
+  float mb_own = m_lds[0][h_own];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) mb = fmaxf(mb, m_lds[w][h]);
-      f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+  for (int w = 1; w < kWaves; ++w) mb_own = fmaxf(mb_own, m_lds[w][h_own]);
+  float l_own = 0.f;
+  f32x4_t v_own = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float mw = m_lds[w][h];
-        if (mw != -INFINITY) {
-          const float f = __expf(mw - mb);
-          const f32x4_t x = *reinterpret_cast<const f32x4_t *>(acc_lds + w * (8 * D) + e0);
+  for (int w = 0; w < kWaves; ++w) {
+    const float mw = m_lds[w][h_own];
+    if (mw != -INFINITY) {
+      const float f = __expf(mw - mb_own);
+      const f32x4_t x = *reinterpret_cast<const f32x4_t *>(acc_lds + w * (8 * D) + ec);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = fmaf(f, x[i], v[i]);
-        }
-      }
-      // device-scope (write-through) like store_f32_device, 16 bytes wide
-      __asm__ volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pacc + e0), "v"(v) : "memory");
-    }
-    if (tid < G) {
-      float mb = m_lds[0][tid];
-#pragma unroll
-      for (int w = 1; w < kWaves; ++w) mb = fmaxf(mb, m_lds[w][tid]);
-      float l = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float mw = m_lds[w][tid];
-        if (mw != -INFINITY) l = fmaf(__expf(mw - mb), lsum_lds[w][tid], l);
-      }
-      float *ml = a.ws.part_ml + part * (2 * G);
-      store_f32_device(ml + tid, mb);
-      store_f32_device(ml + G + tid, l);
+      for (int i = 0; i < 4; ++i) v_own[i] = fmaf(f, x[i], v_own[i]);
+      l_own = fmaf(f, lsum_lds[w][h_own], l_own);
     }
   }
+  // what only the NEXT launch needs: the candidate lists of the tracking and the appended row
+  auto tail_work = [&]() {
   if (kCompact) {
     // ---- candidates of the tracking: this wave's entries that can reach alpha in some head.
     // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
@@ -759,7 +801,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
         const float *src = my_logits + (it - s0) * (16 * kHeadPad) + e_in * kHeadPad;
         sa = *reinterpret_cast<const f32x4_t *>(src);
         sb = *reinterpret_cast<const f32x4_t *>(src + 4);
-        entry = (wv + it * n_wv) * 16 + e_in;
+        entry = sub_of(it) * 16 + e_in;
         cand = sa[0] >= cut[0] || sa[1] >= cut[1] || sa[2] >= cut[2] || sa[3] >= cut[3] ||
                sb[0] >= cut[4] || sb[1] >= cut[5] || sb[2] >= cut[6];
         cand = (cand && entry < n1) || entry == n_old;   // the appended entry starts its tracking there
@@ -788,29 +830,71 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[lane - 16] =
           reinterpret_cast<const uint4 *>(v_new)[lane - 16];
   }
+  };
+  // A unit of one block needs no exchange: its partial is the whole result.
+  const bool alone = n_split == 1;
+  if (!alone) {
+    // publish the partial with device-scope (write-through) stores, 16 bytes wide for the values
+    const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
+    float *pacc = a.ws.part_acc + part * (G * D);
+    if (e0 < G * D) __asm__ volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pacc + e0), "v"(v_own) : "memory");
+    // (the heads' max and sum all go out from ONE wave: dword stores of several waves into the
+    // one cache line they share were seen to reach a device-scope load late)
+    if (tid < G) {
+      float mb = m_lds[0][tid];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) mb = fmaxf(mb, m_lds[w][tid]);
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float mw = m_lds[w][tid];
+        if (mw != -INFINITY) l = fmaf(__expf(mw - mb), lsum_lds[w][tid], l);
+      }
+      float *ml = a.ws.part_ml + part * (2 * G);
+      store_f32_device(ml + tid, mb);
+      store_f32_device(ml + G + tid, l);
+    }
+  }
+  tail_work();                                     // (while the partial's stores travel)
   // ---- ticket: the last block of the unit finishes it
-  wait_own_stores();                               // every wave's partial stores have completed ...
+  if (!alone) wait_own_stores();                   // every wave's partial stores have completed ...
   __syncthreads();
   if (tid == 0) {
-    const int prev = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);   // ... before its ticket is taken
+    int prev = 0;
+    if (!alone)
+      prev = __hip_atomic_fetch_add(a.ticket + unit, 1, __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_AGENT);   // ... before its ticket is taken
     last_flag = (prev == n_split - 1);
-    if (prev == n_split - 1) a.ticket[unit] = 0;   // ready for the next launch
+    if (!alone && prev == n_split - 1) a.ticket[unit] = 0;   // ready for the next launch
     if (kCompact)
       *reinterpret_cast<int32_t *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
                                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad) =
           static_cast<int32_t>(cand_total);
   }
   __syncthreads();
-  if (!last_flag) return;
-  // (two blocks per unit is the usual split of a short cache: no loads of clamped duplicates)
-  if (n_split <= 2) finish_unit<2>(a, unit, n_split);
-  else finish_unit<4>(a, unit, n_split);
+  STAMP(4);
+  STAMPV(7, static_cast<unsigned long long>(last_flag));
+  if (!last_flag) { STAMP(5); return; }
+  // merge the unit's partials (this block's own from its registers) into the output row; two
+  // blocks per unit is the usual split of a short cache: no loads of clamped duplicates
+  if (alone) finish_unit<2, true>(a, unit, n_split, split, v_own, mb_own, l_own);
+  else if (n_split == 2) finish_unit<2, false>(a, unit, n_split, split, v_own, mb_own, l_own);
+  else finish_unit<4, false>(a, unit, n_split, split, v_own, mb_own, l_own);
+  STAMP(5);
 }
 
 }  // namespace
 
+#ifdef LAZYEV_TIMELINE
+// (host) copies the first n_words words of the stamps of the last launch; waits for the device
+extern "C" int lazyev_timeline_read(unsigned long long *out, int n_words) {
+  if (!out || n_words < 0 || n_words > 2048 * 8) return -1;
+  return static_cast<int>(hipMemcpyFromSymbol(out, HIP_SYMBOL(lz_stamp), sizeof(unsigned long long) * n_words));
+}
+#endif
 int decode_fused_split_max() { return kFusedSplitMax; }
+int decode_fused_wave_run(int n_sub, int n_split) { return fused_wave_run(n_sub, n_split); }
+int decode_fused_run_max() { return kRunMax; }
 int decode_fused_head_pad() { return kHeadPad; }
 
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group) {
@@ -844,14 +928,14 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
     return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
   const int n_sub = (a.n_old + 1 + 15) / 16;
-  int run = (n_sub + kWaves * a.n_split - 1) / (kWaves * a.n_split);
+  int run = fused_wave_run(n_sub, a.n_split);
   if (run > kRunMax) run = kRunMax;
   const size_t lds_all = static_cast<size_t>(kWaves) * run * 16 * kHeadPad * sizeof(float);
   const int sb = a.n_split * units;
   const bf16_t *kc = static_cast<const bf16_t *>(a.k_cache), *vc = static_cast<const bf16_t *>(a.v_cache);
   const bf16_t *kn = static_cast<const bf16_t *>(a.k_new), *vn = static_cast<const bf16_t *>(a.v_new);
   const int slots_on = a.slots.prompt_len ? 1 : 0;
-  const bool long_run = (n_sub + kWaves * a.n_split - 1) / (kWaves * a.n_split) > kRunMax;
+  const bool long_run = fused_wave_run(n_sub, a.n_split) > kRunMax;
   if (a.variant == 6 && long_run)
     hipLaunchKernelGGL((decode_fused_kernel<true, true>), dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
                        kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);

@@ -151,6 +151,10 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev
 // One launch per call: split blocks, the last block of a unit merges and tracks (bf16, d 128).
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev);
 int decode_fused_split_max();
+// Most sub-tiles of 16 entries one wave of a call with n_split blocks per unit takes, and how
+// many of them a wave keeps in LDS at a time.
+int decode_fused_wave_run(int n_sub, int n_split);
+int decode_fused_run_max();
 // Can a call with these sizes leave candidate lists (they fit the logits buffer, a wave's logits
 // stay in LDS to the end of its run, and the 8th logit place is free for the entry index)?
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group);

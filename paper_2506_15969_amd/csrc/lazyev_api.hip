@@ -413,7 +413,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
       // leaves its candidate lists segment by segment): one block per compute unit streams
       // fastest (measured at 8192 / 16384 / 32768 entries, 256 against 512 blocks: 93 / 165 /
       // 329 us against 95 / 171 / 345)
-      if ((n_sub + 4 * n_split - 1) / (4 * n_split) > 20) n_split = lo;
+      if (lazyev::decode_fused_wave_run(n_sub, n_split) > lazyev::decode_fused_run_max()) n_split = lo;
     }
     if (n_split > (n_sub + 3) / 4) n_split = (n_sub + 3) / 4;
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();

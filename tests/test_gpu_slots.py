@@ -39,6 +39,7 @@ def _drive(binding, with_weights, follow, variant=None, evict_together=False):
     p_out = torch.zeros((S, HQ, cap), dtype=torch.float32, device="cuda")
     orc, slot = {}, {s: None for s in range(S)}            # slot -> (prompt_len, t0) or None
     outs = []
+    removed = [0] * L                                      # per layer: sum over the events of the largest cut
     for t in range(1, STEPS + 1):
         for (when, kind, s, P, t0) in EVENTS:
             if when != t:
@@ -94,6 +95,7 @@ def _drive(binding, with_weights, follow, variant=None, evict_together=False):
             if follow:
                 gone = {(s, h): orc[(l, s, h)].evict(t - slot[s][1]) for s in active for h in range(HKV)}
                 assert n_ev == max([len(g) for g in gone.values()] + [0]), ("evicted", t, l, n_ev)
+                removed[l] += n_ev
                 if n_ev:
                     eng.stats()
                     pos_g, ts_g, mri_g = (x[l].cpu().numpy() for x in (eng.pos, eng.ts, eng.mri))
@@ -106,6 +108,9 @@ def _drive(binding, with_weights, follow, variant=None, evict_together=False):
                             assert np.array_equal(eng.k_cache[l, s, h, :n].double().cpu().numpy(), u.K)
                             assert np.array_equal(eng.v_cache[l, s, h, :n].double().cpu().numpy(), u.V)
     st = eng.stats()
+    if follow:
+        # with per-sequence timing n_evicted counts, per event, the largest cut among the due units
+        assert st["n_evicted"] == removed
     state = (torch.stack(outs), eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(),
              eng.mri.clone(), eng.pos.clone())
     return eng, orc, slot, st, state
