@@ -218,7 +218,8 @@ def timeline_mode(args):
                 trk = a[live & ~stream]
                 trk = trk[trk[:, 5] >= trk[:, 0]]
                 samples.append(((a[stream][:, :6] - origin) / 100.0, a[stream][:, 7],
-                                (trk[:, [0, 5]] - origin) / 100.0))
+                                (trk[:, [0, 5]] - origin) / 100.0, a[stream][:, 6],
+                                np.nonzero(stream)[0]))
         eng.evict_all(t)                              # (fires where the schedule says so)
     n1 = eng.stats()["len"][0]
     names = ["block start", "first sub-tile multiplied", "end of wave 0's stream", "all four waves done",
@@ -239,6 +240,31 @@ def timeline_mode(args):
                q(np.concatenate([(s[0][:, 5] - s[0][:, 2])[s[1] == 1] for s in samples])),
            "tracking_blocks": {"start": q(np.concatenate([s[2][:, 0] for s in samples])),
                                "end": q(np.concatenate([s[2][:, 1] for s in samples]))}}
+    # Which blocks end their stream late: by the XCD they ran on, by their place among the unit's
+    # blocks, and how far the blocks of one unit lie apart.
+    end = np.concatenate([s[0][:, 2] for s in samples])
+    xcd = np.concatenate([s[3] for s in samples])
+    blk = np.concatenate([s[4] for s in samples])
+    n_split = max(1, int(samples[0][0].shape[0]) // (cfg.batch * cfg.n_kv_heads))
+    res["stream_end_by_xcd"] = {str(int(x)): {"blocks_per_launch": round(float((xcd == x).sum()) / len(samples), 1),
+                                              "mean": round(float(end[xcd == x].mean()), 2)}
+                                for x in np.unique(xcd)}
+    res["stream_end_by_block_of_the_unit"] = {str(j): round(float(end[blk % n_split == j].mean()), 2)
+                                              for j in range(n_split)}
+    res["xcd_of_block_index_mod_8"] = {str(j): sorted(int(x) for x in np.unique(xcd[blk % 8 == j])) for j in range(8)}
+    per_unit = [s[0][:, 2].reshape(-1, n_split) for s in samples]
+    res["spread_of_a_unit's_blocks (latest - earliest stream end)"] = q(
+        np.concatenate([u.max(axis=1) - u.min(axis=1) for u in per_unit]))
+    fin = np.concatenate([s[1] == 1 for s in samples])
+    st = np.concatenate([s[0] for s in samples])
+    res["finishing_blocks"] = {"partials complete - all four waves done": q((st[:, 4] - st[:, 3])[fin]),
+                               "block end - partials complete": q((st[:, 5] - st[:, 4])[fin]),
+                               "stream end": q(st[fin, 2])}
+    res["other_blocks"] = {"block end - all four waves done": q((st[:, 5] - st[:, 3])[~fin]),
+                           "stream end": q(st[~fin, 2])}
+    res["per_launch"] = {"stream_end_sigma": round(float(np.mean([s[0][:, 2].std() for s in samples])), 2),
+                         "mean_stream_end": round(float(np.mean([s[0][:, 2].mean() for s in samples])), 2),
+                         "latest_stream_end": round(float(np.mean([s[0][:, 2].max() for s in samples])), 2)}
     print(json.dumps(res))
     eng.close()
 

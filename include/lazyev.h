@@ -38,6 +38,8 @@ extern "C" {
 #define LAZYEV_EHIP       -4   /* a HIP runtime call failed; lazyev_last_hip_error has the code  */
 #define LAZYEV_ENOMEM     -5   /* host memory for the context or a read-back buffer ran out      */
 #define LAZYEV_ESCRATCH   -6   /* lazyev_evict_static: the shape exceeds the library's static scratch */
+#define LAZYEV_EEXCHANGE  -7   /* lazyev_stats: a block of an earlier decode call gave up waiting for
+                                  another block's partial result; that call's outputs are invalid   */
 
 #define LAZYEV_DTYPE_FP32  0
 #define LAZYEV_DTYPE_BF16  1
@@ -209,7 +211,8 @@ int lazyev_evict_all(lazyev_ctx *ctx, int32_t t, int32_t *n_evicted /*host*/);
  * rows the compaction moved.  Applies any tracking still pending, waits for the stream, then
  * fills the non-null arrays of *out.  The TS / MRI / pos arrays themselves belong to the caller,
  * who reads them directly after this call (there is no copy-out argument).
- * Errors: EINVAL, EHIP, ENOMEM. */
+ * Errors: EINVAL, EHIP, ENOMEM; EEXCHANGE when a decode call since the last lazyev_stats could
+ * not complete its exchange between blocks (not expected on a working GPU; reported once). */
 int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out /*host*/);
 
 /* Per-sequence timing, for a batch whose sequences do not start together (the paper decodes one

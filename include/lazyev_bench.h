@@ -46,6 +46,13 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
  * 2 and 3 are not assigned.  Errors: EINVAL. */
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
 
+/* Kernel 4, units of 2..4 blocks: the unit's last block waits for the partial results of the
+ * others; the wait is bounded by `ticks` of the GPU's constant 100 MHz counter (default 2000000
+ * = 20 ms; the others never wait themselves, so the bound is not reached).  When it is, the block
+ * goes on with what it has and the next lazyev_stats returns LAZYEV_EEXCHANGE.  0 makes a block
+ * give up at its second look (a test of that path).  Errors: EINVAL. */
+int lazyev_set_spin_ticks(lazyev_ctx *ctx, uint32_t ticks);
+
 /* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels
  * (decode_step, or an evict that is due) record HIP events on the stream before, between and
  * after their two kernels.  lazyev_profile_read waits for the stream, adds up the elapsed

@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
                       "(expected at %s)" % _LIB_PATH)
 lib = C.CDLL(_LIB_PATH)
 
-OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP, ENOMEM, ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ECAPACITY, EWORKSPACE, EHIP, ENOMEM, ESCRATCH, EEXCHANGE = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_FP32, DTYPE_BF16 = 0, 1
 SCORE_H1, SCORE_H2 = 1, 2
 SCORE_H2_DECREASING = 16
@@ -54,7 +54,7 @@ EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_de
            "lazyev_score_pairs", "lazyev_destroy", "lazyev_strerror", "lazyev_last_hip_error"]
 # ... and include/lazyev_bench.h (knobs and the per-kernel timer in the same library; the plain
 # streaming probes in liblazyev_bench.so, loaded by bench_lib() when somebody measures)
-BENCH_EXPORTS = ["lazyev_set_chunk", "lazyev_set_target_blocks", "lazyev_set_variant",
+BENCH_EXPORTS = ["lazyev_set_chunk", "lazyev_set_target_blocks", "lazyev_set_variant", "lazyev_set_spin_ticks",
                  "lazyev_profile_arm", "lazyev_profile_read"]
 BENCH_LIB_EXPORTS = ["lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_event_overhead"]
 _BENCH_LIB_PATH = os.path.join(os.path.dirname(_LIB_PATH), "liblazyev_bench.so")
@@ -118,6 +118,8 @@ lib.lazyev_set_target_blocks.restype = C.c_int
 lib.lazyev_set_target_blocks.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_set_variant.restype = C.c_int
 lib.lazyev_set_variant.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_set_spin_ticks.restype = C.c_int
+lib.lazyev_set_spin_ticks.argtypes = [C.c_void_p, C.c_uint32]
 lib.lazyev_profile_arm.restype = C.c_int
 lib.lazyev_profile_arm.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_profile_read.restype = C.c_int
@@ -298,6 +300,9 @@ class LazyEviction:
 
     def set_variant(self, variant: int):
         _check(lib.lazyev_set_variant(self._ctx, variant), "lazyev_set_variant")
+
+    def set_spin_ticks(self, ticks: int):
+        _check(lib.lazyev_set_spin_ticks(self._ctx, ticks), "lazyev_set_spin_ticks")
 
     def profile_arm(self, n_calls: int):
         _check(lib.lazyev_profile_arm(self._ctx, n_calls), "lazyev_profile_arm")

@@ -71,7 +71,11 @@ constexpr int kRunMax = 20;             // sub-tiles whose logits a wave keeps i
 struct WaveMap { int first, step, cnt; };
 __host__ __device__ inline WaveMap fused_wave_map(int n_sub, int n_split, int split, int wave) {
   WaveMap m;
+#ifdef LZ_FLIP
+  m.first = (n_split - 1 - split) * kWaves + wave;
+#else
   m.first = split * kWaves + wave;
+#endif
   m.step = kWaves * n_split;
   m.cnt = m.first < n_sub ? (n_sub - m.first + m.step - 1) / m.step : 0;
   return m;
@@ -84,11 +88,17 @@ __host__ __device__ inline int fused_wave_run(int n_sub, int n_split) {
 #ifdef LAZYEV_TIMELINE
 // Measuring build only (liblazyev_timeline.so, see build.py): every block of the LAST launch
 // leaves time stamps of the constant 100 MHz counter: 0 block start, 1 first sub-tile multiplied,
-// 2 end of wave 0's stream, 3 all four waves done, 4 ticket taken, 5 block end; word 7: 1 if the
-// block finished its unit.  Read with lazyev_timeline_read.
+// 2 end of wave 0's stream, 3 all four waves done, 4 ticket taken, 5 block end; word 6: the XCD the
+// block ran on (hardware register XCC_ID); word 7: 1 if the block finished its unit.  Read with
+// lazyev_timeline_read.
 __device__ unsigned long long lz_stamp[2048 * 8];
 #define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 2048) lz_stamp[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
 #define STAMPV(i, v) do { if (threadIdx.x == 0 && blockIdx.x < 2048) lz_stamp[blockIdx.x * 8 + (i)] = (v); } while (0)
+__device__ inline unsigned long long xcc_id() {
+  unsigned x;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+  return x & 15u;
+}
 #else
 #define STAMP(i) do {} while (0)
 #define STAMPV(i, v) do {} while (0)
@@ -379,6 +389,88 @@ __device__ __forceinline__ void load_partials(PartialGroup<4> &g, const float *c
       : "memory");
 }
 
+// Running merge of partials in block order.  Every product and sum is written out with its
+// rounding (no contraction left to the compiler), so that all kernel instances produce the same
+// bits from the same partials.
+struct Merge {
+  float m = -INFINITY, l = 0.f;
+  float o[4] = {0.f, 0.f, 0.f, 0.f};
+  __device__ __forceinline__ void fold(float mj, float lj, const f32x4_t &oj) {
+#pragma clang fp contract(off)
+    const float m_new = fmaxf(m, mj);
+    // a block without entries has max = -inf, sum = 0, values = 0: its factor is 0
+    const float fr = m == -INFINITY ? 0.f : __expf(m - m_new);
+    const float fj = mj == -INFINITY ? 0.f : __expf(mj - m_new);
+    l = fmaf(l, fr, lj * fj);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = fmaf(o[i], fr, oj[i] * fj);
+    m = m_new;
+  }
+};
+
+// The merged row of a unit: thread t writes output elements 4t .. 4t+3 (all of head h) and, as
+// the owner of a head's first elements, the head's softmax statistics for the tracking.
+__device__ __forceinline__ void write_unit_row(const DecodeArgs &a, int unit, const Merge &mg, int e0, int h) {
+  const int G = a.group;
+  if (e0 >= G * D) return;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
+  const float invl = 1.0f / mg.l;
+  u32x2_t w;
+  w[0] = static_cast<unsigned>(float_to_bf16(mg.o[0] * invl)) |
+         (static_cast<unsigned>(float_to_bf16(mg.o[1] * invl)) << 16);
+  w[1] = static_cast<unsigned>(float_to_bf16(mg.o[2] * invl)) |
+         (static_cast<unsigned>(float_to_bf16(mg.o[3] * invl)) << 16);
+  *reinterpret_cast<u32x2_t *>(static_cast<bf16_t *>(a.out) + head0 * D + e0) = w;
+  if (e0 % D == 0) {
+    float *st = a.stat_out + static_cast<size_t>(unit) * (2 * kHeadPad) + 2 * h;
+    st[0] = mg.m;
+    st[1] = invl;
+  }
+}
+
+// ------------------------------------------------ hand-over of partials, units of 2..4 blocks
+// The unit's LAST block (highest block index) always finishes the unit; the others hand their
+// partial over as a record of 64-bit words, each = (number of the launch << 32) | value bits,
+// written and read with 64-bit device-scope atomics.  A word that shows this launch's number
+// holds this launch's value, whatever else is still on its way, so the writer neither waits for
+// its stores nor signals, and the reader needs no second round trip after a flag: it reads the
+// words it needs until all of them carry the number.  Blocks are started in index order and the
+// writers wait for nothing, so the reader's wait ends; it is bounded all the same (spin_ticks of
+// the 100 MHz counter), after which the block raises the workspace's fault word and goes on.
+// Rows 0..3 of 256 words hold the output elements (element 4 t + i of thread t in word
+// i * 256 + t: one store instruction of a wave writes 512 contiguous bytes), row 4 the heads'
+// maxima (words 0..7) and sums (words 8..15).
+constexpr int kRecWords = 5 * kBlock;
+constexpr int kHandOverMax = 4;                    // blocks per unit up to which partials are handed over
+
+__device__ __forceinline__ void rec_store(unsigned long long *p, float v, unsigned seq) {
+  __hip_atomic_store(p, (static_cast<unsigned long long>(seq) << 32) | __float_as_uint(v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+// What one thread reads of another block's record: its four output elements, its head's max and sum.
+struct RecPart { unsigned long long w[6]; };
+__device__ __forceinline__ void rec_load(RecPart &r, const unsigned long long *rec, int t_own, int h) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r.w[i] = __hip_atomic_load(rec + i * kBlock + t_own, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  r.w[4] = __hip_atomic_load(rec + 4 * kBlock + h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  r.w[5] = __hip_atomic_load(rec + 4 * kBlock + kHeadPad + h, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool rec_valid(const RecPart &r, unsigned seq) {
+  bool ok = true;
+#pragma unroll
+  for (int i = 0; i < 6; ++i) ok = ok && static_cast<unsigned>(r.w[i] >> 32) == seq;
+  return ok;
+}
+__device__ __forceinline__ float rec_value(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w)); }
+
+__global__ void clear_records_kernel(unsigned long long *rec, size_t n_words) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n_words;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x)
+    rec[i] = 0;
+}
+
 // Merges the unit's block partials (in block order, so the result does not depend on which
 // block came last) into the output row and stores the unit's softmax statistics.  Thread t
 // owns output elements 4t .. 4t+3 (all of one head); GW partials per memory round trip.
@@ -389,17 +481,14 @@ template <int GW, bool kOwn>
 __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_j, const f32x4_t &own_o,
                             float own_m, float own_l) {
   const int tid = threadIdx.x;
-  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int G = a.group;
-  const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
   const float *ml = a.ws.part_ml + static_cast<size_t>(unit) * a.n_split_max * (2 * G);
   const float *pa = a.ws.part_acc + static_cast<size_t>(unit) * a.n_split_max * (G * D);
   const int e0 = 4 * tid;
   const int ec = min(e0, G * D - 4);               // threads beyond the group's rows load a valid place
   const int h = ec / D;
 
-  float m_run = -INFINITY, l_run = 0.f;
-  float o_run[4] = {0.f, 0.f, 0.f, 0.f};
+  Merge mg;
   for (int j0 = 0; j0 < n_split; j0 += GW) {
     // all loads unconditional (indices clamped to real partials) and issued together
     PartialGroup<GW> g;
@@ -416,30 +505,10 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_
     for (int jj = 0; jj < GW; ++jj) {
       if (j0 + jj >= n_split) break;               // uniform
       if (j0 + jj == own_j) { g.o[jj] = own_o; g.m[jj] = own_m; g.l[jj] = own_l; }   // (never read back)
-      const float m_new = fmaxf(m_run, g.m[jj]);
-      // a block without entries has max = -inf, sum = 0, values = 0: its factor is 0
-      const float fr = m_run == -INFINITY ? 0.f : __expf(m_run - m_new);
-      const float fj = g.m[jj] == -INFINITY ? 0.f : __expf(g.m[jj] - m_new);
-      l_run = l_run * fr + g.l[jj] * fj;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) o_run[i] = o_run[i] * fr + g.o[jj][i] * fj;
-      m_run = m_new;
+      mg.fold(g.m[jj], g.l[jj], g.o[jj]);
     }
   }
-  if (e0 < G * D) {
-    const float invl = 1.0f / l_run;
-    u32x2_t w;
-    w[0] = static_cast<unsigned>(float_to_bf16(o_run[0] * invl)) |
-           (static_cast<unsigned>(float_to_bf16(o_run[1] * invl)) << 16);
-    w[1] = static_cast<unsigned>(float_to_bf16(o_run[2] * invl)) |
-           (static_cast<unsigned>(float_to_bf16(o_run[3] * invl)) << 16);
-    *reinterpret_cast<u32x2_t *>(static_cast<bf16_t *>(a.out) + head0 * D + e0) = w;
-    if (e0 % D == 0) {
-      float *st = a.stat_out + static_cast<size_t>(unit) * (2 * kHeadPad) + 2 * h;
-      st[0] = m_run;
-      st[1] = invl;
-    }
-  }
+  write_unit_row(a, unit, mg, e0, h);
 }
 
 // ------------------------------------------------------------------------------- the kernel
@@ -466,6 +535,9 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
 
   const int G = a.group;
   STAMP(0);
+#ifdef LAZYEV_TIMELINE
+  STAMPV(6, xcc_id());
+#endif
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
@@ -766,6 +838,18 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       l_own = fmaf(f, lsum_lds[w][h_own], l_own);
     }
   }
+  // the block's max and sum of head lane % 8, in every wave (the candidate cuts below, and what
+  // wave 0 stores for the unit's other blocks)
+  const int hh = lane & 7;
+  float mbh = m_lds[0][hh];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, m_lds[w][hh]);
+  float lbh = 0.f;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const float mw = m_lds[w][hh];
+    if (mw != -INFINITY) lbh = fmaf(__expf(mw - mbh), lsum_lds[w][hh], lbh);
+  }
   // what only the NEXT launch needs: the candidate lists of the tracking and the appended row
   auto tail_work = [&]() {
   if (kCompact) {
@@ -773,16 +857,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
     // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the
     // two sides.  Lane h < 8 works out the cut of head h, everybody reads the eight cuts.
-    const int hh = lane & 7;
-    float mbh = m_lds[0][hh];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, m_lds[w][hh]);
-    float lbh = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float mw = m_lds[w][hh];
-      if (mw != -INFINITY) lbh = fmaf(__expf(mw - mbh), lsum_lds[w][hh], lbh);
-    }
     const float cut_h = (hh < G && lbh > 0.f) ? mbh + __logf(0.98f * a.alpha * lbh) : INFINITY;
     float cut[kHeadPad];
 #pragma unroll
@@ -792,32 +866,44 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
                                     static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
     const int e_in = lane & 15;
     const int s0 = kLong ? seg0 : 0;               // (kLong: the earlier segments are done)
-    for (int it0 = s0; it0 < cnt; it0 += 4) {      // four sub-tiles per round, one entry per lane
-      const int it = it0 + (lane >> 4);
+    // four sub-tiles per round, one entry per lane; the logits of all rounds are read first, then
+    // ONE addition to the block's record count reserves the places of all of the wave's records
+    constexpr int kRounds = (kRunMax + 3) / 4;
+    f32x4_t sa[kRounds], sb[kRounds];
+    unsigned long long mask[kRounds];
+    unsigned n_rec = 0;
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      const int it = s0 + 4 * rd + (lane >> 4);
       bool cand = false;
-      int entry = 0;
-      f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = sa;
+      sa[rd] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      sb[rd] = sa[rd];
       if (it < cnt) {
         const float *src = my_logits + (it - s0) * (16 * kHeadPad) + e_in * kHeadPad;
-        sa = *reinterpret_cast<const f32x4_t *>(src);
-        sb = *reinterpret_cast<const f32x4_t *>(src + 4);
-        entry = sub_of(it) * 16 + e_in;
-        cand = sa[0] >= cut[0] || sa[1] >= cut[1] || sa[2] >= cut[2] || sa[3] >= cut[3] ||
-               sb[0] >= cut[4] || sb[1] >= cut[5] || sb[2] >= cut[6];
+        sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
+        sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
+        const int entry = sub_of(it) * 16 + e_in;
+        cand = sa[rd][0] >= cut[0] || sa[rd][1] >= cut[1] || sa[rd][2] >= cut[2] || sa[rd][3] >= cut[3] ||
+               sb[rd][0] >= cut[4] || sb[rd][1] >= cut[5] || sb[rd][2] >= cut[6];
         cand = (cand && entry < n1) || entry == n_old;   // the appended entry starts its tracking there
+        sb[rd][3] = __int_as_float(entry);         // (the 8th place: groups have at most 7 heads here)
       }
-      const unsigned long long mask = __builtin_amdgcn_ballot_w64(cand);
-      if (mask != 0) {                             // wave-uniform
-        unsigned base = 0;
-        if (lane == 0) base = atomicAdd(&cand_total, static_cast<unsigned>(__popcll(mask)));
-        base = __builtin_amdgcn_readfirstlane(base);
-        if (cand) {
-          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
-          sb[3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa;
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb;
+      mask[rd] = __builtin_amdgcn_ballot_w64(cand);
+      n_rec += static_cast<unsigned>(__popcll(mask[rd]));
+    }
+    if (n_rec != 0) {                              // wave-uniform
+      unsigned base = 0;
+      if (lane == 0) base = atomicAdd(&cand_total, n_rec);
+      base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+      for (int rd = 0; rd < kRounds; ++rd) {
+        if ((mask[rd] >> lane) & 1ull) {
+          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa[rd];
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb[rd];
         }
+        base += static_cast<unsigned>(__popcll(mask[rd]));
       }
     }
   }
@@ -831,31 +917,100 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
           reinterpret_cast<const uint4 *>(v_new)[lane - 16];
   }
   };
-  // A unit of one block needs no exchange: its partial is the whole result.
+  // A unit of one block needs no exchange: its partial is the whole result.  Units of up to
+  // kHandOverMax blocks hand their partials over to the unit's last block; longer splits take
+  // tickets and the block with the last one finishes.
   const bool alone = n_split == 1;
-  if (!alone) {
-    // publish the partial with device-scope (write-through) stores, 16 bytes wide for the values
-    const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
-    float *pacc = a.ws.part_acc + part * (G * D);
-    if (e0 < G * D) __asm__ volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pacc + e0), "v"(v_own) : "memory");
-    // (the heads' max and sum all go out from ONE wave: dword stores of several waves into the
-    // one cache line they share were seen to reach a device-scope load late)
-    if (tid < G) {
-      float mb = m_lds[0][tid];
+#ifdef LZ_NO_HANDOVER
+  const bool hand_over = false;
+#else
+  const bool hand_over = n_split >= 2 && n_split <= kHandOverMax;
+#endif
+  const bool finisher = split == n_split - 1;
+  const int t_own = ec >> 2;                       // (threads beyond the group's rows read a valid place)
+  const unsigned long long *recs =
+      a.ws.part_rec + static_cast<size_t>(unit) * ((kHandOverMax - 1) * kRecWords);
+  RecPart r[kHandOverMax - 1];
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) mb = fmaxf(mb, m_lds[w][tid]);
-      float l = 0.f;
+  for (int j = 0; j < kHandOverMax - 1; ++j)
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float mw = m_lds[w][tid];
-        if (mw != -INFINITY) l = fmaf(__expf(mw - mb), lsum_lds[w][tid], l);
+    for (int i = 0; i < 6; ++i) r[j].w[i] = 0;
+  if (hand_over || !alone) {
+    // the heads' max and sum of this block go out from ONE wave (lane h of wave 0 holds head h's):
+    // dword stores of several waves into the one cache line they share were seen to reach a
+    // device-scope load late
+    const float mb = mbh, l = lbh;
+    if (hand_over && !finisher) {
+      unsigned long long *rec = const_cast<unsigned long long *>(recs) + static_cast<size_t>(split) * kRecWords;
+      if (e0 < G * D) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rec_store(rec + i * kBlock + tid, v_own[i], a.seq);
       }
-      float *ml = a.ws.part_ml + part * (2 * G);
-      store_f32_device(ml + tid, mb);
-      store_f32_device(ml + G + tid, l);
+      if (tid < G) {
+        rec_store(rec + 4 * kBlock + tid, mb, a.seq);
+        rec_store(rec + 4 * kBlock + kHeadPad + tid, l, a.seq);
+      }
+    } else if (hand_over) {
+      // a first look at the other blocks' records, requested before the work below
+#pragma unroll
+      for (int j = 0; j < kHandOverMax - 1; ++j)
+        if (j < n_split - 1) rec_load(r[j], recs + static_cast<size_t>(j) * kRecWords, t_own, h_own);
+    } else {
+      // publish the partial with device-scope (write-through) stores, 16 bytes wide for the values
+      const size_t part = static_cast<size_t>(unit) * a.n_split_max + split;
+      float *pacc = a.ws.part_acc + part * (G * D);
+      if (e0 < G * D) __asm__ volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(pacc + e0), "v"(v_own) : "memory");
+      if (tid < G) {
+        float *ml = a.ws.part_ml + part * (2 * G);
+        store_f32_device(ml + tid, mb);
+        store_f32_device(ml + G + tid, l);
+      }
     }
   }
-  tail_work();                                     // (while the partial's stores travel)
+  tail_work();                                     // (while the partial's stores and loads travel)
+  const size_t count_at = (static_cast<size_t>(unit) * a.p_stride +
+                           static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
+  if (hand_over) {
+    if (finisher) {
+      // wait until every word this thread needs carries this launch's number
+      unsigned long long t_first = 0;
+      for (;;) {
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < kHandOverMax - 1; ++j)
+          if (j < n_split - 1) ok = ok && rec_valid(r[j], a.seq);
+        if (ok) break;
+        const unsigned long long now = wall_clock64();
+        if (t_first == 0) {
+          t_first = now;
+        } else if (now - t_first > a.spin_ticks) {
+          atomicOr(a.ws.fault, 1);                 // (cannot happen, see above; the row is then wrong)
+          break;
+        }
+#pragma unroll
+        for (int j = 0; j < kHandOverMax - 1; ++j)
+          if (j < n_split - 1 && !rec_valid(r[j], a.seq))
+            rec_load(r[j], recs + static_cast<size_t>(j) * kRecWords, t_own, h_own);
+      }
+      STAMP(4);
+      Merge mg;                                    // in block order: the others', then this block's own
+#pragma unroll
+      for (int j = 0; j < kHandOverMax - 1; ++j)
+        if (j < n_split - 1) {
+          const f32x4_t oj = {rec_value(r[j].w[0]), rec_value(r[j].w[1]), rec_value(r[j].w[2]), rec_value(r[j].w[3])};
+          mg.fold(rec_value(r[j].w[4]), rec_value(r[j].w[5]), oj);
+        }
+      mg.fold(mb_own, l_own, v_own);
+      write_unit_row(a, unit, mg, e0, h_own);
+    }
+    if (kCompact) {
+      __syncthreads();                             // cand_total is complete
+      if (tid == 0) *reinterpret_cast<int32_t *>(a.logits_out + count_at) = static_cast<int32_t>(cand_total);
+    }
+    STAMPV(7, static_cast<unsigned long long>(finisher));
+    STAMP(5);
+    return;
+  }
   // ---- ticket: the last block of the unit finishes it
   if (!alone) wait_own_stores();                   // every wave's partial stores have completed ...
   __syncthreads();
@@ -866,19 +1021,14 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
                                     __HIP_MEMORY_SCOPE_AGENT);   // ... before its ticket is taken
     last_flag = (prev == n_split - 1);
     if (!alone && prev == n_split - 1) a.ticket[unit] = 0;   // ready for the next launch
-    if (kCompact)
-      *reinterpret_cast<int32_t *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
-                                                   static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad) =
-          static_cast<int32_t>(cand_total);
+    if (kCompact) *reinterpret_cast<int32_t *>(a.logits_out + count_at) = static_cast<int32_t>(cand_total);
   }
   __syncthreads();
   STAMP(4);
   STAMPV(7, static_cast<unsigned long long>(last_flag));
   if (!last_flag) { STAMP(5); return; }
-  // merge the unit's partials (this block's own from its registers) into the output row; two
-  // blocks per unit is the usual split of a short cache: no loads of clamped duplicates
+  // merge the unit's partials (this block's own from its registers) into the output row
   if (alone) finish_unit<2, true>(a, unit, n_split, split, v_own, mb_own, l_own);
-  else if (n_split == 2) finish_unit<2, false>(a, unit, n_split, split, v_own, mb_own, l_own);
   else finish_unit<4, false>(a, unit, n_split, split, v_own, mb_own, l_own);
   STAMP(5);
 }
@@ -896,6 +1046,12 @@ int decode_fused_split_max() { return kFusedSplitMax; }
 int decode_fused_wave_run(int n_sub, int n_split) { return fused_wave_run(n_sub, n_split); }
 int decode_fused_run_max() { return kRunMax; }
 int decode_fused_head_pad() { return kHeadPad; }
+size_t decode_fused_record_bytes() { return static_cast<size_t>(kRecWords) * sizeof(unsigned long long); }
+
+hipError_t launch_clear_records(unsigned long long *rec, size_t n_words, hipStream_t stream) {
+  hipLaunchKernelGGL(clear_records_kernel, dim3(256), dim3(256), 0, stream, rec, n_words);
+  return hipGetLastError();
+}
 
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group) {
   if (n_split < 1 || n_split > kFusedSplitMax || group >= kHeadPad) return false;
@@ -919,6 +1075,7 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   const int units = a.batch * a.n_kv_heads;
   if (a.dtype != 1 || a.head_dim != D || a.group > kHeadPad || a.n_split < 1 ||
       a.n_split > kFusedSplitMax || a.n_split > a.n_split_max || !a.ticket || !a.logits_out ||
+      !a.ws.part_rec || !a.ws.fault || a.seq == 0 ||
       !a.stat_out || a.p_stride < (a.n_old + 16) / 16 * 16 ||
       (a.track.valid && (a.track.units != units || !a.track.logits || !a.track.stat ||
                          a.track.logits == a.logits_out || a.track.stat == a.stat_out)) ||

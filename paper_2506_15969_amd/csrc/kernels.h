@@ -21,6 +21,9 @@ struct Workspace {
   unsigned long long *activations;  // [n_layers][units][slice_max]  running activation counts
   unsigned long long *rows_moved;   // [n_layers][units]             entries an eviction moved to a new slot
   int32_t  *ticket;       // [units]                     fused kernel: blocks of the unit done so far
+  unsigned long long *part_rec;     // [units][3][fused record]  fused kernel, units of 2..4 blocks: the
+                                    // partials of all blocks but the last as stamped records
+  int32_t  *fault;        // [1]                         set when a block gave up waiting for a record
   unsigned long long *hist;         // [LAZYEV_MAX_HIST_BINS]  MRI histogram under construction
 };
 
@@ -88,6 +91,8 @@ struct DecodeArgs {
   Workspace ws;
   unsigned long long *activation_counter;   // this layer's [units][slice_max] counters
   int32_t *ticket;                          // [units], zero between launches
+  uint32_t seq;                             // fused kernel: number of this launch (never 0), the stamp of its records
+  uint32_t spin_ticks;                      // fused kernel: longest wait for a record, in 10 ns ticks
   // fused kernel: where this call's logits and statistics go, and the previous call to track
   float *logits_out, *stat_out;
   TrackArgs track;
@@ -159,6 +164,8 @@ int decode_fused_run_max();
 // stay in LDS to the end of its run, and the 8th logit place is free for the entry index)?
 bool decode_fused_compact_fits(int n_old, int n_split, int p_stride, int group);
 int decode_fused_head_pad();
+size_t decode_fused_record_bytes();           // one stamped record; a unit has 3
+hipError_t launch_clear_records(unsigned long long *rec, size_t n_words, hipStream_t stream);
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 int evict_lds_candidates();   // candidates per unit whose keys the selection keeps in LDS

@@ -39,6 +39,8 @@ struct lazyev_ctx {
   int last_hip_error;
   int device;                       // the device that was current at lazyev_init
   int32_t *static_scratch;          // that device's copy of `scratch` (see static_scratch_of)
+  uint32_t launch_seq;              // fused kernel: launches so far (the stamp of handed-over partials)
+  uint32_t spin_ticks;              // fused kernel: longest wait for such a partial, 10 ns ticks
   // fused kernel: the call whose tracking has not been applied yet, and the buffer pair in turn
   lazyev::TrackArgs pend;
   int cur_buf;
@@ -102,7 +104,7 @@ constexpr int32_t kCompactMinEntries = 1792;
 size_t fused_p_stride(int32_t capacity) { return static_cast<size_t>((capacity + 15) / 16 * 16) + 65 * 64; }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, sel_keys, activations, rows_moved, ticket, hist, slots, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, sel_keys, activations, rows_moved, ticket, records, fault, hist, slots, total;
   int32_t n_split_max;
 };
 
@@ -132,6 +134,10 @@ Layout layout_of(const lazyev_config *c) {
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
+  // fused kernel, units of 2..4 blocks: three stamped records of partials per unit (zero at first:
+  // no launch has the number 0), and the word a block raises when it gives up waiting for one
+  l.records = off; off = align_up(off + units * 3 * lazyev::decode_fused_record_bytes());
+  l.fault = off; off = align_up(off + sizeof(int32_t));
   l.hist = off; off = align_up(off + LAZYEV_MAX_HIST_BINS * sizeof(unsigned long long));
   l.slots = off; off = align_up(off + 3 * static_cast<size_t>(c->batch) * sizeof(int32_t));
   l.total = off;
@@ -317,6 +323,10 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
+  ctx->ws.part_rec = reinterpret_cast<unsigned long long *>(base + l.records);
+  ctx->ws.fault = reinterpret_cast<int32_t *>(base + l.fault);
+  ctx->launch_seq = 0;
+  ctx->spin_ticks = 2000000;           // 20 ms of the 100 MHz counter
   ctx->ws.hist = reinterpret_cast<unsigned long long *>(base + l.hist);
   ctx->dev_slot_prompt = reinterpret_cast<int32_t *>(base + l.slots);
   ctx->dev_slot_t0 = ctx->dev_slot_prompt + cfg->batch;
@@ -327,7 +337,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   if (ctx->chunk > lazyev::decode_chunk_max()) { delete ctx; return LAZYEV_EINVAL; }
   if (static_scratch_of(&ctx->device, &ctx->static_scratch) != hipSuccess) { delete ctx; return LAZYEV_EHIP; }
 
-  // activation counters, moved-row counters and tickets lie next to each other
+  // activation counters, moved-row counters, tickets, records and the fault word lie next to each other
   hipError_t e = hipMemsetAsync(ctx->ws.activations, 0, l.total - l.activations, ctx->stream);
   if (e == hipSuccess)
     e = lazyev::launch_init_state(cfg->ts, cfg->mri, cfg->pos,
@@ -350,6 +360,12 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks) {
   if (!ctx || n_blocks < 1) return LAZYEV_EINVAL;
   ctx->target_blocks = n_blocks;
   ctx->target_blocks_set = true;
+  return LAZYEV_OK;
+}
+
+int lazyev_set_spin_ticks(lazyev_ctx *ctx, uint32_t ticks) {
+  if (!ctx) return LAZYEV_EINVAL;
+  ctx->spin_ticks = ticks;
   return LAZYEV_OK;
 }
 
@@ -450,6 +466,18 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   a.p_out = p_out; a.p_override = p_override;
   a.ws = ctx->ws;
   a.ticket = ctx->ws.ticket;
+  if (kind == 4) {
+    // the number of this launch stamps the partials its blocks hand over; 0 is what the records
+    // hold before any launch, so after a wrap-around they are cleared and the count restarts
+    if (++ctx->launch_seq == 0) {
+      const hipError_t ec = lazyev::launch_clear_records(
+          ctx->ws.part_rec, static_cast<size_t>(ctx->units) * 3 * lazyev::decode_fused_record_bytes() / 8, ctx->stream);
+      if (ec != hipSuccess) return fail_hip(ctx, ec);
+      ctx->launch_seq = 1;
+    }
+    a.seq = ctx->launch_seq;
+    a.spin_ticks = ctx->spin_ticks;
+  }
   a.activation_counter = ctx->ws.activations + static_cast<size_t>(layer) * ctx->units * lazyev::decode_slice_max();
 
   if (kind != 4) {                                 // the other kernels track in the same call
@@ -699,6 +727,12 @@ int lazyev_stats(lazyev_ctx *ctx, lazyev_stats_t *out) {
   if (e != hipSuccess) return fail_hip(ctx, e);
   e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(ctx, e);
+  // did a block of a decode call give up waiting for another block's partial?
+  int32_t fault = 0;
+  e = hipMemcpy(&fault, ctx->ws.fault, sizeof(fault), hipMemcpyDeviceToHost);
+  if (e == hipSuccess && fault != 0) e = hipMemset(ctx->ws.fault, 0, sizeof(fault));
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (fault != 0) return LAZYEV_EEXCHANGE;
   try {
   if (out->n_activations) {
     const size_t per_layer = static_cast<size_t>(ctx->units) * lazyev::decode_slice_max();
@@ -898,6 +932,7 @@ const char *lazyev_strerror(int code) {
     case LAZYEV_EHIP: return "HIP runtime error";
     case LAZYEV_ENOMEM: return "out of host memory";
     case LAZYEV_ESCRATCH: return "shape beyond the static scratch of lazyev_evict_static";
+    case LAZYEV_EEXCHANGE: return "a block of a decode call gave up waiting for another block's partial result";
     default: return "unknown lazyev error code";
   }
 }
