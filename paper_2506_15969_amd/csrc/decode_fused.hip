@@ -827,16 +827,16 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   for (int w = 1; w < kWaves; ++w) mb_own = fmaxf(mb_own, m_lds[w][h_own]);
   float l_own = 0.f;
   f32x4_t v_own = {0.f, 0.f, 0.f, 0.f};
+  // (no branches from here on where a select does: this phase is a single wave per SIMD running
+  // serial code, every instruction counts)
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
     const float mw = m_lds[w][h_own];
-    if (mw != -INFINITY) {
-      const float f = __expf(mw - mb_own);
-      const f32x4_t x = *reinterpret_cast<const f32x4_t *>(acc_lds + w * (8 * D) + ec);
+    const float f = mw == -INFINITY ? 0.f : __expf(mw - mb_own);   // a wave without entries: factor 0
+    const f32x4_t x = *reinterpret_cast<const f32x4_t *>(acc_lds + w * (8 * D) + ec);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) v_own[i] = fmaf(f, x[i], v_own[i]);
-      l_own = fmaf(f, lsum_lds[w][h_own], l_own);
-    }
+    for (int i = 0; i < 4; ++i) v_own[i] = fmaf(f, x[i], v_own[i]);
+    l_own = fmaf(f, lsum_lds[w][h_own], l_own);
   }
   // the block's max and sum of head lane % 8, in every wave (the candidate cuts below, and what
   // wave 0 stores for the unit's other blocks)
@@ -848,7 +848,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
     const float mw = m_lds[w][hh];
-    if (mw != -INFINITY) lbh = fmaf(__expf(mw - mbh), lsum_lds[w][hh], lbh);
+    lbh = fmaf(mw == -INFINITY ? 0.f : __expf(mw - mbh), lsum_lds[w][hh], lbh);
   }
   // what only the NEXT launch needs: the candidate lists of the tracking and the appended row
   auto tail_work = [&]() {
@@ -872,22 +872,26 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     f32x4_t sa[kRounds], sb[kRounds];
     unsigned long long mask[kRounds];
     unsigned n_rec = 0;
+    if (cnt > s0) {                                // wave-uniform
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      // (reads of a round beyond the run are clamped to its last sub-tile and not used)
+      const int it = s0 + 4 * rd + (lane >> 4);
+      const int itc = min(it, cnt - 1);
+      const float *src = my_logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
+      sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
+      sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
+    }
 #pragma unroll
     for (int rd = 0; rd < kRounds; ++rd) {
       const int it = s0 + 4 * rd + (lane >> 4);
-      bool cand = false;
-      sa[rd] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-      sb[rd] = sa[rd];
-      if (it < cnt) {
-        const float *src = my_logits + (it - s0) * (16 * kHeadPad) + e_in * kHeadPad;
-        sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
-        sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
-        const int entry = sub_of(it) * 16 + e_in;
-        cand = sa[rd][0] >= cut[0] || sa[rd][1] >= cut[1] || sa[rd][2] >= cut[2] || sa[rd][3] >= cut[3] ||
-               sb[rd][0] >= cut[4] || sb[rd][1] >= cut[5] || sb[rd][2] >= cut[6];
-        cand = (cand && entry < n1) || entry == n_old;   // the appended entry starts its tracking there
-        sb[rd][3] = __int_as_float(entry);         // (the 8th place: groups have at most 7 heads here)
-      }
+      const int entry = sub_of(it) * 16 + e_in;
+      // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
+      const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
+                            fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
+      // (the appended entry starts its tracking there, so it always goes along)
+      const bool cand = (it < cnt) & (((d >= 0.f) & (entry < n1)) | (entry == n_old));
+      sb[rd][3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
       mask[rd] = __builtin_amdgcn_ballot_w64(cand);
       n_rec += static_cast<unsigned>(__popcll(mask[rd]));
     }
@@ -905,6 +909,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
         }
         base += static_cast<unsigned>(__popcll(mask[rd]));
       }
+    }
     }
   }
   // the appended row goes to slot N (everybody read it from k_new / v_new)
