@@ -533,7 +533,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   __shared__ unsigned cand_total;                  // candidate records of this block so far
   __shared__ float run_lse[kWaves][kHeadPad];      // kLong: each wave's latest log-sum-exp per head (one word: no torn reads)
 
-  const int G = a.group;
   STAMP(0);
 #ifdef LAZYEV_TIMELINE
   STAMPV(6, xcc_id());
@@ -571,17 +570,15 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   }
   const int c = lane & 15, g = lane >> 4;
   const int unit = blockIdx.x / n_split, split = blockIdx.x % n_split;
-  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
-  const int hc = min(c, G - 1);
   int n_old = n_old_call;
   if (slots_on) {                                  // per-sequence timing: this unit's own length
-    const int32_t P = a.slots.prompt_len[seq], tau = a.t - a.slots.t0[seq];
+    const int seq_s = unit / a.n_kv_heads;
+    const int32_t P = a.slots.prompt_len[seq_s], tau = a.t - a.slots.t0[seq_s];
     if (P < 0 || tau < 1) return;                  // the whole unit sits this call out
     n_old = slot_n_old(P, tau, a.slots.budget, a.slots.window);
   }
   const int n1 = n_old + 1;
   const int n_sub = (n1 + 15) >> 4;
-  const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
 
   // this wave's sub-tiles (fused_wave_map)
   const WaveMap wm = fused_wave_map(n_sub, n_split, split, wave);
@@ -592,24 +589,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   const bf16_t *vc = v_cache + static_cast<size_t>(unit) * capacity * D;
   const bf16_t *k_new = k_new_all + static_cast<size_t>(unit) * D;
   const bf16_t *v_new = v_new_all + static_cast<size_t>(unit) * D;
-  const bf16_t *q_row = static_cast<const bf16_t *>(a.q) + (head0 + hc) * D + g * 8;
-  const int run = min(fused_wave_run(n_sub, n_split), kRunMax);
-  float *my_logits = logit_lds + static_cast<size_t>(wave) * run * (16 * kHeadPad);
-  int seg0 = 0;                                    // first of this wave's sub-tiles whose logits are still in LDS
-  float *logits_out = a.logits_out + static_cast<size_t>(unit) * a.p_stride * kHeadPad;
-
-  float m_ref = -INFINITY, lsum = 0.f;
-  f32x4_t o[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  // B operand of the logits: Q^T, head c (zero rows beyond the group)
-  u32x4_t qb[KC];
-#pragma unroll
-  for (int kk = 0; kk < KC; ++kk) {
-    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(q_row + kk * 32);
-    qb[kk] = c < G ? v : u32x4_t{0, 0, 0, 0};
-  }
 
   auto load_k = [&](SubTile &t, int it) {
     const int sub = sub_of(it);
@@ -630,6 +609,33 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       t.v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(src + c * 8));
     }
   };
+  // ---- the stream starts here: the first sub-tile is requested with what the wave was handed
+  // in registers, before anything is read from the argument block in memory
+  SubTile buf;
+  if (cnt > 0) { load_k(buf, 0); load_v(buf, 0); }
+
+  const int G = a.group;
+  const int seq = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const int hc = min(c, G - 1);
+  const size_t head0 = static_cast<size_t>(seq) * a.n_q_heads + static_cast<size_t>(kvh) * G;
+  const bf16_t *q_row = static_cast<const bf16_t *>(a.q) + (head0 + hc) * D + g * 8;
+  const int run = min(fused_wave_run(n_sub, n_split), kRunMax);
+  float *my_logits = logit_lds + static_cast<size_t>(wave) * run * (16 * kHeadPad);
+  int seg0 = 0;                                    // first of this wave's sub-tiles whose logits are still in LDS
+  float *logits_out = a.logits_out + static_cast<size_t>(unit) * a.p_stride * kHeadPad;
+
+  float m_ref = -INFINITY, lsum = 0.f;
+  f32x4_t o[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // B operand of the logits: Q^T, head c (zero rows beyond the group)
+  u32x4_t qb[KC];
+#pragma unroll
+  for (int kk = 0; kk < KC; ++kk) {
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(q_row + kk * 32);
+    qb[kk] = c < G ? v : u32x4_t{0, 0, 0, 0};
+  }
 
   // kMore (a std::bool_constant): the wave has a sub-tile after this one and requests it here
   auto compute = [&](SubTile &t, int it, auto more_tag) {
@@ -703,9 +709,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     if constexpr (kMore) load_v(t, it + 1);
   };
 
-  SubTile buf;
-  // ---- the stream
-  if (cnt > 0) { load_k(buf, 0); load_v(buf, 0); }
   // this wave's logits -> workspace, 512 bytes per sub-tile: when the run ends, and for a
   // long run every kRunMax sub-tiles
   auto flush = [&](int it0, int it1) {
