@@ -50,7 +50,7 @@ int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);
  * others; the wait is bounded by `ticks` of the GPU's constant 100 MHz counter (default 2000000
  * = 20 ms; the others never wait themselves, so the bound is not reached).  When it is, the block
  * goes on with what it has and the next lazyev_stats returns LAZYEV_EEXCHANGE.  0 makes a block
- * give up at its second look (a test of that path).  Errors: EINVAL. */
+ * give up when its first look finds a partial missing (a test of that path).  Errors: EINVAL. */
 int lazyev_set_spin_ticks(lazyev_ctx *ctx, uint32_t ticks);
 
 /* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels

@@ -989,10 +989,9 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
           if (j < n_split - 1) ok = ok && rec_valid(r[j], a.seq);
         if (ok) break;
         const unsigned long long now = wall_clock64();
-        if (t_first == 0) {
-          t_first = now;
-        } else if (now - t_first > a.spin_ticks) {
-          atomicOr(a.ws.fault, 1);                 // (cannot happen, see above; the row is then wrong)
+        if (t_first == 0) t_first = now;
+        if (now - t_first >= a.spin_ticks) {       // (a limit of 0: no second look)
+          atomicOr(a.ws.fault, 1);                 // (cannot happen otherwise, see above; the row is then wrong)
           break;
         }
 #pragma unroll

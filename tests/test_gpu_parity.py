@@ -48,12 +48,14 @@ def test_cfg1_fp32_every_unit_every_step(lazyev_lib, mode):
 @pytest.mark.parametrize("mode,variant,knob", [("e2e", 0, 128), ("e2e", 0, 64), ("oracle_p", 0, 128),
                                                ("synthetic", 0, 256),
                                                ("e2e", 4, 8), ("e2e", 4, 16), ("e2e", 4, 24),
+                                               ("e2e", 4, 32), ("e2e", 4, 40),
                                                ("e2e", 4, 1000), ("oracle_p", 4, 32),
                                                ("synthetic", 4, 40)])
 def test_cfg2_shapes_scaled_down(lazyev_lib, mode, variant, knob):
     """bf16, 28/4 heads, d=128; cache up to 170+32 entries (7 tiles of 32, ragged tail).
-    variant 4 is the single-launch MFMA kernel, `knob` its target block count (8 units: 1, 2, 3
-    blocks per unit, and as many as the cache length allows: waves with one or no sub-tile);
+    variant 4 is the single-launch MFMA kernel, `knob` its target block count (8 units: 1, 2, 3,
+    4, 5 blocks per unit: alone, partials handed over to the unit's last block, tickets; and as
+    many as the cache length allows: waves with one or no sub-tile);
     variant 0 is the vector-ALU kernel, `knob` its chunk."""
     from lockstep import run_lockstep
     cfg = CONFIGS["cfg2"].scaled(batch=2, prompt_len=100, steps=330, budget=170, window=32,
@@ -195,6 +197,33 @@ def test_two_runs_are_bitwise_identical(lazyev_lib, variant):
     for x, y in zip(state_a, state_b):                   # caches and recurrence state: bitwise
         assert torch.equal(x, y)
     assert torch.equal(out_a, out_b)
+
+
+def test_hand_over_of_partials_reports_a_wait_that_ends(lazyev_lib):
+    """Units of 2..4 blocks: the unit's last block waits (bounded) for the other blocks' partials.
+    With the limit at 0 a block gives up as soon as a look finds a partial missing; every kernel
+    still ends, the next lazyev_stats says so once, and with the limit back the engine goes on
+    and reports nothing."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=1, batch=8, prompt_len=600, steps=60, budget=1024, window=32)
+    wl = Workload(cfg)
+    eng = make_engine(lazyev_lib, cfg, wl, variant=4, target_blocks=2 * cfg.batch * cfg.n_kv_heads)
+    out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+    q, kn, vn = wl.step_inputs(0, 1, cfg.steps + 1, device="cuda")
+    eng.set_spin_ticks(0)
+    for t in range(1, 41):
+        eng.decode_step(0, t, q[t - 1], kn[t - 1], vn[t - 1], out)
+    torch.cuda.synchronize()
+    with pytest.raises(lazyev_lib.LazyevError) as err:
+        eng.stats()
+    assert err.value.code == lazyev_lib.EEXCHANGE
+    eng.set_spin_ticks(2000000)
+    assert eng.stats()["len"][0] == 640                  # reported once
+    for t in range(41, 61):
+        eng.decode_step(0, t, q[t - 1], kn[t - 1], vn[t - 1], out)
+    assert eng.stats()["len"][0] == 660
+    eng.close()
 
 
 @pytest.mark.parametrize("blocks", [8, 24, 1000])
