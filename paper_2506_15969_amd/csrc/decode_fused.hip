@@ -520,8 +520,14 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_
 // in LDS; every kRunMax sub-tiles it then writes the candidates among them, found with the cut
 // that the block's four waves' running statistics give at that moment (a lower bound of the
 // final denominator at any time, so the cut only errs towards more candidates).
+// A call that leaves candidate lists runs blocks of 2 * kWaves waves: the second four ("list
+// waves") sleep at the block barrier while the first four stream, and then build the candidate
+// lists from the logits in LDS while the first four merge, exchange and finish the unit; that
+// phase is serial code of one wave per SIMD, so a second wave per SIMD nearly halves it.  Both
+// block sizes keep to 128 registers per lane, so that a stream block and a tracking block fit a
+// compute unit together.
 template <bool kCompact, bool kLong = false>
-__global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
+__global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fused_kernel(
     const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split, const int capacity,
     const int units_call, const int slots_on, const DecodeArgs a) {
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
@@ -540,6 +546,7 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
+    if (kCompact && threadIdx.x >= kBlock) return;  // (the tracking has no use for list waves)
     const int tb = blockIdx.x - n_split * units_call;
     const int unit = tb / n_split, part = tb % n_split;
     TrackArgs k;
@@ -579,6 +586,117 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
   }
   const int n1 = n_old + 1;
   const int n_sub = (n1 + 15) >> 4;
+  // A unit of one block needs no exchange: its partial is the whole result.  Units of up to
+  // kHandOverMax blocks hand their partials over to the unit's last block; longer splits take
+  // tickets and the block with the last one finishes.
+  const bool alone = n_split == 1;
+#ifdef LZ_NO_HANDOVER
+  const bool hand_over = false;
+#else
+  const bool hand_over = n_split >= 2 && n_split <= kHandOverMax;
+#endif
+
+  // ---- candidates of the tracking among the sub-tiles s0 .. cnt_w - 1 of a wave's run (`wmap`),
+  // whose logits lie at `logits` in LDS: the entries that can reach alpha in some head.
+  // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
+  // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the two
+  // sides.  Lane h < 8 works out the cut of head h, everybody reads the eight cuts.  (After the
+  // block barrier that follows the stream.)
+  auto scan_candidates = [&](const float *logits, int cnt_w, int s0, const WaveMap &wmap, int group, float alpha,
+                             float *region) {
+    const int hh = lane & 7;
+    float mbh = m_lds[0][hh];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, m_lds[w][hh]);
+    float lbh = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float mw = m_lds[w][hh];
+      lbh = fmaf(mw == -INFINITY ? 0.f : __expf(mw - mbh), lsum_lds[w][hh], lbh);
+    }
+    const float cut_h = (hh < group && lbh > 0.f) ? mbh + __logf(0.98f * alpha * lbh) : INFINITY;
+    float cut[kHeadPad];
+#pragma unroll
+    for (int h = 0; h < kHeadPad; ++h)
+      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
+    const int e_in = lane & 15;
+    // four sub-tiles per round, one entry per lane; the logits of all rounds are read first, then
+    // ONE addition to the block's record count reserves the places of all of the wave's records
+    constexpr int kRounds = (kRunMax + 3) / 4;
+    f32x4_t sa[kRounds], sb[kRounds];
+    unsigned long long mask[kRounds];
+    unsigned n_rec = 0;
+    if (cnt_w <= s0) return;                       // wave-uniform
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      // (reads of a round beyond the run are clamped to its last sub-tile and not used)
+      const int it = s0 + 4 * rd + (lane >> 4);
+      const int itc = min(it, cnt_w - 1);
+      const float *src = logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
+      sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
+      sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
+    }
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      const int it = s0 + 4 * rd + (lane >> 4);
+      const int entry = (wmap.first + it * wmap.step) * 16 + e_in;
+      // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
+      const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
+                            fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
+      // (the appended entry starts its tracking there, so it always goes along)
+      const bool cand = (it < cnt_w) & (((d >= 0.f) & (entry < n1)) | (entry == n_old));
+      sb[rd][3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
+      mask[rd] = __builtin_amdgcn_ballot_w64(cand);
+      n_rec += static_cast<unsigned>(__popcll(mask[rd]));
+    }
+    if (n_rec != 0) {                              // wave-uniform
+      unsigned base = 0;
+      if (lane == 0) base = atomicAdd(&cand_total, n_rec);
+      base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+      for (int rd = 0; rd < kRounds; ++rd) {
+        if ((mask[rd] >> lane) & 1ull) {
+          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa[rd];
+          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb[rd];
+        }
+        base += static_cast<unsigned>(__popcll(mask[rd]));
+      }
+    }
+  };
+  // the appended row goes to slot N (the stream waves read it from k_new / v_new)
+  auto append_row = [&]() {
+    const bf16_t *kn = k_new_all + static_cast<size_t>(unit) * D, *vn = v_new_all + static_cast<size_t>(unit) * D;
+    bf16_t *ku = const_cast<bf16_t *>(k_cache) + static_cast<size_t>(unit) * capacity * D;
+    bf16_t *vu = const_cast<bf16_t *>(v_cache) + static_cast<size_t>(unit) * capacity * D;
+    if (lane < 16)
+      reinterpret_cast<uint4 *>(ku + static_cast<size_t>(n_old) * D)[lane] = reinterpret_cast<const uint4 *>(kn)[lane];
+    else if (lane < 32)
+      reinterpret_cast<uint4 *>(vu + static_cast<size_t>(n_old) * D)[lane - 16] = reinterpret_cast<const uint4 *>(vn)[lane - 16];
+  };
+
+  if (kCompact && wave >= kWaves) {
+    // ---- list wave kWaves + w: everything it needs is worked out now, then it sleeps at the
+    // barrier that ends the stream and scans what stream wave w left in LDS (for a long run: the
+    // last segment; the earlier ones went out while the wave streamed)
+    const int w = wave - kWaves;
+    const WaveMap wmap = fused_wave_map(n_sub, n_split, split, w);
+    const int s0 = (kLong && wmap.cnt > 0) ? (wmap.cnt - 1) / kRunMax * kRunMax : 0;
+    const int run_w = min(fused_wave_run(n_sub, n_split), kRunMax);
+    const float *logits = logit_lds + static_cast<size_t>(w) * run_w * (16 * kHeadPad);
+    const int group = a.group;
+    const float alpha = a.alpha;
+    float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
+    __asm__ volatile("" ::"s"(group), "s"(alpha), "s"(region));   // (fetched before the barrier, not after)
+    __syncthreads();                               // the stream has ended, the waves' statistics are in LDS
+    scan_candidates(logits, wmap.cnt, s0, wmap, group, alpha, region);
+    if (split == 0 && w == 1) append_row();
+    __syncthreads();                               // cand_total is complete
+    if (!hand_over) __syncthreads();               // (the ticket route has one more)
+    return;
+  }
 
   // this wave's sub-tiles (fused_wave_map)
   const WaveMap wm = fused_wave_map(n_sub, n_split, split, wave);
@@ -841,8 +959,8 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     for (int i = 0; i < 4; ++i) v_own[i] = fmaf(f, x[i], v_own[i]);
     l_own = fmaf(f, lsum_lds[w][h_own], l_own);
   }
-  // the block's max and sum of head lane % 8, in every wave (the candidate cuts below, and what
-  // wave 0 stores for the unit's other blocks)
+  // the block's max and sum of head lane % 8 (what lanes 0 .. G - 1 of wave 0 store for the unit's
+  // other blocks)
   const int hh = lane & 7;
   float mbh = m_lds[0][hh];
 #pragma unroll
@@ -853,87 +971,6 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
     const float mw = m_lds[w][hh];
     lbh = fmaf(mw == -INFINITY ? 0.f : __expf(mw - mbh), lsum_lds[w][hh], lbh);
   }
-  // what only the NEXT launch needs: the candidate lists of the tracking and the appended row
-  auto tail_work = [&]() {
-  if (kCompact) {
-    // ---- candidates of the tracking: this wave's entries that can reach alpha in some head.
-    // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
-    // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the
-    // two sides.  Lane h < 8 works out the cut of head h, everybody reads the eight cuts.
-    const float cut_h = (hh < G && lbh > 0.f) ? mbh + __logf(0.98f * a.alpha * lbh) : INFINITY;
-    float cut[kHeadPad];
-#pragma unroll
-    for (int h = 0; h < kHeadPad; ++h)
-      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
-    float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
-                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
-    const int e_in = lane & 15;
-    const int s0 = kLong ? seg0 : 0;               // (kLong: the earlier segments are done)
-    // four sub-tiles per round, one entry per lane; the logits of all rounds are read first, then
-    // ONE addition to the block's record count reserves the places of all of the wave's records
-    constexpr int kRounds = (kRunMax + 3) / 4;
-    f32x4_t sa[kRounds], sb[kRounds];
-    unsigned long long mask[kRounds];
-    unsigned n_rec = 0;
-    if (cnt > s0) {                                // wave-uniform
-#pragma unroll
-    for (int rd = 0; rd < kRounds; ++rd) {
-      // (reads of a round beyond the run are clamped to its last sub-tile and not used)
-      const int it = s0 + 4 * rd + (lane >> 4);
-      const int itc = min(it, cnt - 1);
-      const float *src = my_logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
-      sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
-      sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
-    }
-#pragma unroll
-    for (int rd = 0; rd < kRounds; ++rd) {
-      const int it = s0 + 4 * rd + (lane >> 4);
-      const int entry = sub_of(it) * 16 + e_in;
-      // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
-      const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
-                            fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
-      // (the appended entry starts its tracking there, so it always goes along)
-      const bool cand = (it < cnt) & (((d >= 0.f) & (entry < n1)) | (entry == n_old));
-      sb[rd][3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
-      mask[rd] = __builtin_amdgcn_ballot_w64(cand);
-      n_rec += static_cast<unsigned>(__popcll(mask[rd]));
-    }
-    if (n_rec != 0) {                              // wave-uniform
-      unsigned base = 0;
-      if (lane == 0) base = atomicAdd(&cand_total, n_rec);
-      base = __builtin_amdgcn_readfirstlane(base);
-#pragma unroll
-      for (int rd = 0; rd < kRounds; ++rd) {
-        if ((mask[rd] >> lane) & 1ull) {
-          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa[rd];
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb[rd];
-        }
-        base += static_cast<unsigned>(__popcll(mask[rd]));
-      }
-    }
-    }
-  }
-  // the appended row goes to slot N (everybody read it from k_new / v_new)
-  if (split == 0 && wave == 1) {
-    if (lane < 16)
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(kc) + static_cast<size_t>(n_old) * D)[lane] =
-          reinterpret_cast<const uint4 *>(k_new)[lane];
-    else if (lane < 32)
-      reinterpret_cast<uint4 *>(const_cast<bf16_t *>(vc) + static_cast<size_t>(n_old) * D)[lane - 16] =
-          reinterpret_cast<const uint4 *>(v_new)[lane - 16];
-  }
-  };
-  // A unit of one block needs no exchange: its partial is the whole result.  Units of up to
-  // kHandOverMax blocks hand their partials over to the unit's last block; longer splits take
-  // tickets and the block with the last one finishes.
-  const bool alone = n_split == 1;
-#ifdef LZ_NO_HANDOVER
-  const bool hand_over = false;
-#else
-  const bool hand_over = n_split >= 2 && n_split <= kHandOverMax;
-#endif
   const bool finisher = split == n_split - 1;
   const int t_own = ec >> 2;                       // (threads beyond the group's rows read a valid place)
   const unsigned long long *recs =
@@ -975,7 +1012,8 @@ __global__ __launch_bounds__(kBlock, 3) void decode_fused_kernel(
       }
     }
   }
-  tail_work();                                     // (while the partial's stores and loads travel)
+  // (a call that leaves candidate lists has its list waves do this and the lists meanwhile)
+  if (!kCompact && split == 0 && wave == 1) append_row();
   const size_t count_at = (static_cast<size_t>(unit) * a.p_stride +
                            static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
   if (hand_over) {
@@ -1101,10 +1139,10 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   const int slots_on = a.slots.prompt_len ? 1 : 0;
   const bool long_run = fused_wave_run(n_sub, a.n_split) > kRunMax;
   if (a.variant == 6 && long_run)
-    hipLaunchKernelGGL((decode_fused_kernel<true, true>), dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
+    hipLaunchKernelGGL((decode_fused_kernel<true, true>), dim3(sb + (a.track.valid ? sb : 0)), dim3(2 * kBlock), lds_all, stream,
                        kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
   else if (a.variant == 6)
-    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
+    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(2 * kBlock), lds_all, stream,
                        kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
   else
     hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
