@@ -34,14 +34,13 @@ int lazyev_set_target_blocks(lazyev_ctx *ctx, int32_t n_blocks);
  *   0  vector-ALU split kernel + merge kernel (any supported shape; the only one for fp32 or
  *      head_dim 64);
  *   4  one launch: MFMA stream blocks, the block that finishes a unit last merges the partials
- *      into the output; the tracking rides with the next launch (bf16, head_dim 128).  Over a
- *      cache of 1792 entries or more a block leaves only the logits of entries that can still
- *      reach alpha for the tracking; it leaves all of them over a shorter cache, when the
- *      caller passes p_out / p_override, with LAZYEV_SCORE_CURRENT_ATTENTION, or with 8 query
- *      heads per KV head;
- *   5  kernel 4 leaving every logit in all cases, 6 kernel 4 leaving only those of the entries
- *      that can reach alpha also over short caches (same results bit for bit; for comparison
- *      and tests);
+ *      into the output; the tracking rides with the next launch (bf16, head_dim 128).  A block
+ *      leaves only the logits of entries that can still reach alpha for the tracking; it leaves
+ *      all of them when the caller passes p_out / p_override, with
+ *      LAZYEV_SCORE_CURRENT_ATTENTION, or with 8 query heads per KV head;
+ *   5  kernel 4 leaving every logit of a call in the workspace for the tracking, 6 kernel 4
+ *      leaving only those of the entries that can reach alpha (what 4 does whenever nobody reads
+ *      the logits as such; same results bit for bit; for comparison and tests);
  *   1  (default) picks 4 when it applies, else 0.
  * 2 and 3 are not assigned.  Errors: EINVAL. */
 int lazyev_set_variant(lazyev_ctx *ctx, int32_t variant);

@@ -65,16 +65,19 @@ constexpr int kTrackRows = 3;           // entries per thread per tracking batch
 constexpr int kHeadPad = 8;             // logits and statistics are stored for 8 heads per unit
 constexpr int kRunMax = 20;             // sub-tiles whose logits a wave keeps in LDS (10 KB) before it writes them out
 // How a unit's n_sub sub-tiles of 16 entries are dealt to the kWaves * n_split waves of its
-// n_split blocks: wave wv (= kWaves * split + wave) takes wv, wv + kWaves * n_split, ..., so the
-// waves of a unit read one moving window of the cache together (measured against a region of
-// consecutive sub-tiles per block: 28.6 against 29.2 us per call on the 2048-entry workload).
+// n_split blocks: wave wv (= kWaves * (n_split - 1 - split) + wave) takes wv, wv + kWaves * n_split,
+// ..., so the waves of a unit read one moving window of the cache together (measured against a
+// region of consecutive sub-tiles per block: 28.6 against 29.2 us per call on the 2048-entry
+// workload).  The unit's LAST block comes first in that order: when the sub-tiles do not divide
+// evenly its waves take the longer runs, and it is the block that finishes a unit of 2..4 blocks,
+// so the other blocks' partials are on their way while it still streams.
 struct WaveMap { int first, step, cnt; };
 __host__ __device__ inline WaveMap fused_wave_map(int n_sub, int n_split, int split, int wave) {
   WaveMap m;
 #ifdef LZ_FLIP
   m.first = (n_split - 1 - split) * kWaves + wave;
 #else
-  m.first = split * kWaves + wave;
+  m.first = (n_split - 1 - split) * kWaves + wave;
 #endif
   m.step = kWaves * n_split;
   m.cnt = m.first < n_sub ? (n_sub - m.first + m.step - 1) / m.step : 0;
@@ -596,76 +599,7 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
   const bool hand_over = n_split >= 2 && n_split <= kHandOverMax;
 #endif
 
-  // ---- candidates of the tracking among the sub-tiles s0 .. cnt_w - 1 of a wave's run (`wmap`),
-  // whose logits lie at `logits` in LDS: the entries that can reach alpha in some head.
-  // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
-  // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the two
-  // sides.  Lane h < 8 works out the cut of head h, everybody reads the eight cuts.  (After the
-  // block barrier that follows the stream.)
-  auto scan_candidates = [&](const float *logits, int cnt_w, int s0, const WaveMap &wmap, int group, float alpha,
-                             float *region) {
-    const int hh = lane & 7;
-    float mbh = m_lds[0][hh];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) mbh = fmaxf(mbh, m_lds[w][hh]);
-    float lbh = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float mw = m_lds[w][hh];
-      lbh = fmaf(mw == -INFINITY ? 0.f : __expf(mw - mbh), lsum_lds[w][hh], lbh);
-    }
-    const float cut_h = (hh < group && lbh > 0.f) ? mbh + __logf(0.98f * alpha * lbh) : INFINITY;
-    float cut[kHeadPad];
-#pragma unroll
-    for (int h = 0; h < kHeadPad; ++h)
-      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
-    const int e_in = lane & 15;
-    // four sub-tiles per round, one entry per lane; the logits of all rounds are read first, then
-    // ONE addition to the block's record count reserves the places of all of the wave's records
-    constexpr int kRounds = (kRunMax + 3) / 4;
-    f32x4_t sa[kRounds], sb[kRounds];
-    unsigned long long mask[kRounds];
-    unsigned n_rec = 0;
-    if (cnt_w <= s0) return;                       // wave-uniform
-#pragma unroll
-    for (int rd = 0; rd < kRounds; ++rd) {
-      // (reads of a round beyond the run are clamped to its last sub-tile and not used)
-      const int it = s0 + 4 * rd + (lane >> 4);
-      const int itc = min(it, cnt_w - 1);
-      const float *src = logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
-      sa[rd] = *reinterpret_cast<const f32x4_t *>(src);
-      sb[rd] = *reinterpret_cast<const f32x4_t *>(src + 4);
-    }
-#pragma unroll
-    for (int rd = 0; rd < kRounds; ++rd) {
-      const int it = s0 + 4 * rd + (lane >> 4);
-      const int entry = (wmap.first + it * wmap.step) * 16 + e_in;
-      // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
-      const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
-                            fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
-      // (the appended entry starts its tracking there, so it always goes along)
-      const bool cand = (it < cnt_w) & (((d >= 0.f) & (entry < n1)) | (entry == n_old));
-      sb[rd][3] = __int_as_float(entry);           // (the 8th place: groups have at most 7 heads here)
-      mask[rd] = __builtin_amdgcn_ballot_w64(cand);
-      n_rec += static_cast<unsigned>(__popcll(mask[rd]));
-    }
-    if (n_rec != 0) {                              // wave-uniform
-      unsigned base = 0;
-      if (lane == 0) base = atomicAdd(&cand_total, n_rec);
-      base = __builtin_amdgcn_readfirstlane(base);
-#pragma unroll
-      for (int rd = 0; rd < kRounds; ++rd) {
-        if ((mask[rd] >> lane) & 1ull) {
-          const unsigned at = 1 + base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad) = sa[rd];
-          *reinterpret_cast<f32x4_t *>(region + static_cast<size_t>(at) * kHeadPad + 4) = sb[rd];
-        }
-        base += static_cast<unsigned>(__popcll(mask[rd]));
-      }
-    }
-  };
-  // the appended row goes to slot N (the stream waves read it from k_new / v_new)
+  // the appended row goes to slot N (the stream waves read it from k_new / v_new, nobody from the slot)
   auto append_row = [&]() {
     const bf16_t *kn = k_new_all + static_cast<size_t>(unit) * D, *vn = v_new_all + static_cast<size_t>(unit) * D;
     bf16_t *ku = const_cast<bf16_t *>(k_cache) + static_cast<size_t>(unit) * capacity * D;
@@ -677,22 +611,94 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
   };
 
   if (kCompact && wave >= kWaves) {
-    // ---- list wave kWaves + w: everything it needs is worked out now, then it sleeps at the
-    // barrier that ends the stream and scans what stream wave w left in LDS (for a long run: the
-    // last segment; the earlier ones went out while the wave streamed)
+    // ---- list wave kWaves + w: the candidates of the tracking among the sub-tiles that stream
+    // wave w leaves in LDS (for a long run: the last segment; the earlier ones went out while the
+    // wave streamed), i.e. the entries that can reach alpha in some head.
+    // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
+    // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the two
+    // sides.  Everything that does not depend on the logits is worked out now; then the wave
+    // sleeps at the barrier that ends the stream.
     const int w = wave - kWaves;
+    if (split == 0 && w == 1) append_row();
     const WaveMap wmap = fused_wave_map(n_sub, n_split, split, w);
-    const int s0 = (kLong && wmap.cnt > 0) ? (wmap.cnt - 1) / kRunMax * kRunMax : 0;
+    const int cnt_w = wmap.cnt;
+    const int s0 = (kLong && cnt_w > 0) ? (cnt_w - 1) / kRunMax * kRunMax : 0;
     const int run_w = min(fused_wave_run(n_sub, n_split), kRunMax);
     const float *logits = logit_lds + static_cast<size_t>(w) * run_w * (16 * kHeadPad);
     const int group = a.group;
-    const float alpha = a.alpha;
-    float *region = a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
-                                    static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
-    __asm__ volatile("" ::"s"(group), "s"(alpha), "s"(region));   // (fetched before the barrier, not after)
+    const float alpha98 = 0.98f * a.alpha;
+    char *region = reinterpret_cast<char *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                                            static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad);
+    // four sub-tiles per round, one entry per lane
+    constexpr int kRounds = (kRunMax + 3) / 4;
+    const int e_in = lane & 15;
+    const float *src[kRounds];
+    int entry[kRounds];
+    bool always[kRounds], may[kRounds];
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      // (reads of a round beyond the run are clamped to its last sub-tile and not used)
+      const int it = s0 + 4 * rd + (lane >> 4);
+      const int itc = max(min(it, cnt_w - 1), s0);
+      src[rd] = logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
+      entry[rd] = (wmap.first + it * wmap.step) * 16 + e_in;
+      may[rd] = it < cnt_w && entry[rd] < n1;
+      always[rd] = it < cnt_w && entry[rd] == n_old;   // the appended entry starts its tracking there
+    }
+    const int hh = lane & 7;
+    __asm__ volatile("" ::"s"(group), "s"(alpha98), "s"(region));   // (fetched before the barrier, not after)
     __syncthreads();                               // the stream has ended, the waves' statistics are in LDS
-    scan_candidates(logits, wmap.cnt, s0, wmap, group, alpha, region);
-    if (split == 0 && w == 1) append_row();
+    // lane h < 8 works out the cut of head h, everybody reads the eight cuts
+    float mbh = m_lds[0][hh];
+#pragma unroll
+    for (int w2 = 1; w2 < kWaves; ++w2) mbh = fmaxf(mbh, m_lds[w2][hh]);
+    float lbh = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < kWaves; ++w2) {
+      const float mw = m_lds[w2][hh];
+      lbh = fmaf(mw == -INFINITY ? 0.f : __expf(mw - mbh), lsum_lds[w2][hh], lbh);
+    }
+    // the logits of all rounds are read first ...
+    f32x4_t sa[kRounds], sb[kRounds];
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      sa[rd] = *reinterpret_cast<const f32x4_t *>(src[rd]);
+      sb[rd] = *reinterpret_cast<const f32x4_t *>(src[rd] + 4);
+    }
+    const float cut_h = (hh < group && lbh > 0.f) ? mbh + __logf(alpha98 * lbh) : INFINITY;
+    float cut[kHeadPad];
+#pragma unroll
+    for (int h = 0; h < kHeadPad; ++h)
+      cut[h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cut_h), h));
+    unsigned long long mask[kRounds];
+    unsigned n_rec = 0;
+#pragma unroll
+    for (int rd = 0; rd < kRounds; ++rd) {
+      // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
+      const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
+                            fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
+      const bool cand = ((d >= 0.f) & may[rd]) | always[rd];
+      sb[rd][3] = __int_as_float(entry[rd]);       // (the 8th place: groups have at most 7 heads here)
+      mask[rd] = __builtin_amdgcn_ballot_w64(cand);
+      n_rec += static_cast<unsigned>(__popcll(mask[rd]));
+    }
+    // ... then ONE addition to the block's record count reserves the places of all of the wave's records
+    if (n_rec != 0) {                              // wave-uniform
+      unsigned base = 0;
+      if (lane == 0) base = atomicAdd(&cand_total, n_rec);
+      base = __builtin_amdgcn_readfirstlane(base) + 1;
+#pragma unroll
+      for (int rd = 0; rd < kRounds; ++rd) {
+        if ((mask[rd] >> lane) & 1ull) {
+          const unsigned at = base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
+                                                              __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
+          char *dst = region + at * static_cast<unsigned>(kHeadPad * sizeof(float));   // (a 32-bit offset: under 4 GB)
+          *reinterpret_cast<f32x4_t *>(dst) = sa[rd];
+          *reinterpret_cast<f32x4_t *>(dst + 16) = sb[rd];
+        }
+        base += static_cast<unsigned>(__popcll(mask[rd]));
+      }
+    }
     __syncthreads();                               // cand_total is complete
     if (!hand_over) __syncthreads();               // (the ticket route has one more)
     return;

@@ -97,8 +97,6 @@ int32_t capacity_of(const lazyev_config *c) {
   return (c->prompt_len > c->budget ? c->prompt_len : c->budget) + c->window;
 }
 
-constexpr int32_t kCompactMinEntries = 1792;
-
 // Entries per unit in a logits buffer of the fused kernel: the capacity in whole sub-tiles plus
 // the slack its per-block regions of candidate records need (65 slots for each of up to 64 blocks).
 size_t fused_p_stride(int32_t capacity) { return static_cast<size_t>((capacity + 15) / 16 * 16) + 65 * 64; }
@@ -442,10 +440,10 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     a.track = ctx->pend;                           // the previous call's tracking rides along
     a.p_stride = static_cast<int32_t>(fused_p_stride(ctx->capacity));
     // candidate lists instead of every logit, unless somebody reads the logits as such (the
-    // caller through p_out / p_override, or an eviction that ranks by this call's weights) or
-    // the cache is short: building the lists costs a block about 0.6 us at its end and saves
-    // traffic in proportion to the cache length (measured break-even near 1750 entries)
-    compact = ctx->variant != 5 && (ctx->variant == 6 || n_old + 1 >= kCompactMinEntries) && !p_out && !p_override &&
+    // caller through p_out / p_override, or an eviction that ranks by this call's weights): the
+    // lists are built by waves of their own beside the merge, so they cost a call nothing and
+    // save traffic at every cache length (measured 129 .. 4160 entries)
+    compact = ctx->variant != 5 && !p_out && !p_override &&
               !(c.score_flags & LAZYEV_SCORE_CURRENT_ATTENTION) &&
               lazyev::decode_fused_compact_fits(n_old, n_split, a.p_stride, ctx->group);
   }
