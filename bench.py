@@ -238,8 +238,10 @@ def timeline_mode(args):
                       for i, n in enumerate(names)},
            "finisher_tail_us (block end - end of its stream)":
                q(np.concatenate([(s[0][:, 5] - s[0][:, 2])[s[1] == 1] for s in samples])),
-           "tracking_blocks": {"start": q(np.concatenate([s[2][:, 0] for s in samples])),
-                               "end": q(np.concatenate([s[2][:, 1] for s in samples]))}}
+           # (a call that leaves candidate lists has no tracking blocks: its list waves do that work)
+           "tracking_blocks": ({"start": q(np.concatenate([s[2][:, 0] for s in samples])),
+                                "end": q(np.concatenate([s[2][:, 1] for s in samples]))}
+                               if sum(len(s[2]) for s in samples) else {})}
     # Which blocks end their stream late: by the XCD they ran on, by their place among the unit's
     # blocks, and how far the blocks of one unit lie apart.
     end = np.concatenate([s[0][:, 2] for s in samples])

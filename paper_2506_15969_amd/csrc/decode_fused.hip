@@ -523,14 +523,15 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_
 // in LDS; every kRunMax sub-tiles it then writes the candidates among them, found with the cut
 // that the block's four waves' running statistics give at that moment (a lower bound of the
 // final denominator at any time, so the cut only errs towards more candidates).
-// A call that leaves candidate lists runs blocks of 2 * kWaves waves: the second four ("list
-// waves") sleep at the block barrier while the first four stream, and then build the candidate
-// lists from the logits in LDS while the first four merge, exchange and finish the unit; that
-// phase is serial code of one wave per SIMD, so a second wave per SIMD nearly halves it.  Both
-// block sizes keep to 128 registers per lane, so that a stream block and a tracking block fit a
-// compute unit together.
-template <bool kCompact, bool kLong = false>
-__global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fused_kernel(
+// kListWaves (with kCompact): blocks of 2 * kWaves waves.  The second four ("list waves") sleep at
+// the block barrier while the first four stream, and then build the candidate lists from the
+// logits in LDS while the first four merge, exchange and finish the unit; that phase is serial
+// code of one wave per SIMD, so a second wave per SIMD takes the lists off its path.  Used when
+// all blocks of the launch are resident at once with eight waves each (a stream block and a
+// tracking block per compute unit: every instance keeps to 128 registers per lane); a launch of
+// more blocks runs four-wave blocks whose stream waves build their own lists.
+template <bool kCompact, bool kLong = false, bool kListWaves = false>
+__global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fused_kernel(
     const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split, const int capacity,
     const int units_call, const int slots_on, const DecodeArgs a) {
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
@@ -549,7 +550,7 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
   if (static_cast<int>(blockIdx.x) >= n_split * units_call) {
     // tracking of the previous call: n_split blocks per unit, spread over the compute units
     // like the stream blocks
-    if (kCompact && threadIdx.x >= kBlock) return;  // (the tracking has no use for list waves)
+    if (kListWaves && threadIdx.x >= kBlock) return;  // (the tracking has no use for list waves)
     const int tb = blockIdx.x - n_split * units_call;
     const int unit = tb / n_split, part = tb % n_split;
     TrackArgs k;
@@ -610,45 +611,47 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
       reinterpret_cast<uint4 *>(vu + static_cast<size_t>(n_old) * D)[lane - 16] = reinterpret_cast<const uint4 *>(vn)[lane - 16];
   };
 
-  if (kCompact && wave >= kWaves) {
-    // ---- list wave kWaves + w: the candidates of the tracking among the sub-tiles that stream
-    // wave w leaves in LDS (for a long run: the last segment; the earlier ones went out while the
-    // wave streamed), i.e. the entries that can reach alpha in some head.
-    // p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's own (mb, lb), so
-    // p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the rounding of the two
-    // sides.  Everything that does not depend on the logits is worked out now; then the wave
-    // sleeps at the barrier that ends the stream.
-    const int w = wave - kWaves;
-    if (split == 0 && w == 1) append_row();
+  // ---- candidate list of the sub-tiles that stream wave w leaves in LDS (for a long run: the last
+  // segment; the earlier ones went out while the wave streamed), i.e. the entries that can reach
+  // alpha in some head.  p_h = exp(s_h - m_h) / l_h <= exp(s_h - mb_h) / lb_h with the block's
+  // own (mb, lb), so p_h >= alpha needs s_h >= mb_h + log(alpha lb_h); 2 % slack covers the
+  // rounding of the two sides.  In two steps: what does not depend on the logits (plan), and
+  // the rest, after the block barrier that ends the stream (run).  Four sub-tiles per round, one
+  // entry per lane.
+  constexpr int kRounds = (kRunMax + 3) / 4;
+  struct ScanPlan {
+    const float *src[kRounds];
+    int entry[kRounds];
+    bool always[kRounds], may[kRounds];
+    char *region;
+    int group;
+    float alpha98;
+  };
+  auto plan_scan = [&](ScanPlan &sp, int w) {
     const WaveMap wmap = fused_wave_map(n_sub, n_split, split, w);
     const int cnt_w = wmap.cnt;
     const int s0 = (kLong && cnt_w > 0) ? (cnt_w - 1) / kRunMax * kRunMax : 0;
     const int run_w = min(fused_wave_run(n_sub, n_split), kRunMax);
     const float *logits = logit_lds + static_cast<size_t>(w) * run_w * (16 * kHeadPad);
-    const int group = a.group;
-    const float alpha98 = 0.98f * a.alpha;
-    char *region = reinterpret_cast<char *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
-                                                            static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad);
-    // four sub-tiles per round, one entry per lane
-    constexpr int kRounds = (kRunMax + 3) / 4;
+    sp.group = a.group;
+    sp.alpha98 = 0.98f * a.alpha;
+    sp.region = reinterpret_cast<char *>(a.logits_out + (static_cast<size_t>(unit) * a.p_stride +
+                                                         static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad);
     const int e_in = lane & 15;
-    const float *src[kRounds];
-    int entry[kRounds];
-    bool always[kRounds], may[kRounds];
 #pragma unroll
     for (int rd = 0; rd < kRounds; ++rd) {
       // (reads of a round beyond the run are clamped to its last sub-tile and not used)
       const int it = s0 + 4 * rd + (lane >> 4);
       const int itc = max(min(it, cnt_w - 1), s0);
-      src[rd] = logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
-      entry[rd] = (wmap.first + it * wmap.step) * 16 + e_in;
-      may[rd] = it < cnt_w && entry[rd] < n1;
-      always[rd] = it < cnt_w && entry[rd] == n_old;   // the appended entry starts its tracking there
+      sp.src[rd] = logits + (itc - s0) * (16 * kHeadPad) + e_in * kHeadPad;
+      sp.entry[rd] = (wmap.first + it * wmap.step) * 16 + e_in;
+      sp.may[rd] = it < cnt_w && sp.entry[rd] < n1;
+      sp.always[rd] = it < cnt_w && sp.entry[rd] == n_old;   // the appended entry starts its tracking there
     }
-    const int hh = lane & 7;
-    __asm__ volatile("" ::"s"(group), "s"(alpha98), "s"(region));   // (fetched before the barrier, not after)
-    __syncthreads();                               // the stream has ended, the waves' statistics are in LDS
+  };
+  auto run_scan = [&](ScanPlan &sp) {
     // lane h < 8 works out the cut of head h, everybody reads the eight cuts
+    const int hh = lane & 7;
     float mbh = m_lds[0][hh];
 #pragma unroll
     for (int w2 = 1; w2 < kWaves; ++w2) mbh = fmaxf(mbh, m_lds[w2][hh]);
@@ -662,10 +665,10 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
     f32x4_t sa[kRounds], sb[kRounds];
 #pragma unroll
     for (int rd = 0; rd < kRounds; ++rd) {
-      sa[rd] = *reinterpret_cast<const f32x4_t *>(src[rd]);
-      sb[rd] = *reinterpret_cast<const f32x4_t *>(src[rd] + 4);
+      sa[rd] = *reinterpret_cast<const f32x4_t *>(sp.src[rd]);
+      sb[rd] = *reinterpret_cast<const f32x4_t *>(sp.src[rd] + 4);
     }
-    const float cut_h = (hh < group && lbh > 0.f) ? mbh + __logf(alpha98 * lbh) : INFINITY;
+    const float cut_h = (hh < sp.group && lbh > 0.f) ? mbh + __logf(sp.alpha98 * lbh) : INFINITY;
     float cut[kHeadPad];
 #pragma unroll
     for (int h = 0; h < kHeadPad; ++h)
@@ -677,8 +680,8 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
       // s_h >= cut_h in some head  <=>  the largest s_h - cut_h is not negative
       const float d = fmaxf(fmaxf(fmaxf(sa[rd][0] - cut[0], sa[rd][1] - cut[1]), fmaxf(sa[rd][2] - cut[2], sa[rd][3] - cut[3])),
                             fmaxf(fmaxf(sb[rd][0] - cut[4], sb[rd][1] - cut[5]), sb[rd][2] - cut[6]));
-      const bool cand = ((d >= 0.f) & may[rd]) | always[rd];
-      sb[rd][3] = __int_as_float(entry[rd]);       // (the 8th place: groups have at most 7 heads here)
+      const bool cand = ((d >= 0.f) & sp.may[rd]) | sp.always[rd];
+      sb[rd][3] = __int_as_float(sp.entry[rd]);    // (the 8th place: groups have at most 7 heads here)
       mask[rd] = __builtin_amdgcn_ballot_w64(cand);
       n_rec += static_cast<unsigned>(__popcll(mask[rd]));
     }
@@ -692,13 +695,25 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
         if ((mask[rd] >> lane) & 1ull) {
           const unsigned at = base + __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask[rd] >> 32),
                                                               __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask[rd]), 0u));
-          char *dst = region + at * static_cast<unsigned>(kHeadPad * sizeof(float));   // (a 32-bit offset: under 4 GB)
+          char *dst = sp.region + at * static_cast<unsigned>(kHeadPad * sizeof(float));   // (a 32-bit offset: under 4 GB)
           *reinterpret_cast<f32x4_t *>(dst) = sa[rd];
           *reinterpret_cast<f32x4_t *>(dst + 16) = sb[rd];
         }
         base += static_cast<unsigned>(__popcll(mask[rd]));
       }
     }
+  };
+
+  if (kListWaves && wave >= kWaves) {
+    // ---- list wave kWaves + w: appends the new row (one of them), plans, sleeps at the barrier
+    // that ends the stream, builds stream wave w's list
+    const int w = wave - kWaves;
+    if (split == 0 && w == 1) append_row();
+    ScanPlan sp;
+    plan_scan(sp, w);
+    __asm__ volatile("" ::"s"(sp.group), "s"(sp.alpha98), "s"(sp.region));   // (fetched before the barrier, not after)
+    __syncthreads();                               // the stream has ended, the waves' statistics are in LDS
+    run_scan(sp);
     __syncthreads();                               // cand_total is complete
     if (!hand_over) __syncthreads();               // (the ticket route has one more)
     return;
@@ -1018,8 +1033,16 @@ __global__ __launch_bounds__(kCompact ? 2 * kBlock : kBlock, 4) void decode_fuse
       }
     }
   }
-  // (a call that leaves candidate lists has its list waves do this and the lists meanwhile)
-  if (!kCompact && split == 0 && wave == 1) append_row();
+  // what only the NEXT launch needs, while the partial travels: the appended row and this wave's
+  // candidate list (list waves, where the block has them, do both meanwhile)
+  if constexpr (!kListWaves) {
+    if (split == 0 && wave == 1) append_row();
+    if constexpr (kCompact) {
+      ScanPlan sp;
+      plan_scan(sp, wave);
+      run_scan(sp);
+    }
+  }
   const size_t count_at = (static_cast<size_t>(unit) * a.p_stride +
                            static_cast<size_t>(split) * fused_part_cap(n_old, n_split)) * kHeadPad;
   if (hand_over) {
@@ -1122,6 +1145,20 @@ hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Compute units of the current device (asked once).
+static int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
+}
+
 hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent_t *ev) {
   const int units = a.batch * a.n_kv_heads;
   if (a.dtype != 1 || a.head_dim != D || a.group > kHeadPad || a.n_split < 1 ||
@@ -1144,15 +1181,19 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   const bf16_t *kn = static_cast<const bf16_t *>(a.k_new), *vn = static_cast<const bf16_t *>(a.v_new);
   const int slots_on = a.slots.prompt_len ? 1 : 0;
   const bool long_run = fused_wave_run(n_sub, a.n_split) > kRunMax;
-  if (a.variant == 6 && long_run)
-    hipLaunchKernelGGL((decode_fused_kernel<true, true>), dim3(sb + (a.track.valid ? sb : 0)), dim3(2 * kBlock), lds_all, stream,
-                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
-  else if (a.variant == 6)
-    hipLaunchKernelGGL(decode_fused_kernel<true>, dim3(sb + (a.track.valid ? sb : 0)), dim3(2 * kBlock), lds_all, stream,
-                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
-  else
-    hipLaunchKernelGGL(decode_fused_kernel<false>, dim3(sb + (a.track.valid ? sb : 0)), dim3(kBlock), lds_all, stream,
-                       kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a);
+  // list waves (blocks of eight waves) where every block of the launch is resident at once: two
+  // such blocks fit a compute unit
+  const int n_blocks = sb + (a.track.valid ? sb : 0);
+  const bool list_waves = n_blocks <= 2 * compute_units();
+  const dim3 grid(n_blocks), b4(kBlock), b8(2 * kBlock);
+#define LAZYEV_LAUNCH(instance, block) \
+  hipLaunchKernelGGL(instance, grid, block, lds_all, stream, kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a)
+  if (a.variant == 6 && long_run && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, true, true>), b8);
+  else if (a.variant == 6 && long_run) LAZYEV_LAUNCH((decode_fused_kernel<true, true, false>), b4);
+  else if (a.variant == 6 && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, false, true>), b8);
+  else if (a.variant == 6) LAZYEV_LAUNCH((decode_fused_kernel<true, false, false>), b4);
+  else LAZYEV_LAUNCH((decode_fused_kernel<false, false, false>), b4);
+#undef LAZYEV_LAUNCH
   const hipError_t e = hipGetLastError();
   if (ev) { (void)hipEventRecord(ev[1], stream); (void)hipEventRecord(ev[2], stream); }
   return e;
