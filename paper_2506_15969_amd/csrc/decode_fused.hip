@@ -1,27 +1,33 @@
 // Decode step of one layer in ONE launch (bf16, head_dim 128): append, attention (Eq. 4 of the
 // paper) and, one call behind, the recurrence tracking of Alg. 1 / Eq. 1.
 //
-// A unit's cache is cut into 16-entry sub-tiles; wave w of the unit's 4 * n_split waves takes
-// sub-tiles w, w + 4 n_split, ... (the waves of a unit read one moving window of the cache
-// together, which keeps DRAM pages open).  Per sub-tile a wave
-//   loads      K and V as whole 256-byte rows (16 lanes per row), waits, and multiplies; the
-//              other waves of the compute unit keep the memory system busy meanwhile (keeping
-//              a wave's next sub-tile in flight as well measured slower on MI355X)
+// A unit's cache is cut into 16-entry sub-tiles, dealt to the 4 * n_split stream waves of the
+// unit's n_split blocks in turn (fused_wave_map: the waves of a unit read one moving window of the
+// cache together, which keeps DRAM pages open).  Per sub-tile a wave
+//   loads      K and V as whole 256-byte rows (16 lanes per row), non-temporal; the next
+//              sub-tile is requested while the current one is multiplied, the first one from the
+//              arguments a wave is handed in registers, before the argument block is read
 //   K layout   K rows go through a wave-private LDS area to reach the MFMA operand layout
 //   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, the G query rows padded to 16 columns
-//   logits     scaled logits are kept in LDS as [entry][8 heads] and written to the workspace
-//              when the wave's run ends, 512 contiguous bytes per sub-tile (a store among the
-//              loads would hold up the in-order load counter)
+//   logits     scaled logits are kept in LDS as [entry][8 heads]; what the tracking needs of
+//              them goes to the workspace when the wave's run ends (a store among the loads
+//              would hold up the in-order load counter)
 //   softmax    per wave: reference maximum m, sum l, output accumulator O.  The reference is
 //              raised only when a logit exceeds it by more than 8, so rescaling O is rare;
 //              exp(s - m) <= e^8 stays far from overflow
 //   O += P V   v_mfma_f32_16x16x16_bf16 after an in-lane 4x8 transpose of the V rows
-// The four waves of a block merge their (m, l, O) in LDS and publish one partial per block
-// with device-scope stores.  The block that takes the LAST ticket of its unit (a counter in the
-// workspace, taken after the block's stores have completed) merges the unit's partials into
-// the output row and leaves the unit's softmax statistics (max, 1 / sum per head) next to the
-// logits.  No block waits for another block, so the kernel cannot hang on scheduling order;
-// the ticket resets itself for the next launch.
+// The four stream waves of a block merge their (m, l, O) in LDS into one partial per block.
+// What follows the stream is serial code of single waves, where instructions, not bytes, set
+// the time: no branches where a select does, addresses worked out beforehand.
+//
+// Partials of a unit.  One block: its partial is the result.  2 .. 4 blocks (the usual split):
+// the unit's last block finishes the unit, the others hand it their partial as a record of
+// stamped 64-bit words (see "hand-over" below): no acknowledgement is waited for, nothing is
+// signalled, one memory round trip.  More blocks: partials are published with device-scope
+// stores, and the block that takes the LAST ticket of its unit (a counter in the workspace,
+// taken after the block's stores have completed) merges them; the ticket resets itself.  In all
+// cases the partials are merged in block order, and the finishing block leaves the unit's
+// softmax statistics (max, 1 / sum per head) for the tracking.
 //
 // Tracking.  The activation test of Alg. 1 needs p = exp(s - m) / l with the statistics of the
 // WHOLE unit, which exist only when the unit's last block is done.  Doing it there puts a
@@ -32,16 +38,19 @@
 // entry) while the new call streams; lazyev_evict and lazyev_stats apply what is pending
 // through track_kernel.  Logits and statistics are double-buffered.
 //
-// Candidate lists (kernel instance <true>, groups of at most 7 heads).  A block knows, once its
-// four waves have merged, its own share of every head's softmax denominator, which bounds the
+// Candidate lists (kernel instances <true, ..>, groups of at most 7 heads; every call whose
+// logits nobody reads as such).  A block knows, once its four stream waves are done, its own
+// share of every head's softmax denominator, which bounds the
 // true denominator from below: an entry whose weight relative to the BLOCK's denominator
 // stays under alpha in every head cannot reach alpha.  The block then writes only the other
 // entries ("candidates", about a tenth on the benchmark workloads; the appended entry always)
 // as records (7 logits, entry index) into its own region of the logits buffer, and the
 // tracking applies the exact test to the records: the same state bit for bit.  A wave whose run
-// is longer than the sub-tiles it keeps in LDS (instance <true, true>) writes the candidates of
-// every full segment while it streams, with the cut that the block's waves' running sums give
-// at that moment, and only the last segment after the merge.
+// is longer than the sub-tiles it keeps in LDS (instances <true, true, ..>) writes the candidates
+// of every full segment while it streams, with the cut that the block's waves' running sums give
+// at that moment, and only the last segment after the stream.  Where all blocks of the launch
+// fit the chip at once with eight waves each (instances <.., .., true>), four more waves per
+// block ("list waves") sleep through the stream and build the lists beside the merge.
 //
 // MFMA operand layouts (lane l, c = l % 16, g = l / 16):
 //   16x16x32: A[row c][k = 8g..8g+7]  B[k = 8g..8g+7][col c]  C[row 4g+i][col c]
