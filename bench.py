@@ -238,7 +238,8 @@ def timeline_mode(args):
                       for i, n in enumerate(names)},
            "finisher_tail_us (block end - end of its stream)":
                q(np.concatenate([(s[0][:, 5] - s[0][:, 2])[s[1] == 1] for s in samples])),
-           # (a call that leaves candidate lists has no tracking blocks: its list waves do that work)
+           # (the tracking blocks of the launch apply the PREVIOUS call's tracking; the first call of a
+           # layer has none)
            "tracking_blocks": ({"start": q(np.concatenate([s[2][:, 0] for s in samples])),
                                 "end": q(np.concatenate([s[2][:, 1] for s in samples]))}
                                if sum(len(s[2]) for s in samples) else {})}
