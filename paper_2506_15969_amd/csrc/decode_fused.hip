@@ -83,11 +83,7 @@ constexpr int kRunMax = 20;             // sub-tiles whose logits a wave keeps i
 struct WaveMap { int first, step, cnt; };
 __host__ __device__ inline WaveMap fused_wave_map(int n_sub, int n_split, int split, int wave) {
   WaveMap m;
-#ifdef LZ_FLIP
   m.first = (n_split - 1 - split) * kWaves + wave;
-#else
-  m.first = (n_split - 1 - split) * kWaves + wave;
-#endif
   m.step = kWaves * n_split;
   m.cnt = m.first < n_sub ? (n_sub - m.first + m.step - 1) / m.step : 0;
   return m;
@@ -603,11 +599,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
   // kHandOverMax blocks hand their partials over to the unit's last block; longer splits take
   // tickets and the block with the last one finishes.
   const bool alone = n_split == 1;
-#ifdef LZ_NO_HANDOVER
-  const bool hand_over = false;
-#else
   const bool hand_over = n_split >= 2 && n_split <= kHandOverMax;
-#endif
 
   // the appended row goes to slot N (the stream waves read it from k_new / v_new, nobody from the slot)
   auto append_row = [&]() {
