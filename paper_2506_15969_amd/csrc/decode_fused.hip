@@ -535,10 +535,15 @@ __device__ void finish_unit(const DecodeArgs &a, int unit, int n_split, int own_
 // all blocks of the launch are resident at once with eight waves each (a stream block and a
 // tracking block per compute unit: every instance keeps to 128 registers per lane); a launch of
 // more blocks runs four-wave blocks whose stream waves build their own lists.
-template <bool kCompact, bool kLong = false, bool kListWaves = false>
+// kSplit > 0: the instance is for units of exactly kSplit blocks (the benchmark workloads' 2 and
+// 4).  What follows the stream is serial code of single waves, and a split known at compile
+// time takes the ticket route, the loops over a variable number of partials and the divisions
+// by the split out of it.
+template <bool kCompact, bool kLong = false, bool kListWaves = false, int kSplit = 0>
 __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fused_kernel(
-    const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split, const int capacity,
+    const bf16_t *k_cache, const bf16_t *v_cache, const bf16_t *k_new_all, const bf16_t *v_new_all, const int n_old_call, const int n_split_call, const int capacity,
     const int units_call, const int slots_on, const DecodeArgs a) {
+  const int n_split = kSplit > 0 ? kSplit : n_split_call;   // (a constant where the instance fixes it)
   __shared__ float m_lds[kWaves][16], lsum_lds[kWaves][16];
   // one 16-row K sub-tile per wave while streaming; afterwards the wave's output accumulator
   __shared__ u32x4_t stage_lds[kWaves][16 * 16];
@@ -997,11 +1002,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
   const int t_own = ec >> 2;                       // (threads beyond the group's rows read a valid place)
   const unsigned long long *recs =
       a.ws.part_rec + static_cast<size_t>(unit) * ((kHandOverMax - 1) * kRecWords);
-  RecPart r[kHandOverMax - 1];
-#pragma unroll
-  for (int j = 0; j < kHandOverMax - 1; ++j)
-#pragma unroll
-    for (int i = 0; i < 6; ++i) r[j].w[i] = 0;
+  RecPart r[kHandOverMax - 1];                     // (read only where loaded: the finishing block's j < n_split - 1)
   if (hand_over || !alone) {
     // the heads' max and sum of this block go out from ONE wave (lane h of wave 0 holds head h's):
     // dword stores of several waves into the one cache line they share were seen to reach a
@@ -1191,7 +1192,9 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   hipLaunchKernelGGL(instance, grid, block, lds_all, stream, kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a)
   if (a.variant == 6 && long_run && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, true, true>), b8);
   else if (a.variant == 6 && long_run) LAZYEV_LAUNCH((decode_fused_kernel<true, true, false>), b4);
+  else if (a.variant == 6 && list_waves && a.n_split == 2) LAZYEV_LAUNCH((decode_fused_kernel<true, false, true, 2>), b8);
   else if (a.variant == 6 && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, false, true>), b8);
+  else if (a.variant == 6 && a.n_split == 4) LAZYEV_LAUNCH((decode_fused_kernel<true, false, false, 4>), b4);
   else if (a.variant == 6) LAZYEV_LAUNCH((decode_fused_kernel<true, false, false>), b4);
   else LAZYEV_LAUNCH((decode_fused_kernel<false, false, false>), b4);
 #undef LAZYEV_LAUNCH
