@@ -125,6 +125,24 @@ __device__ __forceinline__ bf16_t float_to_bf16(float f) {   // round to nearest
   return static_cast<bf16_t>(u >> 16);
 }
 
+// x + (x of lane ^ 16) + (the same of lane ^ 32), and the maximum likewise: the sum / maximum over
+// the four lanes c, c + 16, c + 32, c + 48.  v_permlane16_swap / v_permlane32_swap exchange 16-
+// and 32-lane halves between two registers in the vector ALU; applied to two copies of x they
+// leave the two summands of every lane side by side (same pairs, same roundings as the
+// shuffles through the LDS crossbar they replace, which cost a wave a round trip each).
+__device__ __forceinline__ float sum_over_lane_groups(float x) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_over_lane_groups(float x) {
+  auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // K and V rows of one sub-tile as a wave holds them: 4 + 4 loads of 16 bytes per lane.
 struct SubTile {
   u32x4_t k[KC];
@@ -821,8 +839,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
       for (int i = 0; i < 4; ++i) dst[(4 * g + i) * kHeadPad + c] = s[i];
     }
     float tmax = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    tmax = max_over_lane_groups(tmax);
     if (__builtin_amdgcn_ballot_w64(tmax > m_ref + kRaise) != 0) {   // wave-uniform, rare
       const float m_new = fmaxf(m_ref, tmax);
       const float f = __expf(m_ref - m_new);       // 0 on the first sub-tile (m_ref = -inf)
@@ -907,8 +924,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
   // the entries at any earlier time.
   auto segment_candidates = [&](int it_a, int it_b) {
     float ls = lsum;
-    ls += __shfl_xor(ls, 16);
-    ls += __shfl_xor(ls, 32);
+    ls = sum_over_lane_groups(ls);
     if (g == 0 && c < kHeadPad) run_lse[wave][c] = ls > 0.f ? m_ref + __logf(ls) : -INFINITY;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -950,8 +966,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
   STAMP(2);
   if (!kCompact) flush(seg0, cnt);
   // ---- the four waves of the block -> one partial
-  lsum += __shfl_xor(lsum, 16);
-  lsum += __shfl_xor(lsum, 32);
+  lsum = sum_over_lane_groups(lsum);
   if (g == 0) { m_lds[wave][c] = m_ref; lsum_lds[wave][c] = lsum; }
   float *acc_lds = reinterpret_cast<float *>(&stage_lds[0][0]);   // [kWaves][8 * D]
 #pragma unroll
@@ -1069,9 +1084,16 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
             rec_load(r[j], recs + static_cast<size_t>(j) * kRecWords, t_own, h_own);
       }
       STAMP(4);
-      Merge mg;                                    // in block order: the others', then this block's own
+      // in block order: the others', then this block's own.  The running merge starts from block
+      // 0's partial as it is: folding it into the empty state would reproduce exactly its bits
+      // (factors 0 and exp(0) = 1) at the price of a dozen instructions.
+      Merge mg;
+      mg.m = rec_value(r[0].w[4]);
+      mg.l = rec_value(r[0].w[5]);
 #pragma unroll
-      for (int j = 0; j < kHandOverMax - 1; ++j)
+      for (int i = 0; i < 4; ++i) mg.o[i] = rec_value(r[0].w[i]);
+#pragma unroll
+      for (int j = 1; j < kHandOverMax - 1; ++j)
         if (j < n_split - 1) {
           const f32x4_t oj = {rec_value(r[j].w[0]), rec_value(r[j].w[1]), rec_value(r[j].w[2]), rec_value(r[j].w[3])};
           mg.fold(rec_value(r[j].w[4]), rec_value(r[j].w[5]), oj);
