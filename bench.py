@@ -265,6 +265,14 @@ def timeline_mode(args):
                                "stream end": q(st[fin, 2])}
     res["other_blocks"] = {"block end - all four waves done": q((st[:, 5] - st[:, 3])[~fin]),
                            "stream end": q(st[~fin, 2])}
+    # the block that ends a launch: did it stream longest, or did it wait for another block's partial?
+    last = [int(np.argmax(s[0][:, 5])) for s in samples]
+    res["last_block_of_a_launch"] = {
+        "is_the_block_whose_stream_ended_last": round(float(np.mean([int(i == int(np.argmax(s[0][:, 2]))) for i, s in zip(last, samples)])), 2),
+        "finishes_its_unit": round(float(np.mean([float(s[1][i] == 1) for i, s in zip(last, samples)])), 2),
+        "stream end": q(np.array([s[0][i, 2] for i, s in zip(last, samples)])),
+        "partials complete - all four waves done": q(np.array([s[0][i, 4] - s[0][i, 3] for i, s in zip(last, samples)])),
+        "block end - end of its stream": q(np.array([s[0][i, 5] - s[0][i, 2] for i, s in zip(last, samples)]))}
     res["per_launch"] = {"stream_end_sigma": round(float(np.mean([s[0][:, 2].std() for s in samples])), 2),
                          "mean_stream_end": round(float(np.mean([s[0][:, 2].mean() for s in samples])), 2),
                          "latest_stream_end": round(float(np.mean([s[0][:, 2].max() for s in samples])), 2)}
