@@ -55,7 +55,7 @@ EXPORTS = ["lazyev_capacity", "lazyev_workspace_size", "lazyev_init", "lazyev_de
 # ... and include/lazyev_bench.h (knobs and the per-kernel timer in the same library; the plain
 # streaming probes in liblazyev_bench.so, loaded by bench_lib() when somebody measures)
 BENCH_EXPORTS = ["lazyev_set_chunk", "lazyev_set_target_blocks", "lazyev_set_variant", "lazyev_set_spin_ticks",
-                 "lazyev_profile_arm", "lazyev_profile_read"]
+                 "lazyev_profile_arm", "lazyev_profile_read", "lazyev_log_words", "lazyev_log_peek"]
 BENCH_LIB_EXPORTS = ["lazyev_stream_probe", "lazyev_stream_read_probe", "lazyev_event_overhead"]
 _BENCH_LIB_PATH = os.path.join(os.path.dirname(_LIB_PATH), "liblazyev_bench.so")
 _bench_lib = None
@@ -122,6 +122,10 @@ lib.lazyev_set_spin_ticks.restype = C.c_int
 lib.lazyev_set_spin_ticks.argtypes = [C.c_void_p, C.c_uint32]
 lib.lazyev_profile_arm.restype = C.c_int
 lib.lazyev_profile_arm.argtypes = [C.c_void_p, C.c_int32]
+lib.lazyev_log_words.restype = C.c_int32
+lib.lazyev_log_words.argtypes = [C.c_void_p]
+lib.lazyev_log_peek.restype = C.c_int
+lib.lazyev_log_peek.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]
 lib.lazyev_profile_read.restype = C.c_int
 lib.lazyev_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.lazyev_destroy.restype = None
@@ -303,6 +307,22 @@ class LazyEviction:
 
     def set_spin_ticks(self, ticks: int):
         _check(lib.lazyev_set_spin_ticks(self._ctx, ticks), "lazyev_set_spin_ticks")
+
+    def log_peek(self, layer: int, back: int = 0):
+        """lazyev_log_peek: (step, bool array [batch, n_kv_heads, 32 * log_words]) of a logged call,
+        or None if the layer has no such call in its activation log."""
+        import numpy as np
+        words = lib.lazyev_log_words(self._ctx)
+        if words <= 0:
+            return None
+        units = self.cfg.batch * self.cfg.n_kv_heads
+        buf = (C.c_uint32 * (units * words))()
+        t = C.c_int32(0)
+        if lib.lazyev_log_peek(self._ctx, layer, back, buf, C.byref(t)) != 0:
+            return None
+        a = np.frombuffer(buf, dtype=np.uint32).reshape(self.cfg.batch, self.cfg.n_kv_heads, words)
+        bits = np.unpackbits(a.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+        return t.value, bits
 
     def profile_arm(self, n_calls: int):
         _check(lib.lazyev_profile_arm(self._ctx, n_calls), "lazyev_profile_arm")

@@ -213,8 +213,10 @@ __device__ __forceinline__ void track_load(const TrackArgs &k, int unit, int par
 }
 
 // The activation test and the TS / MRI update of entry i (Alg. 1, Eq. 1); true if active.
+// log_mask (LDS, or null): the call is logged; an active entry then only sets its bit there.
 __device__ __forceinline__ bool track_one(const TrackArgs &k, int unit, int i, const float (&s)[kHeadPad],
-                                          const float (&m)[kHeadPad], const float (&invl)[kHeadPad]) {
+                                          const float (&m)[kHeadPad], const float (&invl)[kHeadPad],
+                                          unsigned *log_mask) {
   const int seq = unit / k.n_kv_heads, kvh = unit % k.n_kv_heads;
   const int G = k.group;
   const size_t head0 = static_cast<size_t>(seq) * k.n_q_heads + static_cast<size_t>(kvh) * G;
@@ -236,16 +238,20 @@ __device__ __forceinline__ bool track_one(const TrackArgs &k, int unit, int i, c
     mri[i] = 0;
     k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
   } else if (act) {                                // few entries are active: TS / MRI are read only here
-    const int32_t gap = k.t - ts[i];
-    if (gap > mri[i]) mri[i] = gap;                // Eq. 1
-    ts[i] = k.t;                                   // Alg. 1
+    if (log_mask) {
+      atomicOr(log_mask + (i >> 5), 1u << (i & 31));
+    } else {
+      const int32_t gap = k.t - ts[i];
+      if (gap > mri[i]) mri[i] = gap;              // Eq. 1
+      ts[i] = k.t;                                 // Alg. 1
+    }
   }
   return act;
 }
 
 __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, int part, int n_parts,
                                                 int r0, const TrackBatch &b, const float (&m)[kHeadPad],
-                                                const float (&invl)[kHeadPad]) {
+                                                const float (&invl)[kHeadPad], unsigned *log_mask) {
   const int seq = unit / k.n_kv_heads, kvh = unit % k.n_kv_heads;
   const int G = k.group;
   const int n_old = k.n_old, n1 = k.n_old + 1;
@@ -276,9 +282,13 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
       mri[i] = 0;
       k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
     } else if (act) {                              // few entries are active: TS / MRI are read only here
-      const int32_t gap = k.t - ts[i];
-      if (gap > mri[i]) mri[i] = gap;              // Eq. 1
-      ts[i] = k.t;                                 // Alg. 1
+      if (log_mask) {
+        atomicOr(log_mask + (i >> 5), 1u << (i & 31));
+      } else {
+        const int32_t gap = k.t - ts[i];
+        if (gap > mri[i]) mri[i] = gap;            // Eq. 1
+        ts[i] = k.t;                               // Alg. 1
+      }
     }
     n_act += act ? 1u : 0u;
   }
@@ -294,7 +304,8 @@ __host__ __device__ inline int fused_part_cap(int n_old, int n_parts) {
 
 // Tracking from the candidate records of the call's blocks b = part, part + step, ...
 __device__ __forceinline__ unsigned track_records(const TrackArgs &k, int unit, int part, int step,
-                                                  const float (&m)[kHeadPad], const float (&invl)[kHeadPad]) {
+                                                  const float (&m)[kHeadPad], const float (&invl)[kHeadPad],
+                                                  unsigned *log_mask) {
   const int cap = fused_part_cap(k.n_old, k.n_parts);
   unsigned n_act = 0;
   for (int b = part; b < k.n_parts; b += step) {
@@ -304,7 +315,7 @@ __device__ __forceinline__ unsigned track_records(const TrackArgs &k, int unit, 
       const float4 sa = *reinterpret_cast<const float4 *>(region + static_cast<size_t>(1 + r) * kHeadPad);
       const float4 sb = *reinterpret_cast<const float4 *>(region + static_cast<size_t>(1 + r) * kHeadPad + 4);
       const float s[kHeadPad] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, 0.f};
-      n_act += track_one(k, unit, __float_as_int(sb.w), s, m, invl) ? 1u : 0u;
+      n_act += track_one(k, unit, __float_as_int(sb.w), s, m, invl, log_mask) ? 1u : 0u;
     }
   }
   return n_act;
@@ -354,16 +365,47 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
   track_stats(k, unit, m, invl);
   unsigned n_act = 0;
   if (k.compact) {
-    n_act = track_records(k, unit, part, n_parts, m, invl);
+    n_act = track_records(k, unit, part, n_parts, m, invl, nullptr);
   } else {
     const int rounds = track_rounds((k.n_old + 1 + 15) >> 4, n_parts);
     for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
       TrackBatch b;
       track_load(k, unit, part, n_parts, r0, b);
-      n_act += track_apply(k, unit, part, n_parts, r0, b, m, invl);
+      n_act += track_apply(k, unit, part, n_parts, r0, b, m, invl, nullptr);
     }
   }
   track_count(k, unit, part, n_act, cnt_lds);
+}
+
+// The logged calls of a layer applied to TS / MRI: one thread per cache entry, the calls in step
+// order.  An entry's bit in the words of a call says that it was active there (TrackArgs::bitlog).
+__global__ __launch_bounds__(kBlock) void track_flush_kernel(const FlushArgs f) {
+  const int layer = blockIdx.x / f.units, unit = blockIdx.x % f.units;
+  const size_t slab = (static_cast<size_t>(layer) * f.units + unit) * f.capacity;
+  const uint32_t *log = f.bitlog + (static_cast<size_t>(layer) * f.log_slots * f.units + unit) * f.log_words;
+  const size_t slot_stride = static_cast<size_t>(f.units) * f.log_words;
+  constexpr int kAhead = 8;                        // words of this many calls requested together
+  for (int i = threadIdx.x; i < f.capacity; i += kBlock) {
+    const uint32_t bit = 1u << (i & 31);
+    const uint32_t *w = log + (i >> 5);
+    int32_t ts = 0, mri = 0;
+    bool touched = false;
+    for (int s0 = 0; s0 < f.n_calls; s0 += kAhead) {
+      uint32_t v[kAhead];
+#pragma unroll
+      for (int d = 0; d < kAhead; ++d) v[d] = w[static_cast<size_t>(min(s0 + d, f.n_calls - 1)) * slot_stride];
+#pragma unroll
+      for (int d = 0; d < kAhead; ++d) {
+        if (s0 + d < f.n_calls && (v[d] & bit)) {
+          if (!touched) { ts = f.ts[slab + i]; mri = f.mri[slab + i]; touched = true; }
+          const int32_t gap = f.t[s0 + d] - ts;
+          if (gap > mri) mri = gap;                // Eq. 1
+          ts = f.t[s0 + d];                        // Alg. 1
+        }
+      }
+    }
+    if (touched) { f.ts[slab + i] = ts; f.mri[slab + i] = mri; }
+  }
 }
 
 // --------------------------------------------------------------------- last block of a unit
@@ -586,14 +628,36 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
     float m[kHeadPad], invl[kHeadPad];
     track_stats(k, unit, m, invl);
     unsigned n_act = 0;
+    // a logged call: the active entries' bits are collected in LDS (the K staging area, which
+    // a tracking block has no other use for) ...
+    unsigned *log_mask = nullptr;
+    if (k.bitlog) {
+      log_mask = reinterpret_cast<unsigned *>(&stage_lds[0][0]);
+      for (int j = threadIdx.x; j < k.log_words; j += kBlock) log_mask[j] = 0;
+      __syncthreads();
+    }
     if (k.compact) {
-      n_act = track_records(k, unit, part, n_split, m, invl);
+      n_act = track_records(k, unit, part, n_split, m, invl, log_mask);
     } else {
       const int rounds = track_rounds((k.n_old + 1 + 15) >> 4, n_split);
       for (int r0 = 0; r0 < rounds; r0 += kTrackRows) {
         TrackBatch b;
         track_load(k, unit, part, n_split, r0, b);
-        n_act += track_apply(k, unit, part, n_split, r0, b, m, invl);
+        n_act += track_apply(k, unit, part, n_split, r0, b, m, invl, log_mask);
+      }
+    }
+    if (k.bitlog) {
+      // ... and every word of the unit is written by the one block whose entries it covers: word
+      // j holds sub-tiles 2j and 2j + 1, which the wave map gives to one block (an even wave and
+      // the next one); with candidate records that is a block of the logged call's own split,
+      // whose records this tracking block reads if the block's index is its own modulo n_split
+      __syncthreads();
+      const int parts = k.compact ? k.n_parts : n_split;
+      uint32_t *dst = k.bitlog + static_cast<size_t>(unit) * k.log_words;
+      for (int j = threadIdx.x; j < k.log_words; j += kBlock) {
+        const int wv = (2 * j) % (kWaves * parts);
+        const int owner = (parts - 1 - wv / kWaves) % n_split;
+        if (owner == part) dst[j] = log_mask[j];
       }
     }
     track_count(k, unit, part, n_act, cnt_lds);
@@ -1169,6 +1233,17 @@ hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
   return hipGetLastError();
 }
 
+int decode_fused_log_words_max() { return static_cast<int>(sizeof(u32x4_t) * kWaves * 256 / sizeof(unsigned)); }
+
+hipError_t launch_track_flush(const FlushArgs &f, int n_layers, hipStream_t stream) {
+  if (!f.ts || !f.mri || !f.bitlog || f.units < 1 || n_layers < 1 || f.capacity < 1 ||
+      f.log_words < (f.capacity + 31) / 32 || f.n_calls < 0 || f.n_calls > f.log_slots || f.log_slots > kLogSlotsMax)
+    return hipErrorInvalidValue;
+  if (f.n_calls == 0) return hipSuccess;
+  hipLaunchKernelGGL(track_flush_kernel, dim3(static_cast<unsigned>(n_layers) * f.units), dim3(kBlock), 0, stream, f);
+  return hipGetLastError();
+}
+
 // Compute units of the current device (asked once).
 static int compute_units() {
   static int n = 0;
@@ -1193,6 +1268,9 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
                          a.track.logits == a.logits_out || a.track.stat == a.stat_out)) ||
       (a.track.valid && a.track.compact &&
        !decode_fused_compact_fits(a.track.n_old, a.track.n_parts, a.track.p_stride, a.track.group)) ||
+      (a.track.valid && a.track.bitlog &&
+       (a.track.log_words < (a.track.capacity + 31) / 32 || a.track.log_words > decode_fused_log_words_max() ||
+        a.track.slots.prompt_len)) ||
       (a.variant == 6 && (a.p_out || a.p_override || !decode_fused_compact_fits(a.n_old, a.n_split, a.p_stride, a.group))))
     return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);

@@ -68,6 +68,24 @@ struct TrackArgs {
   // floats, cap = fused_part_cap(n_old, n_parts): slot 0 holds the number of records (as an
   // integer), slot 1 + r record r = the entry's 7 logits and, in the 8th place, its index.
   int32_t compact, n_parts;
+  // Activation log (fused kernel, uniform batches).  Not null: the tracking blocks do not touch
+  // TS / MRI of the active entries (a 128-byte line read and written for every 4-byte word) but
+  // leave ONE BIT per cache entry of the unit, bit i = entry i was active in this call, as
+  // log_words 32-bit words here; track_flush_kernel applies the logged calls of a layer in step
+  // order (Eq. 1) before anything reads TS / MRI.  The appended entry is still started at once.
+  uint32_t *bitlog;                 // this call's words of unit 0; unit u's follow at u * log_words
+  int32_t log_words;
+};
+
+// The logged calls of one or several layers applied to TS / MRI (Alg. 1 first loop, Eq. 1, in the
+// order of the calls).  Block b works on layer b / units, unit b % units.
+constexpr int kLogSlotsMax = 256;
+struct FlushArgs {
+  int32_t *ts, *mri;                // first layer's slab; the other layers' follow
+  const uint32_t *bitlog;           // [layer][log_slots][units][log_words], first layer of the launch
+  int32_t units, capacity, log_words, log_slots;
+  int32_t n_calls;                  // logged calls to apply: slots 0 .. n_calls - 1
+  int32_t t[kLogSlotsMax];          // step of the call in slot s (what TS becomes)
 };
 
 struct DecodeArgs {
@@ -167,6 +185,8 @@ int decode_fused_head_pad();
 size_t decode_fused_record_bytes();           // one stamped record; a unit has 3
 hipError_t launch_clear_records(unsigned long long *rec, size_t n_words, hipStream_t stream);
 hipError_t launch_track(const TrackArgs &k, hipStream_t stream);
+hipError_t launch_track_flush(const FlushArgs &f, int n_layers, hipStream_t stream);
+int decode_fused_log_words_max();                // cache entries / 32 up to which the fused kernel can log
 hipError_t launch_evict(const EvictArgs &a, hipStream_t stream, hipEvent_t *ev);
 int evict_lds_candidates();   // candidates per unit whose keys the selection keeps in LDS
 hipError_t launch_init_state(int32_t *ts, int32_t *mri, int32_t *pos, int64_t n_units,

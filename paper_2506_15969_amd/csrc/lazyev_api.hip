@@ -43,7 +43,14 @@ struct lazyev_ctx {
   uint32_t spin_ticks;              // fused kernel: longest wait for such a partial, 10 ns ticks
   // fused kernel: the call whose tracking has not been applied yet, and the buffer pair in turn
   lazyev::TrackArgs pend;
+  int32_t pend_layer;               // the layer of that call
   int cur_buf;
+  // activation log (see TrackArgs::bitlog): per layer, the calls whose tracking has been left as
+  // one bit per cache entry and not yet applied to TS / MRI; null when the shape has no log
+  uint32_t *bitlog;
+  int32_t log_words, log_slots;
+  std::vector<int32_t> log_n;       // per layer: logged calls
+  std::vector<int32_t> log_t;       // [layer][log_slots]: their steps
   // the last decode call, if the fused kernel ran it: its logits and statistics are still in
   // the workspace (what an eviction that ranks by that step's weights reads)
   int32_t last_layer;
@@ -102,7 +109,8 @@ int32_t capacity_of(const lazyev_config *c) {
 size_t fused_p_stride(int32_t capacity) { return static_cast<size_t>((capacity + 15) / 16 * 16) + 65 * 64; }
 
 struct Layout {
-  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, sel_keys, activations, rows_moved, ticket, records, fault, hist, slots, total;
+  size_t part_acc, part_ml, p_tilde, logits1, stat, prefill_stat, src_index, sel_keys, bitlog, activations, rows_moved, ticket, records, fault, hist, slots, total;
+  int32_t log_words, log_slots;     // 0: no activation log for this shape
   int32_t n_split_max;
 };
 
@@ -129,6 +137,16 @@ Layout layout_of(const lazyev_config *c) {
   l.sel_keys = off;
   if (cap - c->window > static_cast<size_t>(lazyev::evict_lds_candidates()))
     off = align_up(off + static_cast<size_t>(c->n_layers) * units * cap * sizeof(unsigned long long));
+  // activation log of the single-launch kernel: [layer][slot][unit][one bit per cache entry], as
+  // many slots as calls lie between two evictions (at most kLogSlotsMax; a full log is applied)
+  l.bitlog = off;
+  l.log_words = 0; l.log_slots = 0;
+  if (c->dtype == LAZYEV_DTYPE_BF16 && c->head_dim == 128 &&
+      (cap + 31) / 32 <= static_cast<size_t>(lazyev::decode_fused_log_words_max())) {
+    l.log_words = static_cast<int32_t>((cap + 31) / 32);
+    l.log_slots = c->window < lazyev::kLogSlotsMax ? c->window : lazyev::kLogSlotsMax;
+    off = align_up(off + static_cast<size_t>(c->n_layers) * l.log_slots * units * l.log_words * sizeof(uint32_t));
+  }
   l.activations = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * lazyev::decode_slice_max() * sizeof(unsigned long long));
   l.rows_moved = off; off = align_up(off + static_cast<size_t>(c->n_layers) * units * sizeof(unsigned long long));
   l.ticket = off; off = align_up(off + units * sizeof(int32_t));
@@ -247,10 +265,56 @@ void fill_due(const lazyev_ctx *ctx, int32_t t, lazyev::EvictArgs &a) {
   }
 }
 
-// Applies the tracking of the last fused decode call if it is still pending.
+// Applies the logged calls of layers l0 .. l1 - 1, which all hold the same calls, to TS / MRI.
+hipError_t flush_log_range(lazyev_ctx *ctx, int l0, int l1) {
+  const int n = ctx->log_n[l0];
+  if (n == 0) return hipSuccess;
+  lazyev::FlushArgs f;
+  std::memset(&f, 0, sizeof(f));
+  const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
+  f.ts = ctx->cfg.ts + static_cast<size_t>(l0) * slab;
+  f.mri = ctx->cfg.mri + static_cast<size_t>(l0) * slab;
+  f.bitlog = ctx->bitlog + static_cast<size_t>(l0) * ctx->log_slots * ctx->units * ctx->log_words;
+  f.units = ctx->units; f.capacity = ctx->capacity;
+  f.log_words = ctx->log_words; f.log_slots = ctx->log_slots;
+  f.n_calls = n;
+  for (int s = 0; s < n; ++s) f.t[s] = ctx->log_t[static_cast<size_t>(l0) * ctx->log_slots + s];
+  const hipError_t e = lazyev::launch_track_flush(f, l1 - l0, ctx->stream);
+  if (e == hipSuccess)
+    for (int l = l0; l < l1; ++l) ctx->log_n[l] = 0;
+  return e;
+}
+
+// Applies every layer's logged calls: consecutive layers that hold the same calls (the usual
+// case: all of them) in one launch.
+hipError_t flush_logs(lazyev_ctx *ctx) {
+  if (!ctx->bitlog) return hipSuccess;
+  const int L = ctx->cfg.n_layers;
+  for (int l0 = 0; l0 < L;) {
+    int l1 = l0 + 1;
+    const int n = ctx->log_n[l0];
+    while (l1 < L && ctx->log_n[l1] == n &&
+           std::equal(ctx->log_t.begin() + static_cast<size_t>(l0) * ctx->log_slots,
+                      ctx->log_t.begin() + static_cast<size_t>(l0) * ctx->log_slots + n,
+                      ctx->log_t.begin() + static_cast<size_t>(l1) * ctx->log_slots) &&
+           static_cast<long long>(l1 + 1 - l0) * ctx->units <= 65535)
+      ++l1;
+    const hipError_t e = flush_log_range(ctx, l0, l1);
+    if (e != hipSuccess) return e;
+    l0 = l1;
+  }
+  return hipSuccess;
+}
+
+// Applies all tracking that is still outstanding, in the order of the calls: the logged calls
+// of every layer, then the last fused decode call if its tracking is still pending.  Everything
+// that reads TS / MRI (an eviction, lazyev_stats, the histogram, a caller who asks for the
+// weights) comes through here first.
 hipError_t flush_tracking(lazyev_ctx *ctx) {
-  if (!ctx->pend.valid) return hipSuccess;
-  const hipError_t e = lazyev::launch_track(ctx->pend, ctx->stream);
+  hipError_t e = flush_logs(ctx);
+  if (e != hipSuccess || !ctx->pend.valid) return e;
+  ctx->pend.bitlog = nullptr;                      // (applied at once)
+  e = lazyev::launch_track(ctx->pend, ctx->stream);
   if (e == hipSuccess) ctx->pend.valid = 0;
   return e;
 }
@@ -285,6 +349,8 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
     ctx->last_step.assign(cfg->n_layers, 0);
     ctx->n_evict_events.assign(cfg->n_layers, 0);
     ctx->n_evicted.assign(cfg->n_layers, 0);
+    ctx->log_n.assign(cfg->n_layers, 0);
+    ctx->log_t.assign(static_cast<size_t>(cfg->n_layers) * (l.log_slots > 0 ? l.log_slots : 1), 0);
   } catch (const std::bad_alloc &) {
     delete ctx;
     return LAZYEV_ENOMEM;
@@ -317,7 +383,11 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
   ctx->last_p_stride = 0;
   ctx->prefill_stat = reinterpret_cast<float *>(base + l.prefill_stat);
   ctx->ws.src_index = reinterpret_cast<int32_t *>(base + l.src_index);
-  ctx->ws.sel_keys = l.activations > l.sel_keys ? reinterpret_cast<unsigned long long *>(base + l.sel_keys) : nullptr;
+  ctx->ws.sel_keys = l.bitlog > l.sel_keys ? reinterpret_cast<unsigned long long *>(base + l.sel_keys) : nullptr;
+  ctx->bitlog = l.log_slots > 0 ? reinterpret_cast<uint32_t *>(base + l.bitlog) : nullptr;
+  ctx->log_words = l.log_words;
+  ctx->log_slots = l.log_slots;
+  ctx->pend_layer = -1;
   ctx->ws.activations = reinterpret_cast<unsigned long long *>(base + l.activations);
   ctx->ws.rows_moved = reinterpret_cast<unsigned long long *>(base + l.rows_moved);
   ctx->ws.ticket = reinterpret_cast<int32_t *>(base + l.ticket);
@@ -437,7 +507,24 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     a.chunk = 16;
     a.logits_out = ctx->ws.logits[ctx->cur_buf];
     a.stat_out = ctx->ws.stat[ctx->cur_buf];
+    if (p_out || p_override) {                     // the caller looks at the weights of this call at once:
+      const hipError_t ef = flush_tracking(ctx);   // everything older is applied first, in order
+      if (ef != hipSuccess) return fail_hip(ctx, ef);
+    }
     a.track = ctx->pend;                           // the previous call's tracking rides along
+    if (a.track.valid && ctx->bitlog && !ctx->slots_on && ctx->pend_layer >= 0) {
+      // ... as one bit per cache entry in the next free slot of its layer's log (a full log is
+      // applied first)
+      const int ly = ctx->pend_layer;
+      if (ctx->log_n[ly] == ctx->log_slots) {
+        const hipError_t ef = flush_log_range(ctx, ly, ly + 1);
+        if (ef != hipSuccess) return fail_hip(ctx, ef);
+      }
+      const int slot = ctx->log_n[ly];
+      a.track.bitlog = ctx->bitlog + (static_cast<size_t>(ly) * ctx->log_slots + slot) * ctx->units * ctx->log_words;
+      a.track.log_words = ctx->log_words;
+      ctx->log_t[static_cast<size_t>(ly) * ctx->log_slots + slot] = a.track.t;
+    }
     a.p_stride = static_cast<int32_t>(fused_p_stride(ctx->capacity));
     // candidate lists instead of every logit, unless somebody reads the logits as such (the
     // caller through p_out / p_override, or an eviction that ranks by this call's weights): the
@@ -487,7 +574,9 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
   ctx->len[layer] = n_old + 1;
   ctx->last_step[layer] = t;
   ctx->last_layer = kind == 4 ? layer : -1;
+  if (kind == 4 && a.track.valid && a.track.bitlog) ctx->log_n[ctx->pend_layer] += 1;   // (that call is in the log now)
   if (kind == 4) {
+    ctx->pend_layer = layer;
     ctx->last_logits = a.logits_out; ctx->last_stat = a.stat_out; ctx->last_p_stride = a.p_stride;
     lazyev::TrackArgs &k = ctx->pend;              // this call's tracking: with the next launch
     std::memset(&k, 0, sizeof(k));
@@ -889,6 +978,21 @@ int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score
   const hipError_t e = lazyev::launch_score_pairs(delta_t, mri, score, n, score_flags,
                                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LAZYEV_OK : LAZYEV_EHIP;
+}
+
+int32_t lazyev_log_words(lazyev_ctx *ctx) { return ctx && ctx->bitlog ? ctx->log_words : 0; }
+
+int lazyev_log_peek(lazyev_ctx *ctx, int32_t layer, int32_t back, uint32_t *words, int32_t *t) {
+  if (!ctx || !words || layer < 0 || layer >= ctx->cfg.n_layers || back < 0) return LAZYEV_EINVAL;
+  if (!ctx->bitlog || back >= ctx->log_n[layer]) return LAZYEV_EINVAL;
+  const int slot = ctx->log_n[layer] - 1 - back;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e == hipSuccess)
+    e = hipMemcpy(words, ctx->bitlog + (static_cast<size_t>(layer) * ctx->log_slots + slot) * ctx->units * ctx->log_words,
+                  static_cast<size_t>(ctx->units) * ctx->log_words * sizeof(uint32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (t) *t = ctx->log_t[static_cast<size_t>(layer) * ctx->log_slots + slot];
+  return LAZYEV_OK;
 }
 
 int lazyev_profile_arm(lazyev_ctx *ctx, int32_t n_calls) {

@@ -232,12 +232,15 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
     the candidate lists) and lazyev_evict_all after every step at which an eviction is due.
 
     The oracle follows the listed (layer, seq, kv_head) units on its own fp64 weights.  What the
-    library decided at a call is read from TS after the NEXT call has been enqueued (an entry
-    older than the call's appended one has TS == t exactly if the call activated it); before a
-    due eviction lazyev_stats applies the last call's tracking, which is what lazyev_evict_all
-    would do first anyway.  A differing decision is accepted only within tol * alpha of the
-    threshold (counted, adopted); TS / MRI are compared after every call, survivor sets, TS,
-    MRI, pos (and rows) after every eviction, outputs at every call.
+    library decided at a call is read after the NEXT call has been enqueued: from the activation
+    log, in which that launch leaves one bit per entry (lazyev_log_peek looks at it and applies
+    nothing), or, for a configuration without a log, from TS (an entry older than the call's
+    appended one has TS == t exactly if the call activated it).  Before a due eviction
+    lazyev_stats applies everything outstanding, which is what lazyev_evict_all would do first
+    anyway.  A differing decision is accepted only within tol * alpha of the threshold (counted,
+    adopted); TS / MRI are compared whenever the library has applied its tracking (after every
+    call without a log; with one, before every eviction and at the end), survivor sets, TS, MRI,
+    pos (and rows) after every eviction, outputs at every call.
     """
     wl = Workload(cfg)
     tol = TOL[cfg.dtype]
@@ -257,14 +260,20 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
                 max_out_err=0.0, compact_calls=0)
     n_len = cfg.prompt_len                      # entries per unit before the next append
 
-    def resolve(call):
-        """Oracle step for a finished call whose tracking the library has applied."""
+    def resolve(call, applied=False):
+        """Oracle step for a finished call whose tracking the library has logged or (applied)
+        written to TS / MRI."""
         l, t, n1, cpu_rows = call
         mine = by_layer[l]
         if not mine:
             return
         ss = torch.tensor([u[1] for u in mine], device=dev)
         hh = torch.tensor([u[2] for u in mine], device=dev)
+        logged = None if applied else eng.log_peek(l, 0)
+        if logged is not None:
+            assert logged[0] == t, ("the layer's latest logged call", l, t, logged[0])
+            stat["logged_calls"] = stat.get("logged_calls", 0) + 1
+            act_log = logged[1][ss.cpu().numpy(), hh.cpu().numpy()]
         ts_g = eng.ts[l][ss, hh, :n1].cpu().numpy()
         mri_g = eng.mri[l][ss, hh, :n1].cpu().numpy()
         o_gpu = out[t % 2, l].float().cpu().numpy().astype(np.float64)
@@ -273,8 +282,8 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
             rows = slice(h * G, (h + 1) * G)
 
             def adopt(p, act, k_u=k_u):
-                act_gpu = act.copy()
-                act_gpu[:n1 - 1] = ts_g[k_u, :n1 - 1] == t      # (the appended entry's own flag is not visible)
+                act_gpu = act.copy()                            # (the appended entry's own flag is not visible)
+                act_gpu[:n1 - 1] = act_log[k_u, :n1 - 1] if logged is not None else ts_g[k_u, :n1 - 1] == t
                 diff = np.nonzero(act != act_gpu)[0]
                 for j in diff:
                     near = np.abs(p[:, j] - cfg.alpha) <= tol * cfg.alpha
@@ -285,8 +294,11 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
             cq, ck, cv = cpu_rows[u]
             o, p, act = orc[u].decode_step(t, cq, ck, cv, act_override=adopt)
             _compare_out(o_gpu[s, rows], o, tol, stat, (u, t))
-            assert np.array_equal(ts_g[k_u], orc[u].TS), ("TS", u, t)
-            assert np.array_equal(mri_g[k_u], orc[u].MRI), ("MRI", u, t)
+            if logged is None:                                  # (TS / MRI hold this call's tracking)
+                assert np.array_equal(ts_g[k_u], orc[u].TS), ("TS", u, t)
+                assert np.array_equal(mri_g[k_u], orc[u].MRI), ("MRI", u, t)
+            else:
+                assert not act_log[k_u, n1 - 1:].any(), ("bits beyond the call's entries", u, t)
             stat["decisions"] += n1
         stat["calls_checked"] += 1
 
@@ -310,8 +322,8 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
                                       for u in by_layer[l]})
             n_len = n1
             if t % cfg.window == 0 and n_len > cfg.budget:
-                eng.stats()                          # the last call's tracking, as lazyev_evict_all applies it
-                resolve(pending)
+                eng.stats()                          # all outstanding tracking, as lazyev_evict_all applies it
+                resolve(pending, applied=True)
                 pending = None
                 n_ev = eng.evict_all(t)
                 assert n_ev == n_len - cfg.budget, (t, n_ev)
@@ -328,7 +340,7 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
             log("t=%d %s" % (t1 - 1, stat))
     st = eng.stats()
     if pending is not None:
-        resolve(pending)
+        resolve(pending, applied=True)
     for l in range(L):
         assert st["last_step"][l] == steps and st["len"][l] == n_len
         if by_layer[l]:
