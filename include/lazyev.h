@@ -148,10 +148,13 @@ int lazyev_prefill_track_seq(lazyev_ctx *ctx, int32_t layer, int32_t seq, const 
  *   an entry is active if any query head of its group has probability >= alpha (fp32 compare);
  *   active entries get MRI = max(MRI, t - TS), then TS = t.
  * `out` and the appended K/V rows are complete when the call's work on the stream is.  The
- * single-launch attention kernel (see lazyev_set_variant) applies the updates of ts / mri / pos
- * with the NEXT call on the context (any layer), with lazyev_evict when an eviction is due, or
- * with lazyev_stats, whichever comes first, and at once when p_out or p_override is given.  A
- * caller that reads ts / mri / pos itself calls lazyev_stats first.
+ * single-launch attention kernel (see lazyev_set_variant) works out which entries were active
+ * with the NEXT call on the context (any layer) and keeps that as one bit per entry; the updates
+ * of ts / mri of a layer's calls are applied together, in the order of the calls, before
+ * anything reads them: by lazyev_evict / lazyev_evict_all, lazyev_stats, lazyev_mri_histogram,
+ * lazyev_admit / lazyev_retire, after at most min(W, 256) calls of the layer, and at once when
+ * p_out or p_override is given.  A caller that reads ts / mri / pos itself calls lazyev_stats
+ * first.
  * t must be the layer's previous step + 1 (first step is 1).
  * p_out (device, nullable): receives the fp32 probabilities the threshold test used, entries
  *   [0, N+1) of each row.
