@@ -57,12 +57,13 @@ int lazyev_set_spin_ticks(lazyev_ctx *ctx, uint32_t ticks);
  * was active, i.e. some head of the group gave it a weight >= alpha; the call's appended entry
  * has no bit), applied to TS / MRI in step order before anything reads them (an eviction,
  * lazyev_stats, lazyev_mri_histogram, a call with p_out / p_override).  lazyev_log_words: 32-bit
- * words per unit, 0 if this configuration keeps no log.  lazyev_log_peek copies the words of
- * all units [batch * n_kv_heads][log_words] of the latest logged call of `layer` (back = 0) or
- * of the one `back` calls before it to `words` (host) and its step to *t (host, nullable); it
- * waits for the stream and applies nothing.  Errors: EINVAL (no such logged call), EHIP. */
+ * words per unit, 0 if this configuration keeps no log.  lazyev_log_peek copies the log_words
+ * words of unit `unit` (= sequence * n_kv_heads + KV head) of the latest logged call of `layer`
+ * (back = 0) or of the one `back` calls before it to `words` (host) and its step to *t (host,
+ * nullable); it waits for the stream and applies nothing.  Errors: EINVAL (no such logged
+ * call), EHIP. */
 int32_t lazyev_log_words(lazyev_ctx *ctx);
-int lazyev_log_peek(lazyev_ctx *ctx, int32_t layer, int32_t back, uint32_t *words, int32_t *t);
+int lazyev_log_peek(lazyev_ctx *ctx, int32_t layer, int32_t back, int32_t unit, uint32_t *words, int32_t *t);
 
 /* Profiling aid.  lazyev_profile_arm makes the next n_calls calls that launch kernels
  * (decode_step, or an evict that is due) record HIP events on the stream before, between and

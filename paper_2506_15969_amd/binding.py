@@ -125,7 +125,7 @@ lib.lazyev_profile_arm.argtypes = [C.c_void_p, C.c_int32]
 lib.lazyev_log_words.restype = C.c_int32
 lib.lazyev_log_words.argtypes = [C.c_void_p]
 lib.lazyev_log_peek.restype = C.c_int
-lib.lazyev_log_peek.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]
+lib.lazyev_log_peek.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_int32)]
 lib.lazyev_profile_read.restype = C.c_int
 lib.lazyev_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.lazyev_destroy.restype = None
@@ -308,21 +308,23 @@ class LazyEviction:
     def set_spin_ticks(self, ticks: int):
         _check(lib.lazyev_set_spin_ticks(self._ctx, ticks), "lazyev_set_spin_ticks")
 
-    def log_peek(self, layer: int, back: int = 0):
-        """lazyev_log_peek: (step, bool array [batch, n_kv_heads, 32 * log_words]) of a logged call,
-        or None if the layer has no such call in its activation log."""
+    def log_peek(self, layer: int, units, back: int = 0):
+        """lazyev_log_peek for the (sequence, kv_head) pairs in `units`: (step, bool array
+        [len(units), 32 * log_words]) of a logged call, or None if the layer has no such call in
+        its activation log."""
         import numpy as np
         words = lib.lazyev_log_words(self._ctx)
         if words <= 0:
             return None
-        units = self.cfg.batch * self.cfg.n_kv_heads
-        buf = (C.c_uint32 * (units * words))()
+        buf = (C.c_uint32 * words)()
         t = C.c_int32(0)
-        if lib.lazyev_log_peek(self._ctx, layer, back, buf, C.byref(t)) != 0:
-            return None
-        a = np.frombuffer(buf, dtype=np.uint32).reshape(self.cfg.batch, self.cfg.n_kv_heads, words)
-        bits = np.unpackbits(a.view(np.uint8), axis=-1, bitorder="little").astype(bool)
-        return t.value, bits
+        rows = []
+        for (seq, kvh) in units:
+            if lib.lazyev_log_peek(self._ctx, layer, back, seq * self.cfg.n_kv_heads + kvh, buf, C.byref(t)) != 0:
+                return None
+            a = np.frombuffer(buf, dtype=np.uint32).copy()
+            rows.append(np.unpackbits(a.view(np.uint8), bitorder="little").astype(bool))
+        return t.value, np.stack(rows)
 
     def profile_arm(self, n_calls: int):
         _check(lib.lazyev_profile_arm(self._ctx, n_calls), "lazyev_profile_arm")

@@ -379,32 +379,61 @@ __global__ __launch_bounds__(kBlock) void track_kernel(const TrackArgs k_all, in
 
 // The logged calls of a layer applied to TS / MRI: one thread per cache entry, the calls in step
 // order.  An entry's bit in the words of a call says that it was active there (TrackArgs::bitlog).
+// Block b works on the kFlushSpan entries from kFlushSpan * (b % spans) on of unit (b / spans) % units
+// of layer b / spans / units, spans = blocks per unit.  The span's 32 words of every logged call
+// go to LDS first (all requested together: one memory round trip), then every thread walks the
+// calls for its four entries.
+constexpr int kFlushSpan = 4 * kBlock;
 __global__ __launch_bounds__(kBlock) void track_flush_kernel(const FlushArgs f) {
-  const int layer = blockIdx.x / f.units, unit = blockIdx.x % f.units;
+  __shared__ uint32_t lw[kLogSlotsMax * (kFlushSpan / 32)];
+  __shared__ int32_t lt[kLogSlotsMax];             // the calls' steps (an indexed read of the argument block costs a scalar load each time)
+  constexpr int kSpanWords = kFlushSpan / 32;
+  const int spans = (f.capacity + kFlushSpan - 1) / kFlushSpan;
+  const int span = blockIdx.x % spans, lu = blockIdx.x / spans;
+  const int layer = lu / f.units, unit = lu % f.units;
   const size_t slab = (static_cast<size_t>(layer) * f.units + unit) * f.capacity;
-  const uint32_t *log = f.bitlog + (static_cast<size_t>(layer) * f.log_slots * f.units + unit) * f.log_words;
-  const size_t slot_stride = static_cast<size_t>(f.units) * f.log_words;
-  constexpr int kAhead = 8;                        // words of this many calls requested together
-  for (int i = threadIdx.x; i < f.capacity; i += kBlock) {
-    const uint32_t bit = 1u << (i & 31);
-    const uint32_t *w = log + (i >> 5);
-    int32_t ts = 0, mri = 0;
+  const uint32_t *log = f.bitlog + (static_cast<size_t>(layer) * f.units + unit) * f.log_slots * f.log_words +
+                        span * kSpanWords;           // (a unit's slots lie together: a stream of n_calls * log_words words)
+  const size_t slot_stride = static_cast<size_t>(f.log_words);
+  const int n_words = min(kSpanWords, f.log_words - span * kSpanWords);
+  for (int x = threadIdx.x; x < f.n_calls * kSpanWords; x += kBlock) {
+    const int s = x / kSpanWords, j = x % kSpanWords;
+    lw[x] = j < n_words ? log[s * slot_stride + j] : 0u;
+  }
+  for (int s = threadIdx.x; s < f.n_calls; s += kBlock) lt[s] = f.t[s];
+  int32_t ts[4], mri[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {                    // (requested while the words travel)
+    const int i = span * kFlushSpan + e * kBlock + static_cast<int>(threadIdx.x);
+    ts[e] = mri[e] = 0;
+    if (i < f.capacity) { ts[e] = f.ts[slab + i]; mri[e] = f.mri[slab + i]; }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int il = e * kBlock + static_cast<int>(threadIdx.x), i = span * kFlushSpan + il;
+    if (i >= f.capacity) continue;
+    const uint32_t *w = lw + (il >> 5);
     bool touched = false;
-    for (int s0 = 0; s0 < f.n_calls; s0 += kAhead) {
-      uint32_t v[kAhead];
+    const int sh = il & 31;
+    for (int s0 = 0; s0 < f.n_calls; s0 += 32) {   // 32 calls at a time: in which of them was the entry active?
+      unsigned calls = 0;
+      const int n32 = min(32, f.n_calls - s0);
 #pragma unroll
-      for (int d = 0; d < kAhead; ++d) v[d] = w[static_cast<size_t>(min(s0 + d, f.n_calls - 1)) * slot_stride];
-#pragma unroll
-      for (int d = 0; d < kAhead; ++d) {
-        if (s0 + d < f.n_calls && (v[d] & bit)) {
-          if (!touched) { ts = f.ts[slab + i]; mri = f.mri[slab + i]; touched = true; }
-          const int32_t gap = f.t[s0 + d] - ts;
-          if (gap > mri) mri = gap;                // Eq. 1
-          ts = f.t[s0 + d];                        // Alg. 1
-        }
+      for (int d = 0; d < 32; ++d)                 // (no branch in here: the LDS reads overlap; reads beyond the
+        calls |= ((w[min(s0 + d, f.n_calls - 1) * kSpanWords] >> sh) & 1u) << d;   // last call repeat it and are masked)
+      calls &= n32 == 32 ? ~0u : (1u << n32) - 1u;
+      while (calls) {                              // ... and those, in step order
+        const int s = s0 + __builtin_ctz(calls);
+        calls &= calls - 1;
+        const int32_t t_s = lt[s];
+        const int32_t gap = t_s - ts[e];
+        if (gap > mri[e]) mri[e] = gap;            // Eq. 1
+        ts[e] = t_s;                               // Alg. 1
+        touched = true;
       }
     }
-    if (touched) { f.ts[slab + i] = ts; f.mri[slab + i] = mri; }
+    if (touched) { f.ts[slab + i] = ts[e]; f.mri[slab + i] = mri[e]; }
   }
 }
 
@@ -653,7 +682,7 @@ __global__ __launch_bounds__(kListWaves ? 2 * kBlock : kBlock, 4) void decode_fu
       // whose records this tracking block reads if the block's index is its own modulo n_split
       __syncthreads();
       const int parts = k.compact ? k.n_parts : n_split;
-      uint32_t *dst = k.bitlog + static_cast<size_t>(unit) * k.log_words;
+      uint32_t *dst = k.bitlog + static_cast<size_t>(unit) * k.log_unit_stride;
       for (int j = threadIdx.x; j < k.log_words; j += kBlock) {
         const int wv = (2 * j) % (kWaves * parts);
         const int owner = (parts - 1 - wv / kWaves) % n_split;
@@ -1240,7 +1269,8 @@ hipError_t launch_track_flush(const FlushArgs &f, int n_layers, hipStream_t stre
       f.log_words < (f.capacity + 31) / 32 || f.n_calls < 0 || f.n_calls > f.log_slots || f.log_slots > kLogSlotsMax)
     return hipErrorInvalidValue;
   if (f.n_calls == 0) return hipSuccess;
-  hipLaunchKernelGGL(track_flush_kernel, dim3(static_cast<unsigned>(n_layers) * f.units), dim3(kBlock), 0, stream, f);
+  const unsigned spans = static_cast<unsigned>((f.capacity + kFlushSpan - 1) / kFlushSpan);
+  hipLaunchKernelGGL(track_flush_kernel, dim3(static_cast<unsigned>(n_layers) * f.units * spans), dim3(kBlock), 0, stream, f);
   return hipGetLastError();
 }
 
@@ -1270,6 +1300,7 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
        !decode_fused_compact_fits(a.track.n_old, a.track.n_parts, a.track.p_stride, a.track.group)) ||
       (a.track.valid && a.track.bitlog &&
        (a.track.log_words < (a.track.capacity + 31) / 32 || a.track.log_words > decode_fused_log_words_max() ||
+        a.track.log_unit_stride < a.track.log_words ||
         a.track.slots.prompt_len)) ||
       (a.variant == 6 && (a.p_out || a.p_override || !decode_fused_compact_fits(a.n_old, a.n_split, a.p_stride, a.group))))
     return hipErrorInvalidValue;

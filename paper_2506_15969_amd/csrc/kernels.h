@@ -73,8 +73,8 @@ struct TrackArgs {
   // leave ONE BIT per cache entry of the unit, bit i = entry i was active in this call, as
   // log_words 32-bit words here; track_flush_kernel applies the logged calls of a layer in step
   // order (Eq. 1) before anything reads TS / MRI.  The appended entry is still started at once.
-  uint32_t *bitlog;                 // this call's words of unit 0; unit u's follow at u * log_words
-  int32_t log_words;
+  uint32_t *bitlog;                 // this call's words of unit 0; unit u's follow at u * log_unit_stride
+  int32_t log_words, log_unit_stride;   // (a unit's slots lie together: stride = log_slots * log_words)
 };
 
 // The logged calls of one or several layers applied to TS / MRI (Alg. 1 first loop, Eq. 1, in the
@@ -82,7 +82,7 @@ struct TrackArgs {
 constexpr int kLogSlotsMax = 256;
 struct FlushArgs {
   int32_t *ts, *mri;                // first layer's slab; the other layers' follow
-  const uint32_t *bitlog;           // [layer][log_slots][units][log_words], first layer of the launch
+  const uint32_t *bitlog;           // [layer][units][log_slots][log_words], first layer of the launch
   int32_t units, capacity, log_words, log_slots;
   int32_t n_calls;                  // logged calls to apply: slots 0 .. n_calls - 1
   int32_t t[kLogSlotsMax];          // step of the call in slot s (what TS becomes)

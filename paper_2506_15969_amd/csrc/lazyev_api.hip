@@ -137,7 +137,7 @@ Layout layout_of(const lazyev_config *c) {
   l.sel_keys = off;
   if (cap - c->window > static_cast<size_t>(lazyev::evict_lds_candidates()))
     off = align_up(off + static_cast<size_t>(c->n_layers) * units * cap * sizeof(unsigned long long));
-  // activation log of the single-launch kernel: [layer][slot][unit][one bit per cache entry], as
+  // activation log of the single-launch kernel: [layer][unit][slot][one bit per cache entry], as
   // many slots as calls lie between two evictions (at most kLogSlotsMax; a full log is applied)
   l.bitlog = off;
   l.log_words = 0; l.log_slots = 0;
@@ -521,8 +521,9 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
         if (ef != hipSuccess) return fail_hip(ctx, ef);
       }
       const int slot = ctx->log_n[ly];
-      a.track.bitlog = ctx->bitlog + (static_cast<size_t>(ly) * ctx->log_slots + slot) * ctx->units * ctx->log_words;
+      a.track.bitlog = ctx->bitlog + (static_cast<size_t>(ly) * ctx->units * ctx->log_slots + slot) * ctx->log_words;
       a.track.log_words = ctx->log_words;
+      a.track.log_unit_stride = ctx->log_slots * ctx->log_words;
       ctx->log_t[static_cast<size_t>(ly) * ctx->log_slots + slot] = a.track.t;
     }
     a.p_stride = static_cast<int32_t>(fused_p_stride(ctx->capacity));
@@ -982,14 +983,16 @@ int lazyev_score_pairs(const int32_t *delta_t, const int32_t *mri, double *score
 
 int32_t lazyev_log_words(lazyev_ctx *ctx) { return ctx && ctx->bitlog ? ctx->log_words : 0; }
 
-int lazyev_log_peek(lazyev_ctx *ctx, int32_t layer, int32_t back, uint32_t *words, int32_t *t) {
-  if (!ctx || !words || layer < 0 || layer >= ctx->cfg.n_layers || back < 0) return LAZYEV_EINVAL;
+int lazyev_log_peek(lazyev_ctx *ctx, int32_t layer, int32_t back, int32_t unit, uint32_t *words, int32_t *t) {
+  if (!ctx || !words || layer < 0 || layer >= ctx->cfg.n_layers || back < 0 || unit < 0 || unit >= ctx->units)
+    return LAZYEV_EINVAL;
   if (!ctx->bitlog || back >= ctx->log_n[layer]) return LAZYEV_EINVAL;
   const int slot = ctx->log_n[layer] - 1 - back;
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess)
-    e = hipMemcpy(words, ctx->bitlog + (static_cast<size_t>(layer) * ctx->log_slots + slot) * ctx->units * ctx->log_words,
-                  static_cast<size_t>(ctx->units) * ctx->log_words * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    e = hipMemcpy(words,
+                  ctx->bitlog + ((static_cast<size_t>(layer) * ctx->units + unit) * ctx->log_slots + slot) * ctx->log_words,
+                  ctx->log_words * sizeof(uint32_t), hipMemcpyDeviceToHost);
   if (e != hipSuccess) return fail_hip(ctx, e);
   if (t) *t = ctx->log_t[static_cast<size_t>(layer) * ctx->log_slots + slot];
   return LAZYEV_OK;

@@ -269,11 +269,11 @@ def run_timed_path(binding, cfg: WorkloadConfig, units, steps=None, gen_block=32
             return
         ss = torch.tensor([u[1] for u in mine], device=dev)
         hh = torch.tensor([u[2] for u in mine], device=dev)
-        logged = None if applied else eng.log_peek(l, 0)
+        logged = None if applied else eng.log_peek(l, [(u[1], u[2]) for u in mine])
         if logged is not None:
             assert logged[0] == t, ("the layer's latest logged call", l, t, logged[0])
             stat["logged_calls"] = stat.get("logged_calls", 0) + 1
-            act_log = logged[1][ss.cpu().numpy(), hh.cpu().numpy()]
+            act_log = logged[1]
         ts_g = eng.ts[l][ss, hh, :n1].cpu().numpy()
         mri_g = eng.mri[l][ss, hh, :n1].cpu().numpy()
         o_gpu = out[t % 2, l].float().cpu().numpy().astype(np.float64)
