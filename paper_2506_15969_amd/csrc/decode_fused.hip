@@ -234,9 +234,11 @@ __device__ __forceinline__ bool track_one(const TrackArgs &k, int unit, int i, c
     }
   }
   if (i == k.n_old) {                              // the appended entry starts here (Sec. 4)
-    ts[i] = k.t;
-    mri[i] = 0;
-    k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
+    if (!log_mask) {                               // (of a logged call: when the log is applied)
+      ts[i] = k.t;
+      mri[i] = 0;
+      k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
+    }
   } else if (act) {                                // few entries are active: TS / MRI are read only here
     if (log_mask) {
       atomicOr(log_mask + (i >> 5), 1u << (i & 31));
@@ -278,9 +280,11 @@ __device__ __forceinline__ unsigned track_apply(const TrackArgs &k, int unit, in
       }
     }
     if (i == n_old) {                              // the appended entry starts here (Sec. 4)
-      ts[i] = k.t;
-      mri[i] = 0;
-      k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
+      if (!log_mask) {                             // (of a logged call: when the log is applied)
+        ts[i] = k.t;
+        mri[i] = 0;
+        k.pos[static_cast<size_t>(unit) * k.capacity + i] = k.prompt_len + k.t - 1;
+      }
     } else if (act) {                              // few entries are active: TS / MRI are read only here
       if (log_mask) {
         atomicOr(log_mask + (i >> 5), 1u << (i & 31));
@@ -387,6 +391,7 @@ constexpr int kFlushSpan = 4 * kBlock;
 __global__ __launch_bounds__(kBlock) void track_flush_kernel(const FlushArgs f) {
   __shared__ uint32_t lw[kLogSlotsMax * (kFlushSpan / 32)];
   __shared__ int32_t lt[kLogSlotsMax];             // the calls' steps (an indexed read of the argument block costs a scalar load each time)
+  __shared__ int32_t lo[kLogSlotsMax];             // the entries the calls appended
   constexpr int kSpanWords = kFlushSpan / 32;
   const int spans = (f.capacity + kFlushSpan - 1) / kFlushSpan;
   const int span = blockIdx.x % spans, lu = blockIdx.x / spans;
@@ -400,7 +405,7 @@ __global__ __launch_bounds__(kBlock) void track_flush_kernel(const FlushArgs f) 
     const int s = x / kSpanWords, j = x % kSpanWords;
     lw[x] = j < n_words ? log[s * slot_stride + j] : 0u;
   }
-  for (int s = threadIdx.x; s < f.n_calls; s += kBlock) lt[s] = f.t[s];
+  for (int s = threadIdx.x; s < f.n_calls; s += kBlock) { lt[s] = f.t[s]; lo[s] = f.n_old[s]; }
   int32_t ts[4], mri[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {                    // (requested while the words travel)
@@ -416,6 +421,23 @@ __global__ __launch_bounds__(kBlock) void track_flush_kernel(const FlushArgs f) 
     const uint32_t *w = lw + (il >> 5);
     bool touched = false;
     const int sh = il & 31;
+    // An entry that one of the calls appended starts there (Sec. 4): no earlier call has a bit for
+    // it, so it is started before the bits are walked.  (Calls of consecutive steps append
+    // consecutive entries: the first guess is right unless steps were left out.)
+    {
+      int s_new = i - lo[0];
+      if (s_new < 0 || s_new >= f.n_calls || lo[s_new] != i) {
+        s_new = -1;
+        if (i >= lo[0] && i <= lo[f.n_calls - 1])
+          for (int s = 0; s < f.n_calls; ++s) s_new = lo[s] == i ? s : s_new;
+      }
+      if (s_new >= 0) {
+        ts[e] = lt[s_new];
+        mri[e] = 0;
+        f.pos[slab + i] = f.prompt_len + lt[s_new] - 1;
+        touched = true;
+      }
+    }
     for (int s0 = 0; s0 < f.n_calls; s0 += 32) {   // 32 calls at a time: in which of them was the entry active?
       unsigned calls = 0;
       const int n32 = min(32, f.n_calls - s0);
@@ -1265,7 +1287,7 @@ hipError_t launch_track(const TrackArgs &k, hipStream_t stream) {
 int decode_fused_log_words_max() { return static_cast<int>(sizeof(u32x4_t) * kWaves * 256 / sizeof(unsigned)); }
 
 hipError_t launch_track_flush(const FlushArgs &f, int n_layers, hipStream_t stream) {
-  if (!f.ts || !f.mri || !f.bitlog || f.units < 1 || n_layers < 1 || f.capacity < 1 ||
+  if (!f.ts || !f.mri || !f.pos || !f.bitlog || f.units < 1 || n_layers < 1 || f.capacity < 1 ||
       f.log_words < (f.capacity + 31) / 32 || f.n_calls < 0 || f.n_calls > f.log_slots || f.log_slots > kLogSlotsMax)
     return hipErrorInvalidValue;
   if (f.n_calls == 0) return hipSuccess;

@@ -72,7 +72,7 @@ struct TrackArgs {
   // TS / MRI of the active entries (a 128-byte line read and written for every 4-byte word) but
   // leave ONE BIT per cache entry of the unit, bit i = entry i was active in this call, as
   // log_words 32-bit words here; track_flush_kernel applies the logged calls of a layer in step
-  // order (Eq. 1) before anything reads TS / MRI.  The appended entry is still started at once.
+  // order (Eq. 1) before anything reads TS / MRI, and starts the entries those calls appended.
   uint32_t *bitlog;                 // this call's words of unit 0; unit u's follow at u * log_unit_stride
   int32_t log_words, log_unit_stride;   // (a unit's slots lie together: stride = log_slots * log_words)
 };
@@ -81,11 +81,13 @@ struct TrackArgs {
 // order of the calls).  Block b works on layer b / units, unit b % units.
 constexpr int kLogSlotsMax = 256;
 struct FlushArgs {
-  int32_t *ts, *mri;                // first layer's slab; the other layers' follow
+  int32_t *ts, *mri, *pos;          // first layer's slab; the other layers' follow
+  int32_t prompt_len;
   const uint32_t *bitlog;           // [layer][units][log_slots][log_words], first layer of the launch
   int32_t units, capacity, log_words, log_slots;
   int32_t n_calls;                  // logged calls to apply: slots 0 .. n_calls - 1
   int32_t t[kLogSlotsMax];          // step of the call in slot s (what TS becomes)
+  int32_t n_old[kLogSlotsMax];      // the entry that call appended (it starts with TS = t, MRI = 0, pos = P + t - 1)
 };
 
 struct DecodeArgs {

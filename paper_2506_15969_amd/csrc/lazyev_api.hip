@@ -51,6 +51,7 @@ struct lazyev_ctx {
   int32_t log_words, log_slots;
   std::vector<int32_t> log_n;       // per layer: logged calls
   std::vector<int32_t> log_t;       // [layer][log_slots]: their steps
+  std::vector<int32_t> log_n_old;   // [layer][log_slots]: the entries they appended
   // the last decode call, if the fused kernel ran it: its logits and statistics are still in
   // the workspace (what an eviction that ranks by that step's weights reads)
   int32_t last_layer;
@@ -274,11 +275,16 @@ hipError_t flush_log_range(lazyev_ctx *ctx, int l0, int l1) {
   const size_t slab = static_cast<size_t>(ctx->units) * ctx->capacity;
   f.ts = ctx->cfg.ts + static_cast<size_t>(l0) * slab;
   f.mri = ctx->cfg.mri + static_cast<size_t>(l0) * slab;
+  f.pos = ctx->cfg.pos + static_cast<size_t>(l0) * slab;
+  f.prompt_len = ctx->cfg.prompt_len;
   f.bitlog = ctx->bitlog + static_cast<size_t>(l0) * ctx->log_slots * ctx->units * ctx->log_words;
   f.units = ctx->units; f.capacity = ctx->capacity;
   f.log_words = ctx->log_words; f.log_slots = ctx->log_slots;
   f.n_calls = n;
-  for (int s = 0; s < n; ++s) f.t[s] = ctx->log_t[static_cast<size_t>(l0) * ctx->log_slots + s];
+  for (int s = 0; s < n; ++s) {
+    f.t[s] = ctx->log_t[static_cast<size_t>(l0) * ctx->log_slots + s];
+    f.n_old[s] = ctx->log_n_old[static_cast<size_t>(l0) * ctx->log_slots + s];
+  }
   const hipError_t e = lazyev::launch_track_flush(f, l1 - l0, ctx->stream);
   if (e == hipSuccess)
     for (int l = l0; l < l1; ++l) ctx->log_n[l] = 0;
@@ -297,6 +303,9 @@ hipError_t flush_logs(lazyev_ctx *ctx) {
            std::equal(ctx->log_t.begin() + static_cast<size_t>(l0) * ctx->log_slots,
                       ctx->log_t.begin() + static_cast<size_t>(l0) * ctx->log_slots + n,
                       ctx->log_t.begin() + static_cast<size_t>(l1) * ctx->log_slots) &&
+           std::equal(ctx->log_n_old.begin() + static_cast<size_t>(l0) * ctx->log_slots,
+                      ctx->log_n_old.begin() + static_cast<size_t>(l0) * ctx->log_slots + n,
+                      ctx->log_n_old.begin() + static_cast<size_t>(l1) * ctx->log_slots) &&
            static_cast<long long>(l1 + 1 - l0) * ctx->units <= 65535)
       ++l1;
     const hipError_t e = flush_log_range(ctx, l0, l1);
@@ -351,6 +360,7 @@ int lazyev_init(const lazyev_config *cfg, lazyev_ctx **out) {
     ctx->n_evicted.assign(cfg->n_layers, 0);
     ctx->log_n.assign(cfg->n_layers, 0);
     ctx->log_t.assign(static_cast<size_t>(cfg->n_layers) * (l.log_slots > 0 ? l.log_slots : 1), 0);
+    ctx->log_n_old.assign(ctx->log_t.size(), 0);
   } catch (const std::bad_alloc &) {
     delete ctx;
     return LAZYEV_ENOMEM;
@@ -525,6 +535,7 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
       a.track.log_words = ctx->log_words;
       a.track.log_unit_stride = ctx->log_slots * ctx->log_words;
       ctx->log_t[static_cast<size_t>(ly) * ctx->log_slots + slot] = a.track.t;
+      ctx->log_n_old[static_cast<size_t>(ly) * ctx->log_slots + slot] = a.track.n_old;
     }
     a.p_stride = static_cast<int32_t>(fused_p_stride(ctx->capacity));
     // candidate lists instead of every logit, unless somebody reads the logits as such (the
