@@ -37,6 +37,10 @@
 // and statistics (>= alpha test over the query group, TS / MRI update, start of the appended
 // entry) while the new call streams; lazyev_evict and lazyev_stats apply what is pending
 // through track_kernel.  Logits and statistics are double-buffered.
+// In a uniform batch the tracking blocks do not touch TS / MRI themselves (a 128-byte line read
+// and written for every 4-byte word of an active entry, beside the stream): they leave one bit
+// per cache entry in the layer's activation log, and track_flush_kernel applies the logged calls
+// in step order before anything reads TS / MRI (TrackArgs::bitlog).
 //
 // Candidate lists (kernel instances <true, ..>, groups of at most 7 heads; every call whose
 // logits nobody reads as such).  A block knows, once its four stream waves are done, its own
