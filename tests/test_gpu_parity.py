@@ -264,6 +264,48 @@ def test_deferred_tracking_equals_immediate(lazyev_lib, blocks):
         assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
 
 
+@pytest.mark.parametrize("window,budget,steps", [(1, 120, 50), (2, 121, 60), (5, 400, 43), (7, 130, 90)])
+def test_activation_log_with_short_windows(lazyev_lib, window, budget, steps):
+    """The tracking of calls that nobody asks the weights of is kept as one bit per entry and
+    applied to TS / MRI later (before an eviction, by lazyev_stats, or when the log's min(W, 256)
+    slots are full).  Windows of 1, 2 and 7 steps (a log of one slot; evictions after every or
+    every other step; applications that fall between evictions) and a budget that is never
+    reached (the log is only ever applied because it is full, and once at the end): the state
+    must equal, bit for bit, that of an engine whose every call is tracked at once (p_out); a
+    lazyev_stats call in the middle of a window must not change that either."""
+    from lockstep import make_engine
+    from paper_2506_15969_amd.workload import Workload
+    cfg = CONFIGS["cfg2"].scaled(n_layers=2, batch=2, prompt_len=100, steps=steps, budget=budget, window=window)
+    wl = Workload(cfg)
+    runs = []
+    for immediate, stats_at in ((True, 0), (False, 0), (False, 17)):
+        eng = make_engine(lazyev_lib, cfg, wl, variant=6 if not immediate else 4, target_blocks=16)
+        out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim), dtype=cfg.torch_dtype, device="cuda")
+        p_out = torch.zeros((cfg.batch, cfg.n_q_heads, cfg.capacity), dtype=torch.float32, device="cuda")
+        ins = [wl.step_inputs(l, 1, cfg.steps + 1, device="cuda") for l in range(cfg.n_layers)]
+        outs, n_ev = [], 0
+        for t in range(1, cfg.steps + 1):
+            for l in range(cfg.n_layers):
+                q, kn, vn = ins[l]
+                eng.decode_step(l, t, q[t - 1], kn[t - 1], vn[t - 1], out,
+                                p_out=p_out if immediate else None)
+                outs.append(out.clone())
+                if t == stats_at and l == 0:
+                    eng.stats()
+            n_ev += eng.evict_all(t)
+        st = eng.stats()
+        runs.append((torch.stack(outs), eng.k_cache.clone(), eng.v_cache.clone(), eng.ts.clone(),
+                     eng.mri.clone(), eng.pos.clone(), st, n_ev))
+        eng.close()
+    a = runs[0]
+    for b in runs[1:]:
+        assert a[7] == b[7]
+        for x, y in zip(a[:6], b[:6]):
+            assert torch.equal(x, y)
+        assert a[6] == b[6] and sum(a[6]["n_activations"]) > 0
+    assert (a[7] > 0) == (budget < 100 + steps)
+
+
 def test_long_runs_per_wave(lazyev_lib):
     """One block per unit over a cache of 1400..1532 entries: every wave owns 22-24 sub-tiles,
     more than it keeps logits for in LDS, so the logits go out in two instalments."""
