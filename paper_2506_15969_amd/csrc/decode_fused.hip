@@ -1347,7 +1347,8 @@ hipError_t launch_decode_fused(const DecodeArgs &a, hipStream_t stream, hipEvent
   const dim3 grid(n_blocks), b4(kBlock), b8(2 * kBlock);
 #define LAZYEV_LAUNCH(instance, block) \
   hipLaunchKernelGGL(instance, grid, block, lds_all, stream, kc, vc, kn, vn, a.n_old, a.n_split, a.capacity, units, slots_on, a)
-  if (a.variant == 6 && long_run && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, true, true>), b8);
+  if (a.variant == 6 && long_run && list_waves && a.n_split == 2) LAZYEV_LAUNCH((decode_fused_kernel<true, true, true, 2>), b8);
+  else if (a.variant == 6 && long_run && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, true, true>), b8);
   else if (a.variant == 6 && long_run) LAZYEV_LAUNCH((decode_fused_kernel<true, true, false>), b4);
   else if (a.variant == 6 && list_waves && a.n_split == 2) LAZYEV_LAUNCH((decode_fused_kernel<true, false, true, 2>), b8);
   else if (a.variant == 6 && list_waves) LAZYEV_LAUNCH((decode_fused_kernel<true, false, true>), b8);

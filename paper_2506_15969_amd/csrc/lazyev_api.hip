@@ -497,17 +497,15 @@ int lazyev_decode_step(lazyev_ctx *ctx, int32_t layer, int32_t t, const void *q,
     const int n_sub = (n_old + 1 + 15) / 16;
     int n_split = (ctx->target_blocks + ctx->units / 2) / ctx->units;
     if (!ctx->target_blocks_set) {
-      // about 16 sub-tiles per wave (measured: fewer, longer-running waves finish a short cache
-      // sooner), but no fewer blocks than compute units and no more than two per compute unit
-      const int lo = (256 + ctx->units - 1) / ctx->units;
-      const int by_run = (n_sub + 32) / 64;
-      if (by_run < n_split) n_split = by_run;
-      if (n_split < lo) n_split = lo;
-      // a long cache (a wave's run exceeds the 20 sub-tiles whose logits it keeps in LDS and
-      // leaves its candidate lists segment by segment): one block per compute unit streams
-      // fastest (measured at 8192 / 16384 / 32768 entries, 256 against 512 blocks: 93 / 165 /
-      // 329 us against 95 / 171 / 345)
-      if (lazyev::decode_fused_wave_run(n_sub, n_split) > lazyev::decode_fused_run_max()) n_split = lo;
+      // one block per compute unit, whatever the cache length: measured at 128 units over caches
+      // of 1088 .. 6144 entries against 1.5 and 2 blocks per compute unit (2448 / 3248 / 4144 /
+      // 5048 entries: 28.3 / 36.5 / 44.5 / 55.9 us per call against 30.2 / 37.4 / 46.4 / 57.0 with
+      // two per compute unit; three blocks per two compute units are worst, 39.3 at 3248).  A
+      // second stream block on a compute unit doubles the bytes its waves keep in flight, which
+      // this memory system answers with a wider spread of the blocks' ends, not with more
+      // bandwidth; a wave whose run then exceeds the sub-tiles it keeps logits of in LDS leaves
+      // its candidate lists segment by segment.
+      n_split = (256 + ctx->units - 1) / ctx->units;
     }
     if (n_split > (n_sub + 3) / 4) n_split = (n_sub + 3) / 4;
     if (n_split > lazyev::decode_fused_split_max()) n_split = lazyev::decode_fused_split_max();
