@@ -45,7 +45,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # only when the timed steps of this run have the same mean cache length.
 PROFILED_TRAFFIC = {"cfg3": (2080.5, 2 * 68000 * 1024 + 2325 * 1024),      # 136.9 MB algorithmic
                     "cfg4": (1088.5, 2 * 36080 * 1024 + 1987 * 1024),      # 71.9 MB
-                    "cfg5": (4128.5, 2 * 135100 * 1024 + 5082 * 1024)}     # 271.0 MB
+                    "cfg5": (4128.5, 2 * 134300 * 1024 + 3988 * 1024)}     # 271.0 MB
 
 
 def algorithmic_bytes_decode(cfg, n1: int) -> int:
